@@ -1,0 +1,205 @@
+/*
+ * libdgs -- the data-parallel hot path of DGS (dual-way gradient sparsification
+ * with sparsification-aware momentum, arXiv 1910.10929) on one AMD MI355X.
+ *
+ * C ABI.  No allocation of device memory happens inside the library: the caller
+ * owns every device buffer, including the workspace.  Unless marked "host", a
+ * pointer argument is a DEVICE pointer.  Every call enqueues its work on the
+ * context's HIP stream and returns without waiting for the GPU (exceptions are
+ * stated per call).  Return value: 0 on success, a negative DGS_E* code
+ * otherwise; nothing is thrown across the boundary.
+ *
+ * Notation: J tensors packed back to back in one flat fp32 buffer of n elements,
+ * tensor j occupying [offsets[j], offsets[j+1]); n_j its size;
+ * k_j = ceil(density * n_j) evaluated in IEEE double; K = sum_j k_j;
+ * key(x) = bits(x) & 0x7FFFFFFF, the magnitude of an fp32 as a 31-bit integer.
+ *
+ * Selection rule used by the worker step and the pull ("thr <- R% of |x|" in
+ * Algorithms 1-3, with density = 1 - R/100): per tensor, exactly the k_j entries
+ * with the largest key; equal keys are resolved towards the lower index.  The
+ * result is therefore unique, and identical on every code path of the library.
+ */
+#ifndef DGS_H
+#define DGS_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dgs_ctx dgs_ctx; /* opaque; host-side plan + views into the workspace */
+
+enum {
+    DGS_OK = 0,
+    DGS_EINVAL = -1,    /* bad argument (NULL, misaligned, out of range) */
+    DGS_ENOMEM = -2,    /* workspace too small / host allocation failed */
+    DGS_ENOTSUP = -3,   /* valid request the library does not implement */
+    DGS_ECAPACITY = -4, /* output capacity exceeded */
+    DGS_EHIP = -5       /* a HIP runtime call failed */
+};
+
+/* Options for dgs_set_option(). */
+enum {
+    DGS_OPT_FORCE_EXACT = 1, /* 1: never use the previous step's threshold as a prediction */
+    DGS_OPT_PROFILE = 2,     /* 1: bracket the kernels of each call with HIP events */
+    DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
+    DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */
+    DGS_OPT_STREAM_QUADS = 5 /* 4096-element groups per workgroup of the streaming kernel */
+};
+
+/* Kernel classes reported by dgs_profile_read(). */
+enum {
+    DGS_PROF_WORKER_STREAM = 0, /* accumulate + candidate pass over grad/state */
+    DGS_PROF_WORKER_SELECT = 1,
+    DGS_PROF_PULL_STREAM = 2,   /* candidate pass over one difference row */
+    DGS_PROF_PULL_SELECT = 3,
+    DGS_PROF_PUSH = 4,
+    DGS_PROF_EXACT_EXTRA = 5,   /* histogram pick + second pass of the non-predicted path */
+    DGS_PROF_KINDS = 6
+};
+
+typedef struct dgs_stats {
+    uint64_t calls_worker, calls_pull, calls_push;
+    uint64_t exact_calls;      /* calls that ran the two-pass (non-predicted) path */
+    uint64_t fallback_tensors; /* tensors whose prediction failed and were re-selected densely */
+    uint64_t fallback_elems;   /* elements re-read by those */
+    uint64_t candidates;       /* candidates collected by streaming passes */
+    uint64_t internal_errors;  /* must stay 0 */
+} dgs_stats;
+
+/*
+ * Bytes of device workspace needed for this layout and W server-side workers
+ * (W may be 0 for a worker-only context).  Pure host computation.
+ * offsets: host, J+1 entries, elements, offsets[0] == 0, strictly increasing
+ * (every tensor has at least one element), offsets[J] = n < 2^32.
+ * Returns 0 on invalid arguments.
+ */
+size_t dgs_workspace_bytes(const uint64_t *offsets, uint32_t J, uint32_t W);
+
+/*
+ * Build a context.  `workspace` is device memory of at least
+ * dgs_workspace_bytes() bytes, 256-byte aligned, owned by the caller and left
+ * untouched by the caller until dgs_destroy().  `hip_stream` is a hipStream_t
+ * (NULL = the default stream).  Uploads the launch plan and clears the
+ * workspace's counters on that stream, then waits for that to finish.
+ */
+int dgs_create(dgs_ctx **out, const uint64_t *offsets /*host*/, uint32_t J, uint32_t W,
+               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Waits for the stream, then releases host resources.  Frees no device memory. */
+int dgs_destroy(dgs_ctx *ctx);
+
+/* K = sum_j ceil(density * n_j).  Pure host. density must be in (0, 1]. */
+int dgs_nnz(const dgs_ctx *ctx, double density, uint64_t *K_out /*host*/);
+
+/*
+ * One worker iteration after the backward pass: Algorithm 3 (accumulate with
+ * momentum, per-tensor threshold, mask, send, rescale the unsent part; Eq. 11-12),
+ * or Algorithm 1 (residual accumulation) -- everything between "Backward" and
+ * "Send encode(g)".
+ *
+ *   grad      n floats, read only: the stochastic gradient.
+ *   momentum  n floats, in/out, or NULL.
+ *   residual  n floats, in/out, or NULL.  Exactly one of the two must be given.
+ *   lr        learning rate eta.
+ *   m         momentum coefficient in [0, 1); must be 0 when `residual` is used.
+ *   density   fraction kept per tensor, in (0, 1].
+ *   idx_out   K x u32: flat indices of the sent entries, ascending; tensor j's
+ *             k_j entries start at sum_{i<j} k_i.
+ *   val_out   K x f32: the sent values.
+ *   nnz_out   host, optional: receives K immediately (it is static).
+ *
+ * Arithmetic, per element i:  a_i = fmaf(lr, grad_i, state_i)   (one rounding,
+ * denormals kept);  sent entries: val = a_i, state_i = m * a_i;  unsent entries:
+ * state_i = a_i.
+ *
+ * State convention.  With `momentum`, the buffer holds s = m * u where u is the
+ * paper's velocity: Algorithm 3 keeps u = a for sent entries and rescales unsent
+ * ones to u = a / m, and its next accumulate multiplies by m again (the
+ * cancellation Eq. 13 relies on); storing s removes the division, keeps
+ * "sent + kept == accumulated" exact, and makes m = 0 legal.  Read the paper's
+ * velocity as u = s / m.  With `residual` (m = 0) the buffer is Algorithm 1's v:
+ * sent entries become 0, unsent ones keep the accumulated value.
+ * Both buffers given (separate momentum and residual, as in momentum-corrected
+ * schemes) is not part of this method: DGS_ENOTSUP.
+ *
+ * Buffers must be 4-byte aligned; 16-byte alignment gives the fast path.
+ */
+int dgs_worker_step(dgs_ctx *ctx, const float *grad, float *momentum, float *residual,
+                    float lr, float m, double density,
+                    uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/);
+
+/*
+ * Give the server side its per-worker difference buffers: W rows of n floats,
+ * row-major, row w = D_w = M - v_w in the notation of Eq. 1-6 (the part of the
+ * accumulated update M that worker w has not been sent yet).  The caller
+ * allocates and zero-initialises it (M_0 = 0, v_w = 0) and keeps it alive.
+ */
+int dgs_server_attach(dgs_ctx *ctx, float *diff);
+
+/*
+ * The server receives one decoded update g from `worker_id` (Algorithm 2,
+ * "M <- M - decode(g)"; Eq. 1):  model[idx] -= val, and D_w[idx] -= val for every
+ * worker w (Eq. 3: the difference owed to every worker, the sender included,
+ * moves with M).  g already carries the learning rate.
+ *   model  n floats in/out (theta_0 + M), or NULL to keep only the differences.
+ *   idx    nnz x u32, strictly ascending (hence unique: the scatter needs no atomics);
+ *   val    nnz x f32.
+ * With DGS_OPT_VALIDATE the order/range precondition is checked on the device
+ * (this synchronises) and DGS_EINVAL is returned on violation, before anything is
+ * modified.
+ */
+int dgs_server_push(dgs_ctx *ctx, float *model, uint32_t worker_id,
+                    const uint32_t *idx, const float *val, uint64_t nnz);
+
+/*
+ * The server answers `worker_id` with secondary compression (Algorithm 2, the
+ * per-tensor threshold loop on G; Eq. 6): G = the k_j largest-magnitude entries
+ * per tensor of D_k; afterwards those entries of D_k are +0 (v_k += G), the rest
+ * stays accumulated on the server.  Outputs as in dgs_worker_step.  If a tensor
+ * of D_k has fewer than k_j nonzeros, zero-valued entries at its lowest indices
+ * complete the message (exactly K pairs are always produced).
+ */
+int dgs_server_pull(dgs_ctx *ctx, uint32_t worker_id, double density,
+                    uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/);
+
+/*
+ * The server answers `worker_id` without secondary compression (Algorithm 2 with
+ * the switch off; Eq. 3-4): G = every entry of D_k with a nonzero magnitude,
+ * ascending; afterwards D_k == 0.  nnz is data dependent: the call waits for
+ * the stream and writes the count to nnz_out (host).  If the count exceeds
+ * `capacity`, nothing is modified, nnz_out still receives the count and
+ * DGS_ECAPACITY is returned.
+ */
+int dgs_server_pull_all(dgs_ctx *ctx, uint32_t worker_id, uint32_t *idx_out, float *val_out,
+                        uint64_t capacity, uint64_t *nnz_out /*host*/);
+
+/*
+ * Worker applies a decoded message (Algorithm 1/3, "theta <- SGD(theta,
+ * decode(G))"; Eq. 5 with sign = +1):  dst[idx] = fmaf(sign, val, dst[idx]).
+ * idx must be unique.
+ */
+int dgs_apply_sparse(dgs_ctx *ctx, float *dst, const uint32_t *idx, const float *val,
+                     uint64_t nnz, float sign);
+
+int dgs_set_option(dgs_ctx *ctx, int option, int64_t value);
+
+/* Waits for the stream, then copies the counters to `out` (host). */
+int dgs_get_stats(dgs_ctx *ctx, dgs_stats *out /*host*/);
+
+/*
+ * With DGS_OPT_PROFILE on: waits for the stream, then reports, for kernel class
+ * `kind`, how many launches were bracketed since the last read and their summed
+ * duration in milliseconds (HIP events on the context's stream); resets that
+ * class.  At most 4096 launches per class are kept between reads.
+ */
+int dgs_profile_read(dgs_ctx *ctx, int kind, uint64_t *launches /*host*/, double *total_ms /*host*/);
+
+const char *dgs_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DGS_H */

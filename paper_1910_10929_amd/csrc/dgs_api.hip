@@ -1,0 +1,587 @@
+// Host side of libdgs: argument checks, the launch plan, workspace carve-up and
+// kernel sequencing.  All arithmetic of the method runs in the kernels.
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/dgs.h"
+#include "dgs_device.h"
+
+using namespace dgs;
+
+namespace {
+
+constexpr uint32_t NPLAN = 8;          // densities cached per context
+constexpr size_t ALIGN = 256;
+constexpr uint32_t MAX_PROF = 4096;
+
+size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
+
+struct Layout {          // byte offsets inside the workspace
+    size_t tile_desc, tdesc, plans, tau, ghist, tile_cnt, slots, ord, stats, flag, total;
+};
+
+bool check_offsets(const uint64_t *offsets, uint32_t J)
+{
+    if (!offsets || J == 0) return false;
+    if (offsets[0] != 0) return false;
+    for (uint32_t j = 0; j < J; ++j)
+        if (offsets[j + 1] <= offsets[j]) return false;
+    if (offsets[J] >= (1ull << 32)) return false;
+    return true;
+}
+
+Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
+{
+    const size_t ntiles = (size_t)((n + TILE - 1) / TILE);
+    Layout L;
+    size_t o = 0;
+    L.tile_desc = o; o = align_up(o + ntiles * sizeof(uint2));
+    L.tdesc = o;     o = align_up(o + (size_t)J * sizeof(TensorDesc));
+    L.plans = o;     o = align_up(o + (size_t)NPLAN * J * sizeof(PlanEntry));
+    L.tau = o;       o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
+    L.ghist = o;     o = align_up(o + (size_t)J * HBINS * sizeof(uint32_t));
+    L.tile_cnt = o;  o = align_up(o + (ntiles + 4) * sizeof(uint32_t));
+    L.slots = o;     o = align_up(o + ntiles * CAPT * sizeof(uint2));
+    L.ord = o;       o = align_up(o + (ntiles + J) * CAPT * sizeof(uint2));
+    L.stats = o;     o = align_up(o + sizeof(DevStats));
+    L.flag = o;      o = align_up(o + 64);
+    L.total = o;
+    return L;
+}
+
+struct PlanSlot {
+    bool valid = false;
+    double density = 0.0;
+    int margin = 0;
+    uint64_t K = 0;
+    uint64_t last_use = 0;
+};
+
+struct ProfClass {
+    std::vector<hipEvent_t> start, stop;
+    uint32_t used = 0;
+};
+
+uint32_t isqrt_u32(uint32_t x) { return (uint32_t)std::floor(std::sqrt((double)x)); }
+
+}  // namespace
+
+struct dgs_ctx {
+    hipStream_t stream = nullptr;
+    uint32_t J = 0, W = 0, n = 0, ntiles = 0, nquads = 0;
+    int cus = 256;
+    std::vector<uint64_t> offsets;
+    char *ws = nullptr;
+    Layout L{};
+    // device views
+    uint2 *tile_desc = nullptr;
+    TensorDesc *tdesc = nullptr;
+    PlanEntry *plans = nullptr;
+    uint32_t *tau = nullptr;
+    uint32_t *ghist = nullptr;
+    uint32_t *tile_cnt = nullptr;
+    uint2 *slots = nullptr;
+    uint2 *ord = nullptr;
+    DevStats *stats = nullptr;
+    uint32_t *flag = nullptr;
+    float *diff = nullptr;
+    // plan cache
+    PlanSlot plan_slot[NPLAN];
+    PlanEntry *plan_stage = nullptr;   // pinned host, NPLAN * J
+    uint64_t tick = 0;
+    // which density each hint set was produced for (0 = none yet)
+    std::vector<double> hint_density;  // W + 1 entries; entry 0 = worker
+    // options
+    bool force_exact = false, profile = false, validate = false;
+    int margin_pct = 50;
+    uint32_t stream_quads = 0;         // 0 = automatic
+    // host counters
+    uint64_t calls_worker = 0, calls_pull = 0, calls_push = 0, exact_calls = 0;
+    ProfClass prof[DGS_PROF_KINDS];
+};
+
+namespace {
+
+struct ProfScope {     // brackets launches with events when profiling is on
+    dgs_ctx *c;
+    int kind;
+    bool on = false;
+    uint32_t slot = 0;
+    ProfScope(dgs_ctx *ctx, int k) : c(ctx), kind(k)
+    {
+        if (!c->profile) return;
+        ProfClass &p = c->prof[kind];
+        if (p.used >= MAX_PROF) return;
+        if (p.used >= p.start.size()) {
+            hipEvent_t a, b;
+            if (hipEventCreate(&a) != hipSuccess) return;
+            if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+            p.start.push_back(a);
+            p.stop.push_back(b);
+        }
+        slot = p.used;
+        on = (hipEventRecord(p.start[slot], c->stream) == hipSuccess);
+    }
+    ~ProfScope()
+    {
+        if (!on) return;
+        ProfClass &p = c->prof[kind];
+        if (hipEventRecord(p.stop[slot], c->stream) == hipSuccess) p.used = slot + 1;
+    }
+};
+
+// k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
+void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out)
+{
+    uint64_t K = 0;
+    for (uint32_t j = 0; j < c->J; ++j) {
+        const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
+        uint64_t k = (uint64_t)std::ceil(density * (double)nj);
+        if (k < 1) k = 1;
+        if (k > nj) k = nj;
+        uint64_t k2 = k + (k * (uint64_t)margin_pct) / 100 + 4ull * isqrt_u32((uint32_t)k) + 16;
+        if (k2 > nj) k2 = nj;
+        out[j].k = (uint32_t)k;
+        out[j].k2 = (uint32_t)k2;
+        out[j].outoff = (uint32_t)K;
+        out[j].pad = 0;
+        K += k;
+    }
+    *K_out = K;
+}
+
+// Returns the cache slot holding the plan for `density`, uploading it if new.
+int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
+{
+    ++c->tick;
+    for (uint32_t s = 0; s < NPLAN; ++s) {
+        PlanSlot &p = c->plan_slot[s];
+        if (p.valid && p.density == density && p.margin == c->margin_pct) {
+            p.last_use = c->tick;
+            *slot_out = s;
+            *K_out = p.K;
+            return DGS_OK;
+        }
+    }
+    uint32_t victim = 0;
+    bool reuse = true;
+    for (uint32_t s = 0; s < NPLAN; ++s) {
+        if (!c->plan_slot[s].valid) { victim = s; reuse = false; break; }
+        if (c->plan_slot[s].last_use < c->plan_slot[victim].last_use) victim = s;
+    }
+    if (reuse) {
+        // the staging area of this slot may still feed an earlier upload
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    }
+    PlanEntry *stage = c->plan_stage + (size_t)victim * c->J;
+    uint64_t K = 0;
+    fill_plan(c, density, c->margin_pct, stage, &K);
+    if (K >= (1ull << 32)) return DGS_EINVAL;
+    if (hipMemcpyAsync(c->plans + (size_t)victim * c->J, stage, (size_t)c->J * sizeof(PlanEntry),
+                       hipMemcpyHostToDevice, c->stream) != hipSuccess)
+        return DGS_EHIP;
+    PlanSlot &p = c->plan_slot[victim];
+    p.valid = true;
+    p.density = density;
+    p.margin = c->margin_pct;
+    p.K = K;
+    p.last_use = c->tick;
+    *slot_out = victim;
+    *K_out = K;
+    return DGS_OK;
+}
+
+bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+bool aligned4(const void *p) { return ((uintptr_t)p & 3u) == 0; }
+
+uint32_t stream_blocks(const dgs_ctx *c, int mode, uint32_t *qpb_out)
+{
+    uint32_t qpb;
+    if (mode == MODE_HIST) {
+        // long contiguous spans per workgroup keep the number of histogram flushes small
+        const uint32_t target = (uint32_t)c->cus * 8u;
+        qpb = (c->nquads + target - 1) / target;
+    } else {
+        qpb = c->stream_quads ? c->stream_quads : 2u;
+    }
+    if (qpb == 0) qpb = 1;
+    *qpb_out = qpb;
+    return (c->nquads + qpb - 1) / qpb;
+}
+
+// The selection pipeline shared by the worker step and the pull.
+//   op_stream: OP_FMA (worker: grad + state) or OP_IDENT (pull: a difference row)
+int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, float *state, float lr,
+                  float m, double density, uint32_t hint_set, uint32_t *idx_out, float *val_out,
+                  uint64_t *nnz_out, int prof_stream, int prof_select)
+{
+    uint32_t slot;
+    uint64_t K;
+    int rc = get_plan(c, density, &slot, &K);
+    if (rc != DGS_OK) return rc;
+    if (nnz_out) *nnz_out = K;
+
+    const bool vec = aligned16(state) && (op_stream == OP_IDENT || aligned16(grad));
+    const bool dense_req = density > DENSE_DENSITY;
+    const bool exact = !dense_req && (c->force_exact || c->hint_density[hint_set] != density);
+    uint32_t *tau = c->tau + (size_t)hint_set * c->J;
+    const PlanEntry *plan = c->plans + (size_t)slot * c->J;
+
+    StreamArgs sa{};
+    sa.grad = grad;
+    sa.state = state;
+    sa.tile_desc = c->tile_desc;
+    sa.tdesc = c->tdesc;
+    sa.tau = tau;
+    sa.tile_cnt = c->tile_cnt;
+    sa.slots = c->slots;
+    sa.ghist = c->ghist;
+    sa.n = c->n;
+    sa.ntiles = c->ntiles;
+    sa.nquads = c->nquads;
+    sa.lr = lr;
+
+    if (dense_req) {
+        if (op_stream == OP_FMA) {
+            ProfScope ps(c, prof_stream);
+            const uint32_t blocks = stream_blocks(c, MODE_PLAIN, &sa.quads_per_block);
+            launch_stream(OP_FMA, MODE_PLAIN, vec, sa, blocks, c->stream);
+        }
+    } else if (exact) {
+        ++c->exact_calls;
+        {
+            ProfScope ps(c, prof_stream);
+            const uint32_t blocks = stream_blocks(c, MODE_HIST, &sa.quads_per_block);
+            launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream);
+        }
+        {
+            ProfScope ps(c, DGS_PROF_EXACT_EXTRA);
+            launch_pick(c->tdesc, plan, c->ghist, tau, c->stats, c->J, c->stream);
+            StreamArgs sb = sa;
+            sb.grad = nullptr;
+            const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sb.quads_per_block);
+            launch_stream(OP_IDENT, MODE_COLLECT, aligned16(state), sb, blocks, c->stream);
+        }
+    } else {
+        ProfScope ps(c, prof_stream);
+        const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sa.quads_per_block);
+        launch_stream(op_stream, MODE_COLLECT, vec, sa, blocks, c->stream);
+    }
+
+    SelectArgs se{};
+    se.state = state;
+    se.tdesc = c->tdesc;
+    se.plan = plan;
+    se.tau = tau;
+    se.tile_cnt = c->tile_cnt;
+    se.slots = c->slots;
+    se.ord = c->ord;
+    se.out_idx = idx_out;
+    se.out_val = val_out;
+    se.stats = c->stats;
+    se.m = m;
+    se.force_dense = dense_req ? 1u : 0u;
+    se.write_hint = dense_req ? 0u : 1u;
+    {
+        ProfScope ps(c, prof_select);
+        launch_select(op_select, se, c->J, c->stream);
+    }
+    if (!dense_req) c->hint_density[hint_set] = density;
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t dgs_workspace_bytes(const uint64_t *offsets, uint32_t J, uint32_t W)
+{
+    if (!check_offsets(offsets, J)) return 0;
+    return make_layout(offsets[J], J, W).total;
+}
+
+int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, void *workspace,
+               size_t workspace_bytes, void *hip_stream)
+{
+    if (!out) return DGS_EINVAL;
+    *out = nullptr;
+    if (!check_offsets(offsets, J) || !workspace) return DGS_EINVAL;
+    if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return DGS_EINVAL;
+    const Layout L = make_layout(offsets[J], J, W);
+    if (workspace_bytes < L.total) return DGS_ENOMEM;
+
+    dgs_ctx *c = new (std::nothrow) dgs_ctx();
+    if (!c) return DGS_ENOMEM;
+    c->stream = (hipStream_t)hip_stream;
+    c->J = J;
+    c->W = W;
+    c->n = (uint32_t)offsets[J];
+    c->ntiles = (c->n + TILE - 1) / TILE;
+    c->nquads = (c->ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    c->offsets.assign(offsets, offsets + J + 1);
+    c->ws = (char *)workspace;
+    c->L = L;
+    c->tile_desc = (uint2 *)(c->ws + L.tile_desc);
+    c->tdesc = (TensorDesc *)(c->ws + L.tdesc);
+    c->plans = (PlanEntry *)(c->ws + L.plans);
+    c->tau = (uint32_t *)(c->ws + L.tau);
+    c->ghist = (uint32_t *)(c->ws + L.ghist);
+    c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
+    c->slots = (uint2 *)(c->ws + L.slots);
+    c->ord = (uint2 *)(c->ws + L.ord);
+    c->stats = (DevStats *)(c->ws + L.stats);
+    c->flag = (uint32_t *)(c->ws + L.flag);
+    c->hint_density.assign((size_t)W + 1, 0.0);
+
+    int dev = 0;
+    hipDeviceProp_t prop;
+    if (hipGetDevice(&dev) == hipSuccess && hipGetDeviceProperties(&prop, dev) == hipSuccess &&
+        prop.multiProcessorCount > 0)
+        c->cus = prop.multiProcessorCount;
+    const char *env = std::getenv("DGS_FORCE_EXACT");
+    if (env && env[0] == '1') c->force_exact = true;
+    env = std::getenv("DGS_STREAM_QUADS");
+    if (env) c->stream_quads = (uint32_t)std::strtoul(env, nullptr, 10);
+
+    // host-side plan: tensor and tile descriptors
+    std::vector<TensorDesc> td(J);
+    std::vector<uint32_t> tau0((size_t)(W + 1) * J);
+    for (uint32_t j = 0; j < J; ++j) {
+        td[j].off = (uint32_t)offsets[j];
+        td[j].n = (uint32_t)(offsets[j + 1] - offsets[j]);
+        td[j].big = td[j].n > SMALL_N ? 1u : 0u;
+        td[j].pad = 0;
+        for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
+    }
+    std::vector<uint2> tiles(c->ntiles);
+    {
+        uint32_t j = 0;
+        for (uint32_t t = 0; t < c->ntiles; ++t) {
+            const uint64_t first = (uint64_t)t * TILE;
+            uint64_t last = first + TILE - 1;
+            if (last >= c->n) last = c->n - 1;
+            while (offsets[j + 1] <= first) ++j;
+            uint32_t jb = j;
+            while (offsets[jb + 1] <= last) ++jb;
+            tiles[t] = make_uint2(j, jb);
+        }
+    }
+
+    bool ok = true;
+    ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->tile_desc, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->tdesc, td.data(), td.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->tau, tau0.data(), tau0.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    if (ok) {
+        launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
+        launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
+        launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);
+        launch_fill_u32(c->flag, 0u, 16, c->stream);
+    }
+    ok = ok && hipStreamSynchronize(c->stream) == hipSuccess;
+    ok = ok && hipGetLastError() == hipSuccess;
+    if (!ok) {
+        if (c->plan_stage) (void)hipHostFree(c->plan_stage);
+        delete c;
+        return DGS_EHIP;
+    }
+    *out = c;
+    return DGS_OK;
+}
+
+int dgs_destroy(dgs_ctx *c)
+{
+    if (!c) return DGS_EINVAL;
+    (void)hipStreamSynchronize(c->stream);
+    for (auto &p : c->prof) {
+        for (auto e : p.start) (void)hipEventDestroy(e);
+        for (auto e : p.stop) (void)hipEventDestroy(e);
+    }
+    if (c->plan_stage) (void)hipHostFree(c->plan_stage);
+    delete c;
+    return DGS_OK;
+}
+
+int dgs_nnz(const dgs_ctx *c, double density, uint64_t *K_out)
+{
+    if (!c || !K_out) return DGS_EINVAL;
+    if (!(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    uint64_t K = 0;
+    for (uint32_t j = 0; j < c->J; ++j) {
+        const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
+        uint64_t k = (uint64_t)std::ceil(density * (double)nj);
+        if (k < 1) k = 1;
+        if (k > nj) k = nj;
+        K += k;
+    }
+    *K_out = K;
+    return DGS_OK;
+}
+
+int dgs_worker_step(dgs_ctx *c, const float *grad, float *momentum, float *residual, float lr, float m,
+                    double density, uint32_t *idx_out, float *val_out, uint64_t *nnz_out)
+{
+    if (!c || !grad || !idx_out || !val_out) return DGS_EINVAL;
+    if (!momentum && !residual) return DGS_EINVAL;
+    if (momentum && residual) return DGS_ENOTSUP;
+    if (!(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!(m >= 0.0f) || !(m < 1.0f)) return DGS_EINVAL;
+    if (residual && m != 0.0f) return DGS_EINVAL;
+    if (!std::isfinite(lr)) return DGS_EINVAL;
+    float *state = momentum ? momentum : residual;
+    if (!aligned4(grad) || !aligned4(state) || !aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
+    ++c->calls_worker;
+    return run_selection(c, OP_FMA, SEL_WORKER, grad, state, lr, m, density, 0, idx_out, val_out, nnz_out,
+                         DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT);
+}
+
+int dgs_server_attach(dgs_ctx *c, float *diff)
+{
+    if (!c || !diff || c->W == 0) return DGS_EINVAL;
+    if (!aligned4(diff)) return DGS_EINVAL;
+    c->diff = diff;
+    return DGS_OK;
+}
+
+int dgs_server_push(dgs_ctx *c, float *model, uint32_t worker_id, const uint32_t *idx, const float *val,
+                    uint64_t nnz)
+{
+    if (!c || !c->diff) return DGS_EINVAL;
+    if (worker_id >= c->W) return DGS_EINVAL;
+    if (nnz > c->n) return DGS_EINVAL;
+    if (nnz && (!idx || !val)) return DGS_EINVAL;
+    if (model && !aligned4(model)) return DGS_EINVAL;
+    if (c->validate && nnz) {
+        launch_fill_u32(c->flag, 0u, 1, c->stream);
+        launch_validate_idx(idx, (uint32_t)nnz, c->n, c->flag, c->stream);
+        uint32_t bad = 0;
+        if (hipMemcpyAsync(&bad, c->flag, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+        if (bad) return DGS_EINVAL;
+    }
+    ++c->calls_push;
+    {
+        ProfScope ps(c, DGS_PROF_PUSH);
+        launch_push(model, c->diff, c->W, c->n, idx, val, (uint32_t)nnz, c->stream);
+    }
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+int dgs_server_pull(dgs_ctx *c, uint32_t worker_id, double density, uint32_t *idx_out, float *val_out,
+                    uint64_t *nnz_out)
+{
+    if (!c || !c->diff || !idx_out || !val_out) return DGS_EINVAL;
+    if (worker_id >= c->W) return DGS_EINVAL;
+    if (!(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
+    float *row = c->diff + (size_t)worker_id * c->n;
+    ++c->calls_pull;
+    return run_selection(c, OP_IDENT, SEL_PULL, nullptr, row, 0.0f, 0.0f, density, 1 + worker_id, idx_out,
+                         val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT);
+}
+
+int dgs_server_pull_all(dgs_ctx *c, uint32_t worker_id, uint32_t *idx_out, float *val_out,
+                        uint64_t capacity, uint64_t *nnz_out)
+{
+    if (!c || !c->diff || !nnz_out) return DGS_EINVAL;
+    if (worker_id >= c->W) return DGS_EINVAL;
+    if (capacity && (!idx_out || !val_out)) return DGS_EINVAL;
+    float *row = c->diff + (size_t)worker_id * c->n;
+    uint32_t *total = c->flag + 4;
+    launch_pull_all_count(row, c->n, c->ntiles, c->tile_cnt, c->stream);
+    launch_pull_all_scan(c->tile_cnt, c->ntiles, total, c->stream);
+    uint32_t cnt = 0;
+    if (hipMemcpyAsync(&cnt, total, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    *nnz_out = cnt;
+    if (cnt > capacity) return DGS_ECAPACITY;
+    if (cnt) launch_pull_all_emit(row, c->n, c->ntiles, c->tile_cnt, idx_out, val_out, c->stream);
+    ++c->calls_pull;
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+int dgs_apply_sparse(dgs_ctx *c, float *dst, const uint32_t *idx, const float *val, uint64_t nnz, float sign)
+{
+    if (!c || !dst) return DGS_EINVAL;
+    if (nnz > c->n) return DGS_EINVAL;
+    if (nnz && (!idx || !val)) return DGS_EINVAL;
+    launch_apply(dst, idx, val, (uint32_t)nnz, sign, c->stream);
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+int dgs_set_option(dgs_ctx *c, int option, int64_t value)
+{
+    if (!c) return DGS_EINVAL;
+    switch (option) {
+    case DGS_OPT_FORCE_EXACT: c->force_exact = value != 0; return DGS_OK;
+    case DGS_OPT_PROFILE: c->profile = value != 0; return DGS_OK;
+    case DGS_OPT_VALIDATE: c->validate = value != 0; return DGS_OK;
+    case DGS_OPT_MARGIN_PCT:
+        if (value < 0 || value > 1000) return DGS_EINVAL;
+        c->margin_pct = (int)value;
+        return DGS_OK;
+    case DGS_OPT_STREAM_QUADS:
+        if (value < 0 || value > (1 << 20)) return DGS_EINVAL;
+        c->stream_quads = (uint32_t)value;
+        return DGS_OK;
+    default: return DGS_EINVAL;
+    }
+}
+
+int dgs_get_stats(dgs_ctx *c, dgs_stats *out)
+{
+    if (!c || !out) return DGS_EINVAL;
+    DevStats d;
+    if (hipMemcpyAsync(&d, c->stats, sizeof d, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    out->calls_worker = c->calls_worker;
+    out->calls_pull = c->calls_pull;
+    out->calls_push = c->calls_push;
+    out->exact_calls = c->exact_calls;
+    out->fallback_tensors = d.fallback_tensors;
+    out->fallback_elems = d.fallback_elems;
+    out->candidates = d.candidates;
+    out->internal_errors = d.internal_errors;
+    return DGS_OK;
+}
+
+int dgs_profile_read(dgs_ctx *c, int kind, uint64_t *launches, double *total_ms)
+{
+    if (!c || kind < 0 || kind >= DGS_PROF_KINDS || !launches || !total_ms) return DGS_EINVAL;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    ProfClass &p = c->prof[kind];
+    double sum = 0.0;
+    for (uint32_t i = 0; i < p.used; ++i) {
+        float ms = 0.0f;
+        if (hipEventElapsedTime(&ms, p.start[i], p.stop[i]) != hipSuccess) return DGS_EHIP;
+        sum += ms;
+    }
+    *launches = p.used;
+    *total_ms = sum;
+    p.used = 0;
+    return DGS_OK;
+}
+
+const char *dgs_strerror(int code)
+{
+    switch (code) {
+    case DGS_OK: return "ok";
+    case DGS_EINVAL: return "invalid argument";
+    case DGS_ENOMEM: return "workspace too small or host allocation failed";
+    case DGS_ENOTSUP: return "not supported";
+    case DGS_ECAPACITY: return "output capacity exceeded";
+    case DGS_EHIP: return "HIP runtime error";
+    default: return "unknown error";
+    }
+}
+
+}  // extern "C"

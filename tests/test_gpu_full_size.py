@@ -1,0 +1,174 @@
+"""GPU parity at the benchmark's full sizes, in the launch configuration
+bench.py times.  Where the oracle finishes in seconds the comparison is element
+by element; on the 1e9-parameter layout the oracle checks sampled tensors and
+the rest is checked through properties that hold at any size."""
+import numpy as np
+import pytest
+
+from paper_1910_10929_amd import dgs, synth
+from harness import Server, Worker, assert_pairs_match, assert_state_match, to_host_u32
+
+pytestmark = pytest.mark.gpu
+
+
+def key_of(x):
+    return np.ascontiguousarray(x).view(np.uint32) & np.uint32(0x7FFFFFFF)
+
+
+def test_c2_resnet50_shapes(oracle):
+    """Config 2: 161 tensors / 25,557,032 parameters, per-tensor log-uniform
+    scale, density 1e-3, m = 0.9; step + push + pull with one worker."""
+    off = synth.layout_resnet50()
+    n = int(off[-1])
+    scales = synth.tensor_scales(len(off) - 1, 2)
+    rng = np.random.default_rng(2)
+    pool = [synth.gaussian_grads(off, scales, rng) for _ in range(3)]
+    ctx = dgs.Context(off, W=1)
+    w = Worker(ctx, density_max=1e-3)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=1e-3)
+    s_ref = np.zeros(n, np.float32)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((1, n), np.float32)
+    for t in range(5):
+        g = pool[t % 3]
+        wi, wv = oracle.worker_step(g, s_ref, off, 1.0, np.float32(0.9), 1e-3)
+        gi, gv = w.step(g, 1.0, 0.9, 1e-3)
+        assert gi.size == 25_670
+        assert_pairs_match(gi, gv, wi, wv, f"worker step {t}")
+        oracle.server_push(model_ref, diff_ref, wi, wv)
+        ctx.server_push(srv.model, 0, w.idx, w.val, gi.size)
+        pi_ref, pv_ref = oracle.server_pull(diff_ref, 0, off, 1e-3)
+        pi, pv = srv.pull(0, 1e-3)
+        assert_pairs_match(pi, pv, pi_ref, pv_ref, f"pull {t}")
+    assert_state_match(w.state_host(), s_ref, "worker state")
+    assert_state_match(srv.model.cpu().numpy(), model_ref, "model")
+    assert_state_match(srv.diff.cpu().numpy()[0], diff_ref[0], "diff")
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    assert st.exact_calls == 2          # first step and first pull only
+    ctx.close()
+
+
+def test_c3_server_stress_32_workers(oracle):
+    """Config 3 (shortened event list): 25.6M-parameter model, 32 workers with
+    their own difference rows, pushes in a seeded interleaving, each followed by a
+    pull of that worker at density 1e-3."""
+    import torch
+    off = synth.layout_resnet50()
+    n = int(off[-1])
+    W = 32
+    scales = synth.tensor_scales(len(off) - 1, 3)
+    rng = np.random.default_rng(3)
+    kj, K = oracle.nnz(off, 1e-3)
+    payloads = [synth.sparse_payload(off, kj, scales, rng) for _ in range(6)]
+    ctx = dgs.Context(off, W=W)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=1e-3)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((W, n), np.float32)
+    order = synth.event_schedule(W, 14, 3)
+    order[7] = order[2]      # make sure at least one worker pulls twice
+    order[11] = order[2]
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = payloads[e % len(payloads)]
+        oracle.server_push(model_ref, diff_ref, idx, val)
+        srv.push(k, idx, val)
+        wi, wv = oracle.server_pull(diff_ref, k, off, 1e-3)
+        gi, gv = srv.pull(k, 1e-3)
+        assert_pairs_match(gi, gv, wi, wv, f"event {e} pull({k})")
+    assert_state_match(srv.model.cpu().numpy(), model_ref, "model")
+    for w_ in (int(order[2]), int(order[0]), 31):
+        assert_state_match(srv.diff[w_].cpu().numpy(), diff_ref[w_], f"diff row {w_}")
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
+    del srv
+    torch.cuda.empty_cache()
+
+
+def test_c4_transformer_shapes_heavy_tails(oracle):
+    """Config 4: 49 tensors / 108,375,552 parameters, Student-t (nu = 3)
+    gradients, a row-sparse embedding gradient (95 % exact zeros), density 1e-3,
+    two workers sharing one context."""
+    off = synth.layout_transformer()
+    n = int(off[-1])
+    J = len(off) - 1
+    scales = synth.tensor_scales(J, 4)
+    rng = np.random.default_rng(4)
+    g = synth.student_t_grads(off, scales, rng)
+    synth.zero_rows(g, int(off[J - 1]), 30522, 768, 0.05, rng)
+    g2 = (g[::-1] * np.float32(0.5)).copy()
+    synth.zero_rows(g2, int(off[J - 1]), 30522, 768, 0.05, rng)
+    ctx = dgs.Context(off, W=0)
+    w = Worker(ctx, density_max=1e-3)
+    s_ref = np.zeros(n, np.float32)
+    for t, gg in enumerate((g, g2, g)):
+        wi, wv = oracle.worker_step(gg, s_ref, off, np.float32(0.1), np.float32(0.9), 1e-3)
+        gi, gv = w.step(gg, 0.1, 0.9, 1e-3)
+        assert gi.size == 108_401
+        assert_pairs_match(gi, gv, wi, wv, f"step {t}")
+    assert_state_match(w.state_host(), s_ref, "state")
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
+
+
+def _billion_grads(scales, rng):
+    """64 tensors of 15,625,000 Gaussian values each: four seeded base blocks,
+    rotated and scaled per tensor (keeps host generation to seconds)."""
+    nj = 15_625_000
+    bases = [rng.standard_normal(nj, dtype=np.float32) for _ in range(4)]
+    g = np.empty(64 * nj, np.float32)
+    for j in range(64):
+        np.multiply(np.roll(bases[j % 4], 1009 * j), np.float32(scales[j]), out=g[j * nj:(j + 1) * nj])
+    return g
+
+
+@pytest.mark.parametrize("rho,K", [(1e-4, 100_032), (1e-2, 10_000_000)])
+def test_c5_one_billion_parameters(oracle, rho, K):
+    """Config 5: 1e9 parameters in 64 equal tensors.  The oracle follows three
+    sampled tensors through both steps; all tensors are checked for exact count,
+    ascending order, the sent/kept split (state == m * val on sent entries) and the
+    threshold property (no kept entry is larger than a sent one)."""
+    import torch
+    off = synth.layout_equal(1_000_000_000, 64)
+    nj = 15_625_000
+    scales = synth.tensor_scales(64, 5)
+    rng = np.random.default_rng(5)
+    g = _billion_grads(scales, rng)
+    ctx = dgs.Context(off, W=0)
+    assert ctx.nnz(rho) == K
+    w = Worker(ctx, density_max=rho)
+    m = np.float32(0.9)
+    sample = [0, 37, 63]
+    one = synth.layout_flat(nj)
+    s_ref = {j: np.zeros(nj, np.float32) for j in sample}
+    kj = K // 64
+    for t in range(2):
+        gt = g if t == 0 else np.roll(g, 7)
+        gi, gv = w.step(gt, 1.0, 0.9, rho)
+        assert gi.size == K
+        assert np.all(np.diff(gi.astype(np.int64)) > 0)
+        tens = gi // nj
+        assert np.array_equal(np.bincount(tens, minlength=64), np.full(64, kj))
+        for j in sample:
+            wi, wv = oracle.worker_step(gt[j * nj:(j + 1) * nj], s_ref[j], one, 1.0, m, rho)
+            sl = slice(j * kj, (j + 1) * kj)
+            assert_pairs_match(gi[sl] - np.uint32(j * nj), gv[sl], wi, wv, f"step {t} tensor {j}")
+        if t == 1:
+            state = w.state_host()
+            for j in sample:
+                assert_state_match(state[j * nj:(j + 1) * nj], s_ref[j], f"state tensor {j}")
+            assert np.array_equal(state[gi].view(np.uint32), (m * gv).view(np.uint32))
+            keys = key_of(state)
+            sent_keys = key_of(gv)
+            keys[gi] = 0
+            for j in range(64):
+                kept_max = keys[j * nj:(j + 1) * nj].max()
+                sent_min = sent_keys[j * kj:(j + 1) * kj].min()
+                assert kept_max <= sent_min, f"tensor {j}: a kept entry outranks a sent one"
+            del state, keys
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    assert st.exact_calls == 1
+    ctx.close()
+    del w
+    torch.cuda.empty_cache()
