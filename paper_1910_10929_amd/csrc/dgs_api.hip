@@ -22,7 +22,7 @@ constexpr uint32_t MAX_PROF = 4096;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
-    size_t tile_desc, tdesc, plans, tau, ghist, tile_cnt, slots, ord, stats, flag, total;
+    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, slots, ord, stats, flag, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -40,10 +40,11 @@ Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
     const size_t ntiles = (size_t)((n + TILE - 1) / TILE);
     Layout L;
     size_t o = 0;
-    L.tile_desc = o; o = align_up(o + ntiles * sizeof(uint2));
+    L.tile_desc = o; o = align_up(o + ntiles * sizeof(uint4));
     L.tdesc = o;     o = align_up(o + (size_t)J * sizeof(TensorDesc));
     L.plans = o;     o = align_up(o + (size_t)NPLAN * J * sizeof(PlanEntry));
     L.tau = o;       o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
+    L.hint2 = o;     o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
     L.ghist = o;     o = align_up(o + (size_t)J * HBINS * sizeof(uint32_t));
     L.tile_cnt = o;  o = align_up(o + (ntiles + 4) * sizeof(uint32_t));
     L.slots = o;     o = align_up(o + ntiles * CAPT * sizeof(uint2));
@@ -79,10 +80,11 @@ struct dgs_ctx {
     char *ws = nullptr;
     Layout L{};
     // device views
-    uint2 *tile_desc = nullptr;
+    uint4 *tile_desc = nullptr;
     TensorDesc *tdesc = nullptr;
     PlanEntry *plans = nullptr;
     uint32_t *tau = nullptr;
+    uint32_t *hint2 = nullptr;
     uint32_t *ghist = nullptr;
     uint32_t *tile_cnt = nullptr;
     uint2 *slots = nullptr;
@@ -207,7 +209,7 @@ uint32_t stream_blocks(const dgs_ctx *c, int mode, uint32_t *qpb_out)
         const uint32_t target = (uint32_t)c->cus * 8u;
         qpb = (c->nquads + target - 1) / target;
     } else {
-        qpb = c->stream_quads ? c->stream_quads : 2u;
+        qpb = c->stream_quads ? c->stream_quads : 1u;
     }
     if (qpb == 0) qpb = 1;
     *qpb_out = qpb;
@@ -236,7 +238,6 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     sa.grad = grad;
     sa.state = state;
     sa.tile_desc = c->tile_desc;
-    sa.tdesc = c->tdesc;
     sa.tau = tau;
     sa.tile_cnt = c->tile_cnt;
     sa.slots = c->slots;
@@ -281,6 +282,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.tile_cnt = c->tile_cnt;
     se.slots = c->slots;
     se.ord = c->ord;
+    se.hint2 = c->hint2 + (size_t)hint_set * c->J;
+    se.exact_mode = exact ? 1u : 0u;
     se.out_idx = idx_out;
     se.out_val = val_out;
     se.stats = c->stats;
@@ -327,10 +330,11 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->offsets.assign(offsets, offsets + J + 1);
     c->ws = (char *)workspace;
     c->L = L;
-    c->tile_desc = (uint2 *)(c->ws + L.tile_desc);
+    c->tile_desc = (uint4 *)(c->ws + L.tile_desc);
     c->tdesc = (TensorDesc *)(c->ws + L.tdesc);
     c->plans = (PlanEntry *)(c->ws + L.plans);
     c->tau = (uint32_t *)(c->ws + L.tau);
+    c->hint2 = (uint32_t *)(c->ws + L.hint2);
     c->ghist = (uint32_t *)(c->ws + L.ghist);
     c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
     c->slots = (uint2 *)(c->ws + L.slots);
@@ -359,7 +363,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
         td[j].pad = 0;
         for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
     }
-    std::vector<uint2> tiles(c->ntiles);
+    std::vector<uint4> tiles(c->ntiles);
     {
         uint32_t j = 0;
         for (uint32_t t = 0; t < c->ntiles; ++t) {
@@ -369,16 +373,22 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
             while (offsets[j + 1] <= first) ++j;
             uint32_t jb = j;
             while (offsets[jb + 1] <= last) ++jb;
-            tiles[t] = make_uint2(j, jb);
+            uint4 d;
+            d.x = j | (td[j].big ? 0x80000000u : 0u);
+            d.y = jb | (td[jb].big ? 0x80000000u : 0u);
+            d.z = (jb != j) ? (uint32_t)offsets[j + 1] : 0xFFFFFFFFu;
+            d.w = (jb != j) ? (uint32_t)offsets[jb] : 0xFFFFFFFFu;
+            tiles[t] = d;
         }
     }
 
     bool ok = true;
     ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemcpyAsync(c->tile_desc, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->tile_desc, tiles.data(), tiles.size() * sizeof(uint4), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tdesc, td.data(), td.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tau, tau0.data(), tau0.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     if (ok) {
+        launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
         launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
         launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
         launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);

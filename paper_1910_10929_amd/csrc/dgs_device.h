@@ -24,9 +24,9 @@ constexpr uint32_t HBITS = 12;
 constexpr uint32_t HBINS = 1u << HBITS;
 constexpr uint32_t HSHIFT = 31 - HBITS;
 // Selection workgroup.
-constexpr uint32_t SEL_THREADS = 512;
+constexpr uint32_t SEL_THREADS = 1024;
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
-constexpr uint32_t SEL_LDS_LIST = 6144;            // candidates kept in LDS (48 KB)
+constexpr uint32_t SEL_LDS_LIST = 8192;            // candidates kept in LDS (64 KB)
 // Above this density candidates stop paying off; such requests select densely.
 constexpr double DENSE_DENSITY = 1.0 / 32.0;
 
@@ -58,8 +58,7 @@ enum SelectOp { SEL_WORKER = 0, SEL_PULL = 1 };
 struct StreamArgs {
     const float *grad;            // OP_FMA only
     float *state;                 // OP_FMA: in/out.  OP_IDENT: read only.
-    const uint2 *tile_desc;       // per tile: tensor of first element, tensor of last valid element
-    const TensorDesc *tdesc;
+    const uint4 *tile_desc;       // per tile: leading tensor, trailing tensor (bit 31: big), end of leading part, begin of trailing part
     const uint32_t *tau;          // per tensor: candidate threshold (TAU_NEVER for small tensors)
     uint32_t *tile_cnt;           // per tile: low 16 = candidates of the leading tensor part, high 16 = trailing part
     uint2 *slots;                 // per tile CAPT x (index, value bits)
@@ -75,13 +74,15 @@ struct SelectArgs {
     uint32_t *tau;                // hints of this stream, updated
     const uint32_t *tile_cnt;
     const uint2 *slots;
-    uint2 *ord;                   // scratch for ordered candidates: tensor j owns CAPT * [first tile + j, last tile + j]
+    uint2 *ord;                   // ordered candidates of tensor j start at CAPT * (first tile + j)
+    uint32_t *hint2;              // per tensor: candidates expected at the hinted threshold (0 = unknown)
     uint32_t *out_idx;
     float *out_val;
     DevStats *stats;
     float m;                      // SEL_WORKER: sent entries keep m * a
     uint32_t force_dense;         // select every tensor straight from `state`
     uint32_t write_hint;
+    uint32_t exact_mode;          // the threshold came from this step's histogram
 };
 
 // Host-callable launchers (defined next to the kernels).

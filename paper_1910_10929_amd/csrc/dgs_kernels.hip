@@ -51,11 +51,21 @@ __device__ __forceinline__ void flush_hist(uint32_t *lhist, uint32_t *ghist, int
 }
 
 template <int OP, int MODE, bool VEC>
-__device__ __forceinline__ void process_tile(const StreamArgs &A, uint32_t t, uint32_t *lhist, int cur)
+__device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *__restrict__ tile_desc,
+                                             const uint32_t *__restrict__ tau, uint32_t t,
+                                             uint32_t *lhist, int cur)
 {
     const uint32_t lane = lane_id();
     const uint32_t base = t * TILE;
     const bool full = (base + TILE <= A.n);
+
+    // Tile descriptor first: its (scalar) load overlaps the vector loads below.
+    //   x = tensor of the first element (bit 31: that tensor is big)
+    //   y = tensor of the last valid element (bit 31: big)
+    //   z = end of the leading tensor part (0xFFFFFFFF when the tile lies inside one tensor)
+    //   w = begin of the trailing tensor part (0xFFFFFFFF when there is none)
+    uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
+    if (MODE != MODE_PLAIN) d = tile_desc[t];
 
     float a[4][4];
     if (VEC && full) {
@@ -107,24 +117,13 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, uint32_t t, ui
     }
     if (MODE == MODE_PLAIN) return;
 
-    // which tensors does this tile touch?
-    const uint2 d = A.tile_desc[t];
-    const uint32_t tA = uniform(d.x), tB = uniform(d.y);
-    const bool straddle = (tA != tB);
-    const TensorDesc dA = A.tdesc[tA];
-    const uint32_t endA = uniform(dA.off + dA.n);
-    uint32_t begB = 0xFFFFFFFFu;
-    uint32_t bigB = 0;
-    if (straddle) {
-        const TensorDesc dB = A.tdesc[tB];
-        begB = uniform(dB.off);
-        bigB = uniform(dB.big);
-    }
-    const uint32_t bigA = uniform(dA.big);
+    const uint32_t tA = d.x & 0x7FFFFFFFu, tB = d.y & 0x7FFFFFFFu;
+    const uint32_t endA = d.z, begB = d.w;
+    const bool straddle = (endA != 0xFFFFFFFFu);
 
     if (MODE == MODE_COLLECT) {
-        const uint32_t tauA = uniform(A.tau[tA]);
-        const uint32_t tauB = straddle ? uniform(A.tau[tB]) : TAU_NEVER;
+        const uint32_t tauA = tau[tA];
+        const uint32_t tauB = (begB != 0xFFFFFFFFu) ? tau[tB] : TAU_NEVER;
         uint2 *myslots = A.slots + (size_t)t * CAPT;
         uint32_t run = 0, runA = 0;
 #pragma unroll
@@ -163,6 +162,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, uint32_t t, ui
         if (lane == 0)
             A.tile_cnt[t] = (run > CAPT) ? CNT_OVERFLOW : (runA | ((run - runA) << 16));
     } else {  // MODE_HIST
+        const bool bigA = (d.x >> 31) != 0, bigB = (d.y >> 31) != 0;
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -185,10 +185,12 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, uint32_t t, ui
 }
 
 template <int OP, int MODE, bool VEC>
-__global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A)
+__global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
+                                                           const uint4 *__restrict__ tile_desc,
+                                                           const uint32_t *__restrict__ tau)
 {
     __shared__ uint32_t lhist[MODE == MODE_HIST ? HBINS : 1];
-    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t wave = uniform(threadIdx.x >> 6);
     const uint32_t q0 = blockIdx.x * A.quads_per_block;
     const uint32_t q1 = min(q0 + A.quads_per_block, A.nquads);
     int cur = -1;
@@ -199,15 +201,15 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A)
     for (uint32_t q = q0; q < q1; ++q) {
         if (MODE == MODE_HIST) {
             // the LDS histogram belongs to the big tensor the quad starts in
-            const uint32_t ft = A.tile_desc[q * WAVES_PER_BLOCK].x;
-            const int qt = A.tdesc[ft].big ? (int)ft : -1;
+            const uint32_t fx = tile_desc[q * WAVES_PER_BLOCK].x;
+            const int qt = (fx >> 31) ? (int)(fx & 0x7FFFFFFFu) : -1;
             if (qt != cur) {
                 flush_hist<MODE>(lhist, A.ghist, cur);
                 cur = qt;
             }
         }
         const uint32_t t = q * WAVES_PER_BLOCK + wave;
-        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, t, lhist, cur);
+        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, tile_desc, tau, t, lhist, cur);
     }
     flush_hist<MODE>(lhist, A.ghist, cur);
 }
@@ -215,8 +217,12 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A)
 template <int OP, int MODE>
 static void launch_stream_t(bool vec, const StreamArgs &a, uint32_t blocks, hipStream_t st)
 {
-    if (vec) hipLaunchKernelGGL((k_stream<OP, MODE, true>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a);
-    else hipLaunchKernelGGL((k_stream<OP, MODE, false>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a);
+    if (vec)
+        hipLaunchKernelGGL((k_stream<OP, MODE, true>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a,
+                           a.tile_desc, a.tau);
+    else
+        hipLaunchKernelGGL((k_stream<OP, MODE, false>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a,
+                           a.tile_desc, a.tau);
 }
 
 void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream)
@@ -234,18 +240,26 @@ void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blo
 }
 
 // ---------------------------------------------------------------------------
-// workgroup helpers for pick / select (SEL_THREADS threads unless stated)
+// workgroup helpers for pick / select
 // ---------------------------------------------------------------------------
 
+// Inclusive prefix sum over the 64 lanes of a wavefront, in registers (DPP):
+// four shifts inside each row of 16 lanes, then two row broadcasts.
 __device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
 {
-    const uint32_t lane = lane_id();
-#pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        uint32_t t = __shfl_up(v, d, 64);
-        if (lane >= (uint32_t)d) v += t;
-    }
-    return v;
+    int x = (int)v;
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return (uint32_t)x;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(v), 63);
 }
 
 // Exclusive scan over the workgroup in thread order; `total` is the workgroup sum.
@@ -269,28 +283,53 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wsum, 
     return before + incl - v;
 }
 
-// In an LDS histogram h[NB] (NB = NT * BPT), find the bucket holding the key of
-// rank R counted from the top (R >= 1), and the rank inside that bucket.
-// res[0] = bucket (or -1 if R exceeds the histogram total), res[1] = rank inside.
-template <int NB, int NT, int NW>
-__device__ __forceinline__ void find_rank(const uint32_t *h, uint32_t R, uint32_t *wsum, int *res)
+// In an LDS histogram h[NB] (NB a multiple of 64, at most 4096), find for each of
+// two ranks RA, RB (counted from the top bin, >= 1) the bin holding it and the
+// rank inside that bin:  res = {binA, rankA, binB, rankB}, bin -1 if the rank
+// exceeds the histogram total.  Every wavefront sums rows of 64 bins, then
+// wavefront 0 scans the row sums and the two rows it lands in.
+// Barriers: one on entry (h complete), one in the middle, one on exit.
+template <int NB, int NW>
+__device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t RA, uint32_t RB, uint32_t *rowsum,
+                                           int *res)
 {
-    constexpr int BPT = NB / NT;
-    static_assert(BPT * NT == NB, "bins must divide evenly");
-    const int hi = NB - 1 - (int)threadIdx.x * BPT;   // thread 0 owns the top bins
-    uint32_t sum = 0;
+    constexpr int ROWS = NB / 64;
+    static_assert(ROWS * 64 == NB && ROWS <= 64, "histogram shape");
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;
+    __syncthreads();
+    for (int r = (int)wave; r < ROWS; r += NW) {
+        const uint32_t s = wave_sum(h[r * 64 + lane]);
+        if (lane == 0) rowsum[r] = s;
+    }
+    __syncthreads();
+    if (wave == 0) {
+        // lane l looks at row ROWS-1-l: the top row first
+        const uint32_t rs = (lane < (uint32_t)ROWS) ? rowsum[ROWS - 1 - lane] : 0u;
+        const uint32_t rincl = wave_incl_scan(rs);
 #pragma unroll
-    for (int i = 0; i < BPT; ++i) sum += h[hi - i];
-    if (threadIdx.x == 0) { res[0] = -1; res[1] = 0; }
-    uint32_t total;
-    const uint32_t excl = block_excl_scan<NW>(sum, wsum, total);   // keys in higher bins
-    if (excl < R && R <= excl + sum) {
-        uint32_t acc = excl;
-#pragma unroll
-        for (int i = 0; i < BPT; ++i) {
-            const uint32_t c = h[hi - i];
-            if (acc + c >= R) { res[0] = hi - i; res[1] = (int)(R - acc); break; }
-            acc += c;
+        for (int which = 0; which < 2; ++which) {
+            const uint32_t R = which ? RB : RA;
+            int bin = -1;
+            uint32_t rin = 0;
+            const uint64_t hit = ballot64(lane < (uint32_t)ROWS && rincl >= R);
+            if (hit != 0 && R != 0) {
+                const int rl = __ffsll((unsigned long long)hit) - 1;          // first row reaching R
+                const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)(rincl - rs), rl);
+                const int row = ROWS - 1 - rl;
+                const uint32_t Rr = R - above;                                 // rank inside the row
+                const uint32_t v = h[row * 64 + (63 - lane)];                  // top bin first
+                const uint32_t vincl = wave_incl_scan(v);
+                const uint64_t hit2 = ballot64(vincl >= Rr);
+                const int bl = __ffsll((unsigned long long)hit2) - 1;
+                const uint32_t above2 = (uint32_t)__builtin_amdgcn_readlane((int)(vincl - v), bl);
+                bin = row * 64 + 63 - bl;
+                rin = Rr - above2;
+            }
+            if (lane == 0) {
+                res[2 * which] = bin;
+                res[2 * which + 1] = (int)rin;
+            }
         }
     }
     __syncthreads();
@@ -306,21 +345,17 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
     const uint32_t j = blockIdx.x;
     if (!tdesc[j].big) return;
     __shared__ uint32_t h[HBINS];
-    __shared__ uint32_t wsum[4];
-    __shared__ int res[2];
+    __shared__ uint32_t rowsum[64];
+    __shared__ int res[4];
     uint32_t *g = ghist + (size_t)j * HBINS;
     for (uint32_t b = threadIdx.x; b < HBINS; b += 256) {
         h[b] = g[b];
         g[b] = 0;   // leave the histogram clean for the next use
     }
-    __syncthreads();
     const PlanEntry pe = plan[j];
-    find_rank<HBINS, 256, 4>(h, pe.k2, wsum, res);
-    int b2 = res[0];
-    __syncthreads();
-    find_rank<HBINS, 256, 4>(h, pe.k, wsum, res);
-    int b1 = res[0];
+    find_ranks<HBINS, 4>(h, pe.k2, pe.k, rowsum, res);
     if (threadIdx.x == 0) {
+        const int b2 = res[0], b1 = res[2];
         uint32_t t;
         if (b2 < 0 || b1 < 0) {
             atomicAdd(&stats->internal_errors, 1ull);
@@ -347,13 +382,23 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 // ---------------------------------------------------------------------------
 
 struct SrcDense {          // the tensor itself: position p <-> element off + p
+    static constexpr bool AGG = false;
     const float *base;
     uint32_t off;
     __device__ __forceinline__ uint32_t bits(uint32_t p) const { return __float_as_uint(base[off + p]); }
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return off + p; }
 };
 
+struct SrcDenseLds {       // a small tensor staged in LDS: position p <-> element off + p
+    static constexpr bool AGG = false;
+    const uint32_t *v;
+    uint32_t off;
+    __device__ __forceinline__ uint32_t bits(uint32_t p) const { return v[p]; }
+    __device__ __forceinline__ uint32_t index(uint32_t p) const { return off + p; }
+};
+
 struct SrcList {           // ordered candidates (index, value bits)
+    static constexpr bool AGG = true;   // candidates share their top key bits: merge per wavefront
     const uint2 *list;
     __device__ __forceinline__ uint32_t bits(uint32_t p) const { return list[p].y; }
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return list[p].x; }
@@ -362,119 +407,125 @@ struct SrcList {           // ordered candidates (index, value bits)
 struct SelShared {
     uint32_t h[2048];
     uint32_t wsum[SEL_WAVES];
-    int res[2];
-    uint32_t bcast[4];
+    uint32_t rowsum[64];
+    int res[4];
 };
 
+// Count into an LDS histogram.  With AGG, lanes of a wavefront that hit the same
+// bin are merged into one atomic (all 64 lanes must call this together).
+template <bool AGG>
+__device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
+{
+    if (!AGG) {
+        if (valid) atomicAdd(&h[bin], 1u);
+        return;
+    }
+    uint64_t todo = ballot64(valid);
+    while (todo != 0) {
+        const int leader = __ffsll((unsigned long long)todo) - 1;
+        const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+        const uint64_t same = ballot64(valid && bin == b0);
+        if ((int)lane_id() == leader) atomicAdd(&h[b0], (uint32_t)__popcll(same));
+        todo &= ~same;
+    }
+}
+
 // Exact selection over `cN` ordered entries of `src`; emits the k winners in
-// order, applies the state fix-up, returns the next threshold hint through
-// *tau_next (0 if rank k2 was not measurable).
+// order and applies the state fix-up.  If R != 0 and R <= cN, also finds the
+// 21-bit key prefix of the entry of rank R: *tau_next = its lower edge (>= 1)
+// and *expect = how many entries lie at or above that edge; otherwise both 0.
 template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
-                                            const uint32_t k2, SelShared &S, const SelectArgs &A,
-                                            const uint32_t outoff, uint32_t *tau_next)
+                                            const uint32_t R, SelShared &S, const SelectArgs &A,
+                                            const uint32_t outoff, uint32_t *tau_next, uint32_t *expect)
 {
     const uint32_t tid = threadIdx.x;
-    const bool measurable = (cN >= k2);
+    const bool measurable = (R != 0) && (cN >= R);
+    *tau_next = 0;
+    *expect = 0;
 
     // ---- pass 1: key bits [30:20]
     for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
     __syncthreads();
-    {
-        uint32_t p = tid;
-        for (; p + 3 * SEL_THREADS < cN; p += 4 * SEL_THREADS) {
-            uint32_t k0 = src.bits(p), k1 = src.bits(p + SEL_THREADS), k2_ = src.bits(p + 2 * SEL_THREADS),
-                     k3 = src.bits(p + 3 * SEL_THREADS);
-            atomicAdd(&S.h[(k0 & 0x7FFFFFFFu) >> 20], 1u);
-            atomicAdd(&S.h[(k1 & 0x7FFFFFFFu) >> 20], 1u);
-            atomicAdd(&S.h[(k2_ & 0x7FFFFFFFu) >> 20], 1u);
-            atomicAdd(&S.h[(k3 & 0x7FFFFFFFu) >> 20], 1u);
+    for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+        uint32_t kk[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t p = pb + i * SEL_THREADS + tid;
+            kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
         }
-        for (; p < cN; p += SEL_THREADS) atomicAdd(&S.h[(src.bits(p) & 0x7FFFFFFFu) >> 20], 1u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            hist_add<Src::AGG>(S.h, kk[i] >> 20, pb + i * SEL_THREADS + tid < cN);
     }
-    __syncthreads();
-    find_rank<2048, SEL_THREADS, SEL_WAVES>(S.h, k, S.wsum, S.res);
+    find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
     const int b1 = S.res[0];
     const uint32_t r1 = (uint32_t)S.res[1];
+    const int c1 = S.res[2];
+    const uint32_t q1 = (uint32_t)S.res[3];
     __syncthreads();
-    int c1 = b1;
-    uint32_t q1 = 0;
-    if (measurable) {
-        find_rank<2048, SEL_THREADS, SEL_WAVES>(S.h, k2, S.wsum, S.res);
-        c1 = S.res[0];
-        q1 = (uint32_t)S.res[1];
-        __syncthreads();
-    }
     if (b1 < 0 || c1 < 0) {   // cannot happen for cN >= k
         if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
-        *tau_next = 0;
         return;
     }
 
     // ---- pass 2: key bits [19:10] inside bucket b1 (and inside c1 for the hint)
+    const bool two = measurable && (c1 != b1);
     for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
     __syncthreads();
-    {
-        const bool two = measurable && (c1 != b1);
-        uint32_t p = tid;
-        for (; p + 3 * SEL_THREADS < cN; p += 4 * SEL_THREADS) {
-            uint32_t kk[4];
+    for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+        uint32_t kk[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kk[i] = src.bits(p + i * SEL_THREADS) & 0x7FFFFFFFu;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int top = (int)(kk[i] >> 20);
-                if (top == b1) atomicAdd(&S.h[(kk[i] >> 10) & 1023u], 1u);
-                else if (two && top == c1) atomicAdd(&S.h[1024u + ((kk[i] >> 10) & 1023u)], 1u);
-            }
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t p = pb + i * SEL_THREADS + tid;
+            kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0xFFFFFFFFu;   // top bits match no bucket
         }
-        for (; p < cN; p += SEL_THREADS) {
-            const uint32_t key = src.bits(p) & 0x7FFFFFFFu;
-            const int top = (int)(key >> 20);
-            if (top == b1) atomicAdd(&S.h[(key >> 10) & 1023u], 1u);
-            else if (two && top == c1) atomicAdd(&S.h[1024u + ((key >> 10) & 1023u)], 1u);
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int top = (int)(kk[i] >> 20);
+            if (top == b1) atomicAdd(&S.h[(kk[i] >> 10) & 1023u], 1u);
+            else if (two && top == c1) atomicAdd(&S.h[1024u + ((kk[i] >> 10) & 1023u)], 1u);
         }
     }
-    __syncthreads();
-    find_rank<1024, SEL_THREADS, SEL_WAVES>(S.h, r1, S.wsum, S.res);
+    find_ranks<1024, SEL_WAVES>(S.h, r1, (measurable && !two) ? q1 : r1, S.rowsum, S.res);
     const int b2 = S.res[0];
     const uint32_t r2 = (uint32_t)S.res[1];
+    int c2 = S.res[2];
+    uint32_t q2 = (uint32_t)S.res[3];
     __syncthreads();
-    uint32_t hint = 0;
-    if (measurable) {
-        find_rank<1024, SEL_THREADS, SEL_WAVES>(S.h + ((c1 != b1) ? 1024 : 0), q1, S.wsum, S.res);
-        const int c2 = S.res[0];
+    if (two) {
+        find_ranks<1024, SEL_WAVES>(S.h + 1024, q1, q1, S.rowsum, S.res);
+        c2 = S.res[0];
+        q2 = (uint32_t)S.res[1];
         __syncthreads();
-        if (c2 >= 0) hint = ((uint32_t)c1 << 20) | ((uint32_t)c2 << 10);
-        if (hint == 0) hint = 1;
     }
-    *tau_next = hint;
+    if (measurable && c2 >= 0) {
+        const uint32_t edge = ((uint32_t)c1 << 20) | ((uint32_t)c2 << 10);
+        *tau_next = edge ? edge : 1u;
+        *expect = R - q2 + S.h[(two ? 1024 : 0) + c2];
+    }
     if (b2 < 0) {
         if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
         return;
     }
+    __syncthreads();
 
     // ---- pass 3: key bits [9:0] inside (b1, b2)
     const uint32_t pfx = ((uint32_t)b1 << 10) | (uint32_t)b2;
     for (uint32_t b = tid; b < 1024; b += SEL_THREADS) S.h[b] = 0;
     __syncthreads();
-    {
-        uint32_t p = tid;
-        for (; p + 3 * SEL_THREADS < cN; p += 4 * SEL_THREADS) {
-            uint32_t kk[4];
+    for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+        uint32_t kk[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) kk[i] = src.bits(p + i * SEL_THREADS) & 0x7FFFFFFFu;
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t p = pb + i * SEL_THREADS + tid;
+            kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0xFFFFFFFFu;
+        }
 #pragma unroll
-            for (int i = 0; i < 4; ++i)
-                if ((kk[i] >> 10) == pfx) atomicAdd(&S.h[kk[i] & 1023u], 1u);
-        }
-        for (; p < cN; p += SEL_THREADS) {
-            const uint32_t key = src.bits(p) & 0x7FFFFFFFu;
-            if ((key >> 10) == pfx) atomicAdd(&S.h[key & 1023u], 1u);
-        }
+        for (int i = 0; i < 4; ++i)
+            if ((kk[i] >> 10) == pfx) atomicAdd(&S.h[kk[i] & 1023u], 1u);
     }
-    __syncthreads();
-    find_rank<1024, SEL_THREADS, SEL_WAVES>(S.h, r2, S.wsum, S.res);
+    find_ranks<1024, SEL_WAVES>(S.h, r2, r2, S.rowsum, S.res);
     const int b3 = S.res[0];
     const uint32_t rT = (uint32_t)S.res[1];   // how many entries equal to T are taken (lowest index first)
     __syncthreads();
@@ -540,8 +591,36 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
     if (run_sel != k && tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
 }
 
+// What one thread fetches for one tile before it knows the tile's count.
+struct TileFetch {
+    uint32_t w;      // count word
+    uint4 pa, pb;    // candidate slots 0..3
+};
+
+__device__ __forceinline__ TileFetch fetch_tile(const uint32_t *__restrict__ tile_cnt,
+                                                const uint2 *__restrict__ slots, uint32_t t, bool valid)
+{
+    TileFetch f;
+    f.w = 0;
+    f.pa = make_uint4(0, 0, 0, 0);
+    f.pb = f.pa;
+    if (valid) {
+        f.w = tile_cnt[t];
+        const uint4 *sp = (const uint4 *)(slots + (size_t)t * CAPT);
+        f.pa = sp[0];
+        f.pb = sp[1];
+    }
+    return f;
+}
+
+// One workgroup per tensor.  Big tensors: join the per-tile candidate slots into
+// one ordered list (LDS, mirrored to global scratch for lists that outgrow LDS),
+// then select.  Small tensors, dense requests and failed predictions: select
+// straight from the state buffer.
 template <int OP>
-__global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
+__global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
+                                                        const uint32_t *__restrict__ tile_cnt,
+                                                        const uint2 *__restrict__ slots)
 {
     __shared__ SelShared S;
     __shared__ uint2 llist[SEL_LDS_LIST];
@@ -554,80 +633,123 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
     const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
     bool dense = (!td.big) || A.force_dense;
     uint32_t c = 0;
-    uint32_t tau_next = 0;
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
-
-    const uint32_t ntl = thi - tlo + 1;
-    const uint32_t per = (ntl + SEL_THREADS - 1) / SEL_THREADS;
-    const uint32_t my_lo = min(tlo + tid * per, thi + 1);
-    const uint32_t my_hi = min(my_lo + per, thi + 1);
+    uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
 
     if (!dense) {
-        // candidates of this tensor, tile by tile
-        uint32_t mine = 0, ovf = 0;
-        for (uint32_t t = my_lo; t < my_hi; ++t) {
-            const uint32_t w = A.tile_cnt[t];
-            if (w == CNT_OVERFLOW) ovf = 1;
-            else mine += (t == tlo && head_shared) ? (w >> 16) : (w & 0xFFFFu);
+        // ---- chunks of SEL_THREADS tiles, one tile per thread; the next chunk's
+        //      loads are in flight while the current one is scanned and copied
+        const uint32_t ntl = thi - tlo + 1;
+        uint32_t ovf = 0;
+        TileFetch cur = fetch_tile(tile_cnt, slots, tlo + tid, tlo + tid <= thi);
+        for (uint32_t cb = 0; cb < ntl; cb += SEL_THREADS) {
+            const uint32_t t = tlo + cb + tid;
+            const uint32_t tn = t + SEL_THREADS;
+            TileFetch nxt;
+            nxt.w = 0;
+            if (cb + SEL_THREADS < ntl) nxt = fetch_tile(tile_cnt, slots, tn, tn <= thi);
+            uint32_t w = cur.w;
+            if (w == CNT_OVERFLOW) { ovf = 1; w = 0; }
+            const bool hs = head_shared && (t == tlo);
+            const uint32_t cnt = hs ? (w >> 16) : (w & 0xFFFFu);
+            const uint32_t start = hs ? (w & 0xFFFFu) : 0u;
+            uint32_t ctot;
+            const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
+            if (cnt != 0) {
+                const uint2 *sl = slots + (size_t)t * CAPT + start;
+                uint32_t i0 = 0;
+                if (start == 0) {
+                    const uint2 e0 = make_uint2(cur.pa.x, cur.pa.y), e1 = make_uint2(cur.pa.z, cur.pa.w);
+                    const uint2 e2 = make_uint2(cur.pb.x, cur.pb.y), e3 = make_uint2(cur.pb.z, cur.pb.w);
+                    if (cnt > 0) { glist[pos + 0] = e0; if (pos + 0 < SEL_LDS_LIST) llist[pos + 0] = e0; }
+                    if (cnt > 1) { glist[pos + 1] = e1; if (pos + 1 < SEL_LDS_LIST) llist[pos + 1] = e1; }
+                    if (cnt > 2) { glist[pos + 2] = e2; if (pos + 2 < SEL_LDS_LIST) llist[pos + 2] = e2; }
+                    if (cnt > 3) { glist[pos + 3] = e3; if (pos + 3 < SEL_LDS_LIST) llist[pos + 3] = e3; }
+                    i0 = 4;
+                }
+                // the rest of a crowded tile, four independent loads at a time
+                for (uint32_t i = i0; i < cnt; i += 4) {
+                    uint2 e[4];
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) e[u] = (i + u < cnt) ? sl[i + u] : make_uint2(0, 0);
+#pragma unroll
+                    for (uint32_t u = 0; u < 4; ++u) {
+                        if (i + u < cnt) {
+                            glist[pos + i + u] = e[u];
+                            if (pos + i + u < SEL_LDS_LIST) llist[pos + i + u] = e[u];
+                        }
+                    }
+                }
+            }
+            c += ctot;
+            cur = nxt;
         }
-        uint32_t total;
-        const uint32_t before = block_excl_scan<SEL_WAVES>(mine, S.wsum, total);
-        const uint32_t any_ovf = __syncthreads_or((int)ovf);
-        c = total;   // < 2^30: n < 2^32 and at most a quarter of a tile are candidates
-        if (any_ovf || c < pe.k) {
-            dense = true;
-            if (tid == 0) {
+        const bool any_ovf = __syncthreads_or((int)ovf) != 0;   // also orders the list writes
+        if (any_ovf || c < pe.k) dense = true;
+        if (tid == 0) {
+            if (dense) {
                 atomicAdd(&A.stats->fallback_tensors, 1ull);
                 atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+            } else {
+                atomicAdd(&A.stats->candidates, (unsigned long long)c);
             }
-        } else {
-            // gather into index order
-            uint2 *dst = (c <= SEL_LDS_LIST) ? llist : (A.ord + (size_t)(tlo + j) * CAPT);
-            uint32_t pos = before;
-            for (uint32_t t = my_lo; t < my_hi; ++t) {
-                const uint32_t w = A.tile_cnt[t];
-                const bool hs = (t == tlo && head_shared);
-                const uint32_t cnt = hs ? (w >> 16) : (w & 0xFFFFu);
-                const uint32_t start = hs ? (w & 0xFFFFu) : 0u;
-                const uint2 *sl = A.slots + (size_t)t * CAPT + start;
-                for (uint32_t i = 0; i < cnt; ++i) dst[pos + i] = sl[i];
-                pos += cnt;
-            }
-            if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
-            __threadfence_block();
-            __syncthreads();
         }
     }
 
+    // ---- rank whose key becomes the next predicted threshold
+    uint32_t R = 0;
+    if (td.big && A.write_hint) {
+        float d = 1.0f;     // growth of the tail count since the threshold was set
+        const uint32_t E = A.hint2[j];
+        if (!dense && !A.exact_mode && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
+        R = (uint32_t)((float)pe.k2 / d);
+        const uint32_t rmin = max(1u, pe.k / 4u);
+        R = min(max(R, rmin), td.n);
+    }
+
+    uint32_t tau_next = 0, expect = 0;
     if (dense) {
-        SrcDense src{A.state, td.off};
-        select_emit<OP, 8>(src, td.n, pe.k, pe.k2, S, A, pe.outoff, &tau_next);
+        if (td.n <= 2 * SEL_LDS_LIST) {
+            uint32_t *lv = (uint32_t *)llist;
+            __syncthreads();
+            for (uint32_t p = tid; p < td.n; p += SEL_THREADS) lv[p] = __float_as_uint(A.state[td.off + p]);
+            __syncthreads();
+            SrcDenseLds src{lv, td.off};
+            select_emit<OP, 4>(src, td.n, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+        } else {
+            SrcDense src{A.state, td.off};
+            select_emit<OP, 8>(src, td.n, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+        }
     } else if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, pe.k2, S, A, pe.outoff, &tau_next);
+        select_emit<OP, 4>(src, c, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
     } else {
-        SrcList src{A.ord + (size_t)(tlo + j) * CAPT};
-        select_emit<OP, 8>(src, c, pe.k, pe.k2, S, A, pe.outoff, &tau_next);
+        SrcList src{glist};
+        select_emit<OP, 8>(src, c, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
     }
 
     if (td.big && A.write_hint && tid == 0) {
-        uint32_t t = tau_next;
-        if (t == 0) {
-            // rank k2 was not among the candidates: relax the current threshold by a quarter
-            float f = __uint_as_float(tau_cur & 0x7FFFFFFFu) * 0.75f;
-            t = __float_as_uint(f) & 0x7FFFFFFFu;
-            if (!(tau_cur > 1u) || t == 0) t = 1;
+        uint32_t tn = tau_next;
+        if (tn == 0) {
+            // rank R was not among the candidates: relax the current threshold by a quarter
+            const float f = __uint_as_float(tau_cur & 0x7FFFFFFFu) * 0.75f;
+            tn = __float_as_uint(f) & 0x7FFFFFFFu;
+            if (!(tau_cur > 1u) || tn == 0) tn = 1;
+            expect = 0;
         }
-        if (t >= 0x7F800000u) t = 0x7F7FFFFFu;   // keep the hint finite
-        A.tau[j] = t;
+        if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;   // keep the hint finite
+        A.tau[j] = tn;
+        A.hint2[j] = expect;
     }
 }
 
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (op == SEL_WORKER) hipLaunchKernelGGL(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), 0, st, a);
-    else hipLaunchKernelGGL(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), 0, st, a);
+    if (op == SEL_WORKER)
+        hipLaunchKernelGGL(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), 0, st, a, a.tile_cnt, a.slots);
+    else
+        hipLaunchKernelGGL(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), 0, st, a, a.tile_cnt, a.slots);
 }
 
 // ---------------------------------------------------------------------------
