@@ -303,12 +303,13 @@ __device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t RA, uint3
         if (lane == 0) rowsum[r] = s;
     }
     __syncthreads();
-    if (wave == 0) {
+    if (wave < 2) {
+        // wavefront 0 searches RA, wavefront 1 searches RB (one wavefront does both if alone);
         // lane l looks at row ROWS-1-l: the top row first
         const uint32_t rs = (lane < (uint32_t)ROWS) ? rowsum[ROWS - 1 - lane] : 0u;
         const uint32_t rincl = wave_incl_scan(rs);
-#pragma unroll
-        for (int which = 0; which < 2; ++which) {
+        const int first = (NW >= 2) ? (int)wave : 0, last = (NW >= 2) ? (int)wave : 1;
+        for (int which = first; which <= last; ++which) {
             const uint32_t R = which ? RB : RA;
             int bin = -1;
             uint32_t rin = 0;
@@ -434,85 +435,136 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
 // order and applies the state fix-up.  If R != 0 and R <= cN, also finds the
 // 21-bit key prefix of the entry of rank R: *tau_next = its lower edge (>= 1)
 // and *expect = how many entries lie at or above that edge; otherwise both 0.
+// win_base: (collection threshold >> 11) for candidate lists, 0xFFFFFFFF otherwise.
 template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
-                                            const uint32_t R, SelShared &S, const SelectArgs &A,
-                                            const uint32_t outoff, uint32_t *tau_next, uint32_t *expect)
+                                            const uint32_t R, const uint32_t win_base, SelShared &S,
+                                            const SelectArgs &A, const uint32_t outoff,
+                                            uint32_t *tau_next, uint32_t *expect)
 {
     const uint32_t tid = threadIdx.x;
     const bool measurable = (R != 0) && (cN >= R);
     *tau_next = 0;
     *expect = 0;
 
-    // ---- pass 1: key bits [30:20]
-    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
-    __syncthreads();
-    for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
-        uint32_t kk[4];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t p = pb + i * SEL_THREADS + tid;
-            kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
-        }
-#pragma unroll
-        for (int i = 0; i < 4; ++i)
-            hist_add<Src::AGG>(S.h, kk[i] >> 20, pb + i * SEL_THREADS + tid < cN);
-    }
-    find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
-    const int b1 = S.res[0];
-    const uint32_t r1 = (uint32_t)S.res[1];
-    const int c1 = S.res[2];
-    const uint32_t q1 = (uint32_t)S.res[3];
-    __syncthreads();
-    if (b1 < 0 || c1 < 0) {   // cannot happen for cN >= k
-        if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
-        return;
-    }
+    uint32_t pfx = 0;        // key prefix of the k-th entry, `lowbits` bits still unresolved
+    uint32_t r2 = 0;         // its rank among the entries sharing that prefix
+    uint32_t lowbits = 10;
+    bool have_prefix = false;
 
-    // ---- pass 2: key bits [19:10] inside bucket b1 (and inside c1 for the hint)
-    const bool two = measurable && (c1 != b1);
-    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
-    __syncthreads();
-    for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
-        uint32_t kk[4];
+    // ---- candidate lists: every key is >= the collection threshold, and the k-th key
+    //      normally lies within a factor ~1.4 of it.  One pass over a window of 2047
+    //      buckets of key >> 11 above the threshold (bucket 2047 = everything beyond)
+    //      resolves 20 key bits at once.
+    if (Src::AGG && win_base != 0xFFFFFFFFu) {
+        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
+        __syncthreads();
+        for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+            uint32_t kk[4];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const uint32_t p = pb + i * SEL_THREADS + tid;
-            kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0xFFFFFFFFu;   // top bits match no bucket
-        }
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t p = pb + i * SEL_THREADS + tid;
+                kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
+            }
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int top = (int)(kk[i] >> 20);
-            if (top == b1) atomicAdd(&S.h[(kk[i] >> 10) & 1023u], 1u);
-            else if (two && top == c1) atomicAdd(&S.h[1024u + ((kk[i] >> 10) & 1023u)], 1u);
+            for (int i = 0; i < 4; ++i) {
+                if (pb + i * SEL_THREADS + tid < cN) {
+                    const uint32_t hi = kk[i] >> 11;
+                    const uint32_t w = (hi > win_base) ? (hi - win_base) : 0u;
+                    atomicAdd(&S.h[min(w, 2047u)], 1u);
+                }
+            }
         }
-    }
-    find_ranks<1024, SEL_WAVES>(S.h, r1, (measurable && !two) ? q1 : r1, S.rowsum, S.res);
-    const int b2 = S.res[0];
-    const uint32_t r2 = (uint32_t)S.res[1];
-    int c2 = S.res[2];
-    uint32_t q2 = (uint32_t)S.res[3];
-    __syncthreads();
-    if (two) {
-        find_ranks<1024, SEL_WAVES>(S.h + 1024, q1, q1, S.rowsum, S.res);
-        c2 = S.res[0];
-        q2 = (uint32_t)S.res[1];
+        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
+        const int bk = S.res[0], bR = S.res[2];
+        const uint32_t rk = (uint32_t)S.res[1], rR = (uint32_t)S.res[3];
+        if (bk >= 0 && bk < 2047 && bR >= 0 && bR < 2047) {
+            have_prefix = true;
+            pfx = win_base + (uint32_t)bk;
+            r2 = rk;
+            lowbits = 11;
+            if (measurable) {
+                const uint32_t edge = (win_base + (uint32_t)bR) << 11;
+                *tau_next = edge ? edge : 1u;
+                *expect = R - rR + S.h[bR];
+            }
+        }
         __syncthreads();
     }
-    if (measurable && c2 >= 0) {
-        const uint32_t edge = ((uint32_t)c1 << 20) | ((uint32_t)c2 << 10);
-        *tau_next = edge ? edge : 1u;
-        *expect = R - q2 + S.h[(two ? 1024 : 0) + c2];
-    }
-    if (b2 < 0) {
-        if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
-        return;
-    }
-    __syncthreads();
 
-    // ---- pass 3: key bits [9:0] inside (b1, b2)
-    const uint32_t pfx = ((uint32_t)b1 << 10) | (uint32_t)b2;
-    for (uint32_t b = tid; b < 1024; b += SEL_THREADS) S.h[b] = 0;
+    if (!have_prefix) {
+        // ---- pass 1: key bits [30:20]
+        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
+        __syncthreads();
+        for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+            uint32_t kk[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t p = pb + i * SEL_THREADS + tid;
+                kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                hist_add<Src::AGG>(S.h, kk[i] >> 20, pb + i * SEL_THREADS + tid < cN);
+        }
+        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
+        const int b1 = S.res[0];
+        const uint32_t r1 = (uint32_t)S.res[1];
+        const int c1 = S.res[2];
+        const uint32_t q1 = (uint32_t)S.res[3];
+        __syncthreads();
+        if (b1 < 0 || c1 < 0) {   // cannot happen for cN >= k
+            if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
+            return;
+        }
+
+        // ---- pass 2: key bits [19:10] inside bucket b1 (and inside c1 for the hint)
+        const bool two = measurable && (c1 != b1);
+        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
+        __syncthreads();
+        for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+            uint32_t kk[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const uint32_t p = pb + i * SEL_THREADS + tid;
+                kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0xFFFFFFFFu;   // top bits match no bucket
+            }
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int top = (int)(kk[i] >> 20);
+                if (top == b1) atomicAdd(&S.h[(kk[i] >> 10) & 1023u], 1u);
+                else if (two && top == c1) atomicAdd(&S.h[1024u + ((kk[i] >> 10) & 1023u)], 1u);
+            }
+        }
+        find_ranks<1024, SEL_WAVES>(S.h, r1, (measurable && !two) ? q1 : r1, S.rowsum, S.res);
+        const int b2 = S.res[0];
+        r2 = (uint32_t)S.res[1];
+        int c2 = S.res[2];
+        uint32_t q2 = (uint32_t)S.res[3];
+        __syncthreads();
+        if (two) {
+            find_ranks<1024, SEL_WAVES>(S.h + 1024, q1, q1, S.rowsum, S.res);
+            c2 = S.res[0];
+            q2 = (uint32_t)S.res[1];
+            __syncthreads();
+        }
+        if (measurable && c2 >= 0) {
+            const uint32_t edge = ((uint32_t)c1 << 20) | ((uint32_t)c2 << 10);
+            *tau_next = edge ? edge : 1u;
+            *expect = R - q2 + S.h[(two ? 1024 : 0) + c2];
+        }
+        if (b2 < 0) {
+            if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
+            return;
+        }
+        pfx = ((uint32_t)b1 << 10) | (uint32_t)b2;
+        lowbits = 10;
+        __syncthreads();
+    }
+
+    // ---- last pass: the low key bits among the entries sharing the prefix
+    const uint32_t lowmask = (1u << lowbits) - 1u;
+    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
     __syncthreads();
     for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
         uint32_t kk[4];
@@ -523,9 +575,9 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            if ((kk[i] >> 10) == pfx) atomicAdd(&S.h[kk[i] & 1023u], 1u);
+            if ((kk[i] >> lowbits) == pfx) atomicAdd(&S.h[kk[i] & lowmask], 1u);
     }
-    find_ranks<1024, SEL_WAVES>(S.h, r2, r2, S.rowsum, S.res);
+    find_ranks<2048, SEL_WAVES>(S.h, r2, r2, S.rowsum, S.res);
     const int b3 = S.res[0];
     const uint32_t rT = (uint32_t)S.res[1];   // how many entries equal to T are taken (lowest index first)
     __syncthreads();
@@ -533,7 +585,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
         if (tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
         return;
     }
-    const uint32_t T = (pfx << 10) | (uint32_t)b3;
+    const uint32_t T = (pfx << lowbits) | (uint32_t)b3;
 
     // ---- ordered emission
     uint32_t run_sel = 0, run_eq = 0;
@@ -594,7 +646,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
 // What one thread fetches for one tile before it knows the tile's count.
 struct TileFetch {
     uint32_t w;      // count word
-    uint4 pa, pb;    // candidate slots 0..3
+    uint4 p[4];      // candidate slots 0..7 (one 64-byte line)
 };
 
 __device__ __forceinline__ TileFetch fetch_tile(const uint32_t *__restrict__ tile_cnt,
@@ -602,21 +654,30 @@ __device__ __forceinline__ TileFetch fetch_tile(const uint32_t *__restrict__ til
 {
     TileFetch f;
     f.w = 0;
-    f.pa = make_uint4(0, 0, 0, 0);
-    f.pb = f.pa;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) f.p[i] = make_uint4(0, 0, 0, 0);
     if (valid) {
         f.w = tile_cnt[t];
         const uint4 *sp = (const uint4 *)(slots + (size_t)t * CAPT);
-        f.pa = sp[0];
-        f.pb = sp[1];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) f.p[i] = sp[i];
     }
     return f;
 }
 
+// Ordered-list entry: LDS while it fits, global scratch beyond.
+__device__ __forceinline__ void put_entry(uint2 *llist, uint2 *glist, uint32_t pos, uint2 e)
+{
+    if (pos < SEL_LDS_LIST) llist[pos] = e;
+    else glist[pos] = e;
+}
+
+constexpr uint32_t SEL_BATCH = 3;   // chunks of SEL_THREADS tiles whose loads are issued together
+
 // One workgroup per tensor.  Big tensors: join the per-tile candidate slots into
-// one ordered list (LDS, mirrored to global scratch for lists that outgrow LDS),
-// then select.  Small tensors, dense requests and failed predictions: select
-// straight from the state buffer.
+// one ordered list (LDS; lists that outgrow it continue in global scratch), then
+// select.  Small tensors, dense requests and failed predictions: select straight
+// from the state buffer.
 template <int OP>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                                                         const uint32_t *__restrict__ tile_cnt,
@@ -637,55 +698,58 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
 
     if (!dense) {
-        // ---- chunks of SEL_THREADS tiles, one tile per thread; the next chunk's
-        //      loads are in flight while the current one is scanned and copied
+        // ---- one tile per thread and chunk; the loads of SEL_BATCH chunks are in flight together
         const uint32_t ntl = thi - tlo + 1;
         uint32_t ovf = 0;
-        TileFetch cur = fetch_tile(tile_cnt, slots, tlo + tid, tlo + tid <= thi);
-        for (uint32_t cb = 0; cb < ntl; cb += SEL_THREADS) {
-            const uint32_t t = tlo + cb + tid;
-            const uint32_t tn = t + SEL_THREADS;
-            TileFetch nxt;
-            nxt.w = 0;
-            if (cb + SEL_THREADS < ntl) nxt = fetch_tile(tile_cnt, slots, tn, tn <= thi);
-            uint32_t w = cur.w;
-            if (w == CNT_OVERFLOW) { ovf = 1; w = 0; }
-            const bool hs = head_shared && (t == tlo);
-            const uint32_t cnt = hs ? (w >> 16) : (w & 0xFFFFu);
-            const uint32_t start = hs ? (w & 0xFFFFu) : 0u;
-            uint32_t ctot;
-            const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
-            if (cnt != 0) {
-                const uint2 *sl = slots + (size_t)t * CAPT + start;
-                uint32_t i0 = 0;
-                if (start == 0) {
-                    const uint2 e0 = make_uint2(cur.pa.x, cur.pa.y), e1 = make_uint2(cur.pa.z, cur.pa.w);
-                    const uint2 e2 = make_uint2(cur.pb.x, cur.pb.y), e3 = make_uint2(cur.pb.z, cur.pb.w);
-                    if (cnt > 0) { glist[pos + 0] = e0; if (pos + 0 < SEL_LDS_LIST) llist[pos + 0] = e0; }
-                    if (cnt > 1) { glist[pos + 1] = e1; if (pos + 1 < SEL_LDS_LIST) llist[pos + 1] = e1; }
-                    if (cnt > 2) { glist[pos + 2] = e2; if (pos + 2 < SEL_LDS_LIST) llist[pos + 2] = e2; }
-                    if (cnt > 3) { glist[pos + 3] = e3; if (pos + 3 < SEL_LDS_LIST) llist[pos + 3] = e3; }
-                    i0 = 4;
-                }
-                // the rest of a crowded tile, four independent loads at a time
-                for (uint32_t i = i0; i < cnt; i += 4) {
-                    uint2 e[4];
+        for (uint32_t cb = 0; cb < ntl; cb += SEL_BATCH * SEL_THREADS) {
+            TileFetch f[SEL_BATCH];
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u) e[u] = (i + u < cnt) ? sl[i + u] : make_uint2(0, 0);
+            for (uint32_t u = 0; u < SEL_BATCH; ++u) {
+                const uint32_t t = tlo + cb + u * SEL_THREADS + tid;
+                f[u] = fetch_tile(tile_cnt, slots, t, t <= thi);
+            }
 #pragma unroll
-                    for (uint32_t u = 0; u < 4; ++u) {
-                        if (i + u < cnt) {
-                            glist[pos + i + u] = e[u];
-                            if (pos + i + u < SEL_LDS_LIST) llist[pos + i + u] = e[u];
+            for (uint32_t u = 0; u < SEL_BATCH; ++u) {
+                if (cb + u * SEL_THREADS >= ntl) break;      // uniform
+                const uint32_t t = tlo + cb + u * SEL_THREADS + tid;
+                uint32_t w = f[u].w;
+                if (w == CNT_OVERFLOW) { ovf = 1; w = 0; }
+                const bool hs = head_shared && (t == tlo);
+                const uint32_t cnt = hs ? (w >> 16) : (w & 0xFFFFu);
+                const uint32_t start = hs ? (w & 0xFFFFu) : 0u;
+                uint32_t ctot;
+                const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
+                if (cnt != 0) {
+                    const uint2 *sl = slots + (size_t)t * CAPT + start;
+                    uint32_t i0 = 0;
+                    if (start == 0) {
+#pragma unroll
+                        for (uint32_t i = 0; i < 4; ++i) {
+                            if (2 * i < cnt) put_entry(llist, glist, pos + 2 * i, make_uint2(f[u].p[i].x, f[u].p[i].y));
+                            if (2 * i + 1 < cnt) put_entry(llist, glist, pos + 2 * i + 1, make_uint2(f[u].p[i].z, f[u].p[i].w));
                         }
+                        i0 = 8;
+                    }
+                    // the rest of a crowded tile, four independent loads at a time
+                    for (uint32_t i = i0; i < cnt; i += 4) {
+                        uint2 e[4];
+#pragma unroll
+                        for (uint32_t v = 0; v < 4; ++v) e[v] = (i + v < cnt) ? sl[i + v] : make_uint2(0, 0);
+#pragma unroll
+                        for (uint32_t v = 0; v < 4; ++v)
+                            if (i + v < cnt) put_entry(llist, glist, pos + i + v, e[v]);
                     }
                 }
+                c += ctot;
             }
-            c += ctot;
-            cur = nxt;
         }
         const bool any_ovf = __syncthreads_or((int)ovf) != 0;   // also orders the list writes
         if (any_ovf || c < pe.k) dense = true;
+        if (!dense && c > SEL_LDS_LIST) {
+            // the list outgrew LDS: complete the global copy
+            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
+            __syncthreads();
+        }
         if (tid == 0) {
             if (dense) {
                 atomicAdd(&A.stats->fallback_tensors, 1ull);
@@ -708,6 +772,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     }
 
     uint32_t tau_next = 0, expect = 0;
+    const uint32_t win_base = (tau_cur & 0x7FFFFFFFu) >> 11;
     if (dense) {
         if (td.n <= 2 * SEL_LDS_LIST) {
             uint32_t *lv = (uint32_t *)llist;
@@ -715,17 +780,17 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
             for (uint32_t p = tid; p < td.n; p += SEL_THREADS) lv[p] = __float_as_uint(A.state[td.off + p]);
             __syncthreads();
             SrcDenseLds src{lv, td.off};
-            select_emit<OP, 4>(src, td.n, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+            select_emit<OP, 4>(src, td.n, pe.k, R, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect);
         } else {
             SrcDense src{A.state, td.off};
-            select_emit<OP, 8>(src, td.n, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+            select_emit<OP, 8>(src, td.n, pe.k, R, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect);
         }
     } else if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+        select_emit<OP, 4>(src, c, pe.k, R, win_base, S, A, pe.outoff, &tau_next, &expect);
     } else {
         SrcList src{glist};
-        select_emit<OP, 8>(src, c, pe.k, R, S, A, pe.outoff, &tau_next, &expect);
+        select_emit<OP, 8>(src, c, pe.k, R, win_base, S, A, pe.outoff, &tau_next, &expect);
     }
 
     if (td.big && A.write_hint && tid == 0) {
