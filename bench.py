@@ -1,15 +1,20 @@
 #!/usr/bin/env python3
 """Benchmark of the DGS hot path on one MI355X.
 
-A step = one pass of the whole hot path on the ResNet-50-shaped workload
-(25,557,032 fp32 parameters in 161 tensors, density 1e-3, one worker):
-dgs_worker_step -> dgs_server_push -> dgs_server_pull.  Inputs are seeded and
-synthetic (per-tensor log-uniform scale, Gaussian values, a pool of 8 gradient
-sets cycled), resident in HBM before the timed region starts.
+Default workload (`--workload c2`): a step = one pass of the whole hot path on
+the ResNet-50-shaped parameter set (25,557,032 fp32 parameters in 161 tensors,
+density 1e-3, one worker): dgs_worker_step -> dgs_server_push ->
+dgs_server_pull.  Inputs are seeded and synthetic (per-tensor log-uniform scale,
+Gaussian values, a pool of gradient sets cycled), resident in HBM before the
+timed region starts.
+
+Other workloads, for the design notes (not the default bench line):
+  c3  server stress: 32 workers' difference rows, step = push + pull of a seeded worker
+  c5  1e9 parameters in 64 tensors, `--density` 1e-4 or 1e-2, step as in c2
 
 Prints ONE JSON line: params/s over the timed steps, the roofline of the
-dominant kernel (the fused accumulate + candidate streaming pass, timed with HIP
-events on its own stream), and the CPU oracle timed on a bounded sample.
+dominant kernel (the streaming pass, timed with HIP events on the stream it is
+launched on), and the CPU oracle timed on a bounded sample.
 """
 from __future__ import annotations
 
@@ -26,56 +31,103 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
-POOL = 8
-DENSITY = 1e-3
 LR, MOMENTUM = 1.0, 0.9
-SEED = 2
 
-# HBM traffic per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE /
-# WRITE_SIZE runs (see profiles/); None until measured for this workload.
-MEASURED_TRAFFIC_BYTES = None
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE,
+# WRITE_SIZE, scaled by the same counters on a copy kernel of known size); the
+# summaries are under profiles/.  None = not measured for that workload.
+MEASURED_TRAFFIC_BYTES = {"c2": 308.47e6, "c3": None, "c5": None}
 
 
-def make_workload():
+def make_workload(name, density):
     from paper_1910_10929_amd import synth
-    off = synth.layout_resnet50()
-    scales = synth.tensor_scales(len(off) - 1, SEED)
-    rng = np.random.default_rng(SEED)
-    grads = [synth.gaussian_grads(off, scales, rng) for _ in range(POOL)]
-    return off, grads
+    if name in ("c2", "c3"):
+        off = synth.layout_resnet50()
+        seed = 2 if name == "c2" else 3
+        scales = synth.tensor_scales(len(off) - 1, seed)
+        rng = np.random.default_rng(seed)
+        if name == "c2":
+            grads = [synth.gaussian_grads(off, scales, rng) for _ in range(8)]
+            return dict(off=off, grads=grads, W=1, density=density or 1e-3,
+                        desc="resnet50-shaped 25,557,032 fp32 params in 161 tensors, 1 worker: "
+                             "worker_step + server_push + server_pull per step")
+        rho = density or 1e-3
+        sizes = np.diff(off.astype(np.int64))
+        counts = np.ceil(rho * sizes.astype(np.float64)).astype(np.int64)
+        payloads = [synth.sparse_payload(off, counts, scales, rng) for _ in range(32)]
+        order = synth.event_schedule(32, 4096, 3)
+        return dict(off=off, payloads=payloads, order=order, W=32, density=rho,
+                    desc="server stress: 25,557,032-param model, 32 workers' difference rows, "
+                         "step = server_push of a pooled payload + server_pull of a seeded worker")
+    if name == "c5":
+        off = synth.layout_equal(1_000_000_000, 64)
+        scales = synth.tensor_scales(64, 5)
+        rng = np.random.default_rng(5)
+        grads = [synth.tiled_gaussian_grads(off, scales, rng) for _ in range(2)]
+        return dict(off=off, grads=grads, W=1, density=density or 1e-4,
+                    desc="1e9 fp32 params in 64 equal tensors, 1 worker: worker_step + "
+                         "server_push + server_pull per step")
+    raise SystemExit(f"unknown workload {name}")
 
 
-def cpu_baseline(off, grads, steps=2):
-    """The oracle as it stands, single thread, on the first `steps` steps of the
-    same workload."""
+def cpu_baseline(wl, name, budget_s=20.0):
+    """The oracle as it stands, single thread, on the first steps of the same
+    workload (as many as fit in about `budget_s` seconds, at least one)."""
     from oracle import dgs_oracle as oracle
+    off = wl["off"]
     n = int(off[-1])
-    state = np.zeros(n, np.float32)
-    model = np.zeros(n, np.float32)
-    diff = np.zeros((1, n), np.float32)
+    rho = wl["density"]
     oracle.lib()
+    model = np.zeros(n, np.float32)
+    steps = 0
     t0 = time.perf_counter()
-    for t in range(steps):
-        i, v = oracle.worker_step(grads[t % POOL], state, off, LR, np.float32(MOMENTUM), DENSITY)
-        oracle.server_push(model, diff, i, v)
-        oracle.server_pull(diff, 0, off, DENSITY)
+    if name == "c3":
+        diff = np.zeros((wl["W"], n), np.float32)
+        while True:
+            i, v = wl["payloads"][steps % len(wl["payloads"])]
+            oracle.server_push(model, diff, i, v)
+            oracle.server_pull(diff, int(wl["order"][steps]), off, rho)
+            steps += 1
+            if time.perf_counter() - t0 > budget_s * 0.5 or steps >= 64:
+                break
+        what = "events (push + pull)"
+    else:
+        state = np.zeros(n, np.float32)
+        diff = np.zeros((1, n), np.float32)
+        while True:
+            g = wl["grads"][steps % len(wl["grads"])]
+            i, v = oracle.worker_step(g, state, off, LR, np.float32(MOMENTUM), rho)
+            oracle.server_push(model, diff, i, v)
+            oracle.server_pull(diff, 0, off, rho)
+            steps += 1
+            if time.perf_counter() - t0 > budget_s * 0.5 or steps >= 16:
+                break
+        what = "steps (worker_step + push + pull)"
     dt = time.perf_counter() - t0
     return {"value": n * steps / dt, "unit": "params/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {steps} steps of the same workload (worker_step + push + pull), {dt:.1f} s"}
+            "sample": f"first {steps} {what} of the same workload, {dt:.1f} s on one host core"}
 
 
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=100)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5"])
+    ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--force-exact", action="store_true", help="time the non-predicted two-pass path")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run 20 elementwise copies of one 25,557,032-float tensor and exit "
+                         "(known traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
+    name = args.workload
+    steps = args.steps if args.steps is not None else (20 if name == "c5" else 200)
+    warmup = args.warmup if args.warmup is not None else (12 if name == "c5" else 40)
 
     import torch
     from paper_1910_10929_amd import dgs
@@ -83,91 +135,118 @@ def main():
     dgs.lib()                       # no fallback: fails if libdgs.so is missing
     assert torch.cuda.is_available(), "bench.py needs an MI355X"
     dev = "cuda:0"
-    off, grads = make_workload()
+    if args.calibrate_copy:
+        src = torch.randn(25_557_032, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(20):
+            torch.mul(src, 1.0, out=dst)      # reads 102,228,128 B, writes 102,228,128 B
+        torch.cuda.synchronize()
+        print(json.dumps({"calibrate_copy": {"launches": 20, "read_bytes": src.numel() * 4,
+                                             "write_bytes": src.numel() * 4}}))
+        return
+    wl = make_workload(name, args.density)
+    off = wl["off"]
     n = int(off[-1])
     J = len(off) - 1
+    W = wl["W"]
+    rho = wl["density"]
 
-    ctx = dgs.Context(off, W=1, device=dev)
+    ctx = dgs.Context(off, W=W, device=dev)
     if args.force_exact:
         ctx.set_option(dgs.OPT_FORCE_EXACT, 1)
-    K = ctx.nnz(DENSITY)
-    g_dev = [torch.from_numpy(g).to(dev) for g in grads]
-    state = torch.zeros(n, dtype=torch.float32, device=dev)
+    K = ctx.nnz(rho)
     model = torch.zeros(n, dtype=torch.float32, device=dev)
-    diff = torch.zeros((1, n), dtype=torch.float32, device=dev)
+    diff = torch.zeros((W, n), dtype=torch.float32, device=dev)
     ctx.server_attach(diff)
-    idx = torch.zeros(K, dtype=torch.int32, device=dev)
-    val = torch.zeros(K, dtype=torch.float32, device=dev)
     pidx = torch.zeros(K, dtype=torch.int32, device=dev)
     pval = torch.zeros(K, dtype=torch.float32, device=dev)
 
-    def step(t):
-        ctx.worker_step(g_dev[t % POOL], state, LR, MOMENTUM, DENSITY, idx, val)
-        ctx.server_push(model, 0, idx, val, K)
-        ctx.server_pull(0, DENSITY, pidx, pval)
+    if name == "c3":
+        pay = [(torch.from_numpy(i.view(np.int32)).to(dev), torch.from_numpy(v).to(dev), i.size)
+               for i, v in wl["payloads"]]
+        order = [int(x) for x in wl["order"]]
+
+        def step(t):
+            i, v, nn = pay[t % len(pay)]
+            w = order[t % len(order)]
+            ctx.server_push(model, w, i, v, nn)
+            ctx.server_pull(w, rho, pidx, pval)
+        dominant, dom_kind, dom_bytes = "k_stream<ident,collect> (dgs_server_pull streaming pass)", dgs.PROF_PULL_STREAM, 4.0 * n
+        step_bytes = (8.0 * K + 8.0 * (W + 1) * K) + (4.0 * n + 12.0 * K)
+    else:
+        g_dev = [torch.from_numpy(g).to(dev) for g in wl["grads"]]
+        state = torch.zeros(n, dtype=torch.float32, device=dev)
+        idx = torch.zeros(K, dtype=torch.int32, device=dev)
+        val = torch.zeros(K, dtype=torch.float32, device=dev)
+
+        def step(t):
+            ctx.worker_step(g_dev[t % len(g_dev)], state, LR, MOMENTUM, rho, idx, val)
+            ctx.server_push(model, 0, idx, val, K)
+            ctx.server_pull(0, rho, pidx, pval)
+        dominant, dom_kind, dom_bytes = "k_stream<fma,collect> (dgs_worker_step streaming pass)", dgs.PROF_WORKER_STREAM, 12.0 * n
+        step_bytes = (12.0 * n + 12.0 * K) + (8.0 * K + 8.0 * (W + 1) * K) + (4.0 * n + 12.0 * K)
 
     t = 0
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         step(t)
         t += 1
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         step(t)
         t += 1
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    ms_per_step = dt / args.steps * 1e3
+    ms_per_step = dt / steps * 1e3
 
-    # per-kernel durations, HIP events on the context's stream, same workload continuing
+    # per-kernel durations: HIP events on the context's stream, same workload continuing
     ctx.set_option(dgs.OPT_PROFILE, 1)
-    prof_steps = min(args.steps, 200)
-    for _ in range(prof_steps):
+    for _ in range(min(steps, 200)):
         step(t)
         t += 1
     torch.cuda.synchronize()
     kinds = {"worker_stream": dgs.PROF_WORKER_STREAM, "worker_select": dgs.PROF_WORKER_SELECT,
              "pull_stream": dgs.PROF_PULL_STREAM, "pull_select": dgs.PROF_PULL_SELECT,
-             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA}
-    kernel_us = {}
-    for name, kind in kinds.items():
+             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA, "event_pair": dgs.PROF_EMPTY}
+    kernel_us, dom_us = {}, None
+    for kname, kind in kinds.items():
         cnt, ms = ctx.profile_read(kind)
-        kernel_us[name] = (ms / cnt * 1e3) if cnt else None
+        kernel_us[kname] = round(ms / cnt * 1e3, 2) if cnt else None
+        if kind == dom_kind and cnt:
+            dom_us = ms / cnt * 1e3
     ctx.set_option(dgs.OPT_PROFILE, 0)
     st = ctx.stats()
 
-    # roofline of the dominant kernel: 12 B per parameter (read grad, read state, write state)
-    alg_bytes = 12.0 * n
-    ws_us = kernel_us["worker_stream"]
-    achieved = alg_bytes / (ws_us * 1e-6) / 1e9 if ws_us else None
-    roofline = {"bound": "hbm", "kernel": "k_stream<fma,collect> (dgs_worker_step streaming pass)",
+    # an event pair with nothing between its records still measures a few microseconds:
+    # take that bracket cost off the dominant kernel's bracketed time
+    raw_us = dom_us
+    if dom_us and kernel_us.get("event_pair"):
+        dom_us = dom_us - kernel_us["event_pair"]
+    achieved = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us else None
+    roofline = {"bound": "hbm", "kernel": dominant,
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
-                "traffic": MEASURED_TRAFFIC_BYTES, "algorithmic_bytes": alg_bytes,
-                "avg_launch_us": ws_us}
+                "traffic": MEASURED_TRAFFIC_BYTES[name], "algorithmic_bytes": dom_bytes,
+                "avg_launch_us": dom_us, "avg_bracketed_us": raw_us}
 
     out = {
         "metric": "params/sec and HBM GB/s (% of peak) for dgs_worker_step + server push/pull",
-        "value": n * args.steps / dt,
+        "value": n * steps / dt,
         "unit": "params/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": ms_per_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f32", "data": "synthetic",
-        "config": {"workload": "resnet50-shaped 25,557,032 fp32 params in 161 tensors, density 1e-3, "
-                               "1 worker: worker_step + server_push + server_pull per step",
-                   "n": n, "tensors": J, "density": DENSITY, "K": K, "workers": 1,
+        "config": {"workload": f"{name}: {wl['desc']}, density {rho:g}",
+                   "n": n, "tensors": J, "density": rho, "K": K, "workers": W,
                    "momentum": MOMENTUM, "path": "exact" if args.force_exact else "predicted"},
         "roofline": roofline,
         "kernel_us": kernel_us,
-        "step_algorithmic_GBs": (12.0 * n + 12.0 * K + 8.0 * K + 16.0 * K + 4.0 * n + 12.0 * K) / (dt / args.steps) / 1e9,
+        "step_algorithmic_GBs": step_bytes / (dt / steps) / 1e9,
         "stats": {"exact_calls": st.exact_calls, "fallback_tensors": st.fallback_tensors,
                   "internal_errors": st.internal_errors},
     }
-    if not args.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(off, grads)
-    else:
-        out["cpu_baseline"] = None
+    out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(wl, name)
     ctx.close()
     print(json.dumps(out))
 

@@ -57,7 +57,8 @@ enum {
     DGS_PROF_PULL_SELECT = 3,
     DGS_PROF_PUSH = 4,
     DGS_PROF_EXACT_EXTRA = 5,   /* histogram pick + second pass of the non-predicted path */
-    DGS_PROF_KINDS = 6
+    DGS_PROF_EMPTY = 6,         /* an event pair with nothing in between: the bracket's own cost */
+    DGS_PROF_KINDS = 7
 };
 
 typedef struct dgs_stats {

@@ -151,7 +151,9 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
         out[j].k = (uint32_t)k;
         out[j].k2 = (uint32_t)k2;
         out[j].outoff = (uint32_t)K;
-        out[j].pad = 0;
+        uint64_t k2p = 2 * k + 4ull * isqrt_u32((uint32_t)k) + 16;
+        if (k2p > nj) k2p = nj;
+        out[j].k2_pull = (uint32_t)k2p;
         K += k;
     }
     *K_out = K;
@@ -294,6 +296,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         ProfScope ps(c, prof_select);
         launch_select(op_select, se, c->J, c->stream);
     }
+    if (c->profile) { ProfScope empty(c, DGS_PROF_EMPTY); }
     if (!dense_req) c->hint_density[hint_set] = density;
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;

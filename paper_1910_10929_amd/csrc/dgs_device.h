@@ -41,7 +41,7 @@ struct PlanEntry {
     uint32_t k;       // ceil(density * n_j)
     uint32_t k2;      // rank whose key becomes the next predicted threshold (>= k, <= n_j)
     uint32_t outoff;  // sum of k over earlier tensors
-    uint32_t pad;
+    uint32_t k2_pull; // same for a pull, whose sent entries vanish: about 2k (<= n_j)
 };
 
 struct DevStats {

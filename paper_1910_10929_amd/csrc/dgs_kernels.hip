@@ -176,7 +176,9 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *_
                     if (bigB) tt = (int)tB;
                 }
                 if (tt < 0) continue;
-                const uint32_t bin = (__float_as_uint(a[r][j]) & 0x7FFFFFFFu) >> HSHIFT;
+                const uint32_t key = __float_as_uint(a[r][j]) & 0x7FFFFFFFu;
+                if (key == 0) continue;            // zeros (often the bulk of a difference row) are implied
+                const uint32_t bin = key >> HSHIFT;
                 if (tt == cur) atomicAdd(&lhist[bin], 1u);
                 else atomicAdd(&A.ghist[(size_t)tt * HBINS + bin], 1u);
             }
@@ -357,10 +359,13 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
     find_ranks<HBINS, 4>(h, pe.k2, pe.k, rowsum, res);
     if (threadIdx.x == 0) {
         const int b2 = res[0], b1 = res[2];
+        // the histogram holds the nonzero keys only: a rank beyond its total means
+        // "fewer nonzeros than that", and every nonzero is collected
         uint32_t t;
-        if (b2 < 0 || b1 < 0) {
-            atomicAdd(&stats->internal_errors, 1ull);
+        if (b2 < 0 && b1 < 0) {
             t = 1;
+        } else if (b2 < 0) {
+            t = (b1 > 0) ? (1u << HSHIFT) : 1u;
         } else if (b2 > 0) {
             t = (uint32_t)b2 << HSHIFT;
         } else if (b1 > 0) {
@@ -410,6 +415,7 @@ struct SelShared {
     uint32_t wsum[SEL_WAVES];
     uint32_t rowsum[64];
     int res[4];
+    uint32_t kmin;
 };
 
 // Count into an LDS histogram.  With AGG, lanes of a wavefront that hit the same
@@ -643,26 +649,22 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
     if (run_sel != k && tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
 }
 
-// What one thread fetches for one tile before it knows the tile's count.
-struct TileFetch {
-    uint32_t w;      // count word
-    uint4 p[4];      // candidate slots 0..7 (one 64-byte line)
-};
-
-__device__ __forceinline__ TileFetch fetch_tile(const uint32_t *__restrict__ tile_cnt,
-                                                const uint2 *__restrict__ slots, uint32_t t, bool valid)
+// Minimum over the 64 lanes of a wavefront (DPP, same pattern as the scan);
+// the result is valid in lane 63.
+__device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
 {
-    TileFetch f;
-    f.w = 0;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) f.p[i] = make_uint4(0, 0, 0, 0);
-    if (valid) {
-        f.w = tile_cnt[t];
-        const uint4 *sp = (const uint4 *)(slots + (size_t)t * CAPT);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) f.p[i] = sp[i];
-    }
-    return f;
+    int x = (int)v;
+    const int id = (int)0xFFFFFFFFu;
+#define DGS_MIN_STEP(ctrl, rmask)                                                             \
+    x = (int)min((uint32_t)x, (uint32_t)__builtin_amdgcn_update_dpp(id, x, ctrl, rmask, 0xf, false))
+    DGS_MIN_STEP(0x111, 0xf);
+    DGS_MIN_STEP(0x112, 0xf);
+    DGS_MIN_STEP(0x114, 0xf);
+    DGS_MIN_STEP(0x118, 0xf);
+    DGS_MIN_STEP(0x142, 0xa);
+    DGS_MIN_STEP(0x143, 0xc);
+#undef DGS_MIN_STEP
+    return (uint32_t)x;
 }
 
 // Ordered-list entry: LDS while it fits, global scratch beyond.
@@ -672,12 +674,21 @@ __device__ __forceinline__ void put_entry(uint2 *llist, uint2 *glist, uint32_t p
     else glist[pos] = e;
 }
 
-constexpr uint32_t SEL_BATCH = 3;   // chunks of SEL_THREADS tiles whose loads are issued together
+constexpr uint32_t SEL_BATCH = 3;                               // chunks of SEL_THREADS tiles per batch
+constexpr uint32_t SEL_BATCH_TILES = SEL_BATCH * SEL_THREADS;   // 3072
+constexpr uint32_t SEL_QUADS = SEL_THREADS / 4;                 // groups of 4 lanes, one tile each
+constexpr uint32_t SEL_COPY_ITERS = SEL_BATCH_TILES / SEL_QUADS;
 
 // One workgroup per tensor.  Big tensors: join the per-tile candidate slots into
 // one ordered list (LDS; lists that outgrow it continue in global scratch), then
 // select.  Small tensors, dense requests and failed predictions: select straight
 // from the state buffer.
+//
+// Joining: the first 64-byte line of every tile's slots (8 candidates) is fetched
+// by 4 cooperating lanes before the counts are known; the counts are fetched one
+// tile per thread (coalesced), scanned into list positions, and the lanes then
+// drop their two entries into place.  Tiles with more than 8 candidates, and a
+// first tile shared with the previous tensor, take a per-tile loop.
 template <int OP>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                                                         const uint32_t *__restrict__ tile_cnt,
@@ -685,6 +696,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
 {
     __shared__ SelShared S;
     __shared__ uint2 llist[SEL_LDS_LIST];
+    __shared__ uint32_t tpos[SEL_BATCH_TILES];   // per tile of the batch: position in the list
+    __shared__ uint32_t tcw[SEL_BATCH_TILES];    // per tile of the batch: count | first slot << 16
     const uint32_t j = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const TensorDesc td = A.tdesc[j];
@@ -694,56 +707,92 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
     bool dense = (!td.big) || A.force_dense;
     uint32_t c = 0;
+    uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
     uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
+    if (tid == 0) S.kmin = 0xFFFFFFFFu;
 
     if (!dense) {
-        // ---- one tile per thread and chunk; the loads of SEL_BATCH chunks are in flight together
         const uint32_t ntl = thi - tlo + 1;
+        const uint32_t ql = tid >> 2, sub = tid & 3u;
         uint32_t ovf = 0;
-        for (uint32_t cb = 0; cb < ntl; cb += SEL_BATCH * SEL_THREADS) {
-            TileFetch f[SEL_BATCH];
+        for (uint32_t cb = 0; cb < ntl; cb += SEL_BATCH_TILES) {
+            // first line of every tile of the batch, 4 lanes per tile
+            uint4 pf[SEL_COPY_ITERS];
+#pragma unroll
+            for (uint32_t it = 0; it < SEL_COPY_ITERS; ++it) {
+                const uint32_t tl = cb + it * SEL_QUADS + ql;
+                pf[it] = make_uint4(0, 0, 0, 0);
+                if (tl < ntl) pf[it] = ((const uint4 *)(slots + (size_t)(tlo + tl) * CAPT))[sub];
+            }
+            // counts, one tile per thread and chunk
+            uint32_t w[SEL_BATCH];
 #pragma unroll
             for (uint32_t u = 0; u < SEL_BATCH; ++u) {
-                const uint32_t t = tlo + cb + u * SEL_THREADS + tid;
-                f[u] = fetch_tile(tile_cnt, slots, t, t <= thi);
+                const uint32_t tl = cb + u * SEL_THREADS + tid;
+                w[u] = (tl < ntl) ? tile_cnt[tlo + tl] : 0u;
             }
 #pragma unroll
             for (uint32_t u = 0; u < SEL_BATCH; ++u) {
                 if (cb + u * SEL_THREADS >= ntl) break;      // uniform
-                const uint32_t t = tlo + cb + u * SEL_THREADS + tid;
-                uint32_t w = f[u].w;
-                if (w == CNT_OVERFLOW) { ovf = 1; w = 0; }
-                const bool hs = head_shared && (t == tlo);
-                const uint32_t cnt = hs ? (w >> 16) : (w & 0xFFFFu);
-                const uint32_t start = hs ? (w & 0xFFFFu) : 0u;
+                const uint32_t tl = cb + u * SEL_THREADS + tid;
+                uint32_t ww = w[u];
+                if (ww == CNT_OVERFLOW) { ovf = 1; ww = 0; }
+                const bool hs = head_shared && (tl == 0);
+                const uint32_t cnt = hs ? (ww >> 16) : (ww & 0xFFFFu);
+                const uint32_t start = hs ? (ww & 0xFFFFu) : 0u;
                 uint32_t ctot;
                 const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
-                if (cnt != 0) {
-                    const uint2 *sl = slots + (size_t)t * CAPT + start;
-                    uint32_t i0 = 0;
-                    if (start == 0) {
+                tpos[u * SEL_THREADS + tid] = pos;
+                tcw[u * SEL_THREADS + tid] = cnt | (start << 16);
+                c += ctot;
+            }
+            __syncthreads();
+            // entries into place
 #pragma unroll
-                        for (uint32_t i = 0; i < 4; ++i) {
-                            if (2 * i < cnt) put_entry(llist, glist, pos + 2 * i, make_uint2(f[u].p[i].x, f[u].p[i].y));
-                            if (2 * i + 1 < cnt) put_entry(llist, glist, pos + 2 * i + 1, make_uint2(f[u].p[i].z, f[u].p[i].w));
-                        }
-                        i0 = 8;
+            for (uint32_t it = 0; it < SEL_COPY_ITERS; ++it) {
+                const uint32_t li = it * SEL_QUADS + ql;
+                const uint32_t tl = cb + li;
+                if (tl >= ntl) continue;
+                const uint32_t cw = tcw[li];
+                const uint32_t cnt = cw & 0xFFFFu, start = cw >> 16;
+                const uint32_t pos = tpos[li];
+                if (cnt == 0) continue;
+                uint32_t i0 = 0;
+                if (start == 0) {
+                    if (2 * sub < cnt) {
+                        put_entry(llist, glist, pos + 2 * sub, make_uint2(pf[it].x, pf[it].y));
+                        kmin = min(kmin, pf[it].y & 0x7FFFFFFFu);
                     }
+                    if (2 * sub + 1 < cnt) {
+                        put_entry(llist, glist, pos + 2 * sub + 1, make_uint2(pf[it].z, pf[it].w));
+                        kmin = min(kmin, pf[it].w & 0x7FFFFFFFu);
+                    }
+                    i0 = 8;
+                }
+                if (sub == 0 && i0 < cnt) {
                     // the rest of a crowded tile, four independent loads at a time
+                    const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT + start;
                     for (uint32_t i = i0; i < cnt; i += 4) {
                         uint2 e[4];
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) e[v] = (i + v < cnt) ? sl[i + v] : make_uint2(0, 0);
 #pragma unroll
-                        for (uint32_t v = 0; v < 4; ++v)
-                            if (i + v < cnt) put_entry(llist, glist, pos + i + v, e[v]);
+                        for (uint32_t v = 0; v < 4; ++v) {
+                            if (i + v < cnt) {
+                                put_entry(llist, glist, pos + i + v, e[v]);
+                                kmin = min(kmin, e[v].y & 0x7FFFFFFFu);
+                            }
+                        }
                     }
                 }
-                c += ctot;
             }
+            __syncthreads();   // tpos / tcw are reused by the next batch
         }
+        kmin = wave_min_to_last(kmin);
+        if (lane_id() == 63) atomicMin(&S.kmin, kmin);
         const bool any_ovf = __syncthreads_or((int)ovf) != 0;   // also orders the list writes
+        kmin = S.kmin;
         if (any_ovf || c < pe.k) dense = true;
         if (!dense && c > SEL_LDS_LIST) {
             // the list outgrew LDS: complete the global copy
@@ -763,16 +812,25 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     // ---- rank whose key becomes the next predicted threshold
     uint32_t R = 0;
     if (td.big && A.write_hint) {
-        float d = 1.0f;     // growth of the tail count since the threshold was set
-        const uint32_t E = A.hint2[j];
-        if (!dense && !A.exact_mode && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
-        R = (uint32_t)((float)pe.k2 / d);
-        const uint32_t rmin = max(1u, pe.k / 4u);
-        R = min(max(R, rmin), td.n);
+        if (OP == SEL_WORKER) {
+            // sent entries stay large (they keep m * a), so the tail above a fixed key grows
+            // from step to step: scale the rank by the growth seen since the hint was set
+            float d = 1.0f;
+            const uint32_t E = A.hint2[j];
+            if (!dense && !A.exact_mode && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
+            R = (uint32_t)((float)pe.k2 / d);
+            const uint32_t rmin = max(1u, pe.k / 4u);
+            R = min(max(R, rmin), td.n);
+        } else {
+            // sent entries become zero: even with no new update before the next pull,
+            // k entries must remain above the hinted key
+            R = pe.k2_pull;
+        }
     }
 
     uint32_t tau_next = 0, expect = 0;
-    const uint32_t win_base = (tau_cur & 0x7FFFFFFFu) >> 11;
+    // every candidate key is >= kmin (>= the collection threshold): the window starts there
+    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (kmin >> 11);
     if (dense) {
         if (td.n <= 2 * SEL_LDS_LIST) {
             uint32_t *lv = (uint32_t *)llist;
@@ -796,10 +854,15 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     if (td.big && A.write_hint && tid == 0) {
         uint32_t tn = tau_next;
         if (tn == 0) {
-            // rank R was not among the candidates: relax the current threshold by a quarter
+            // rank R was not among the candidates: relax the current threshold by a quarter,
+            // but not below half of the smallest candidate (all of them already pass)
             const float f = __uint_as_float(tau_cur & 0x7FFFFFFFu) * 0.75f;
             tn = __float_as_uint(f) & 0x7FFFFFFFu;
             if (!(tau_cur > 1u) || tn == 0) tn = 1;
+            if (!dense && kmin != 0xFFFFFFFFu && kmin < 0x7F800000u) {
+                const uint32_t half = __float_as_uint(__uint_as_float(kmin) * 0.5f) & 0x7FFFFFFFu;
+                if (half > tn) tn = half;
+            }
             expect = 0;
         }
         if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;   // keep the hint finite

@@ -111,6 +111,22 @@ def gaussian_grads(offsets: np.ndarray, scales, rng: np.random.Generator) -> np.
     return x
 
 
+def tiled_gaussian_grads(offsets: np.ndarray, scales, rng: np.random.Generator,
+                         bases: int = 4, shift: int = 1009) -> np.ndarray:
+    """Gaussian gradients for very large layouts of equal tensors: `bases` seeded
+    N(0,1) blocks of one tensor's size, rotated by `shift * j` and scaled per
+    tensor.  Keeps host generation of 1e9 values to seconds."""
+    J = len(offsets) - 1
+    nj = int(offsets[1] - offsets[0])
+    assert all(int(offsets[j + 1] - offsets[j]) == nj for j in range(J))
+    blocks = [rng.standard_normal(nj, dtype=np.float32) for _ in range(bases)]
+    g = np.empty(J * nj, np.float32)
+    for j in range(J):
+        s = np.float32(1.0 if scales is None else scales[j])
+        np.multiply(np.roll(blocks[j % bases], shift * j), s, out=g[j * nj:(j + 1) * nj])
+    return g
+
+
 def student_t_grads(offsets: np.ndarray, scales, rng: np.random.Generator,
                     nu: float = 3.0) -> np.ndarray:
     """Heavy-tailed gradients: scale_j * t_nu."""

@@ -111,17 +111,6 @@ def test_c4_transformer_shapes_heavy_tails(oracle):
     ctx.close()
 
 
-def _billion_grads(scales, rng):
-    """64 tensors of 15,625,000 Gaussian values each: four seeded base blocks,
-    rotated and scaled per tensor (keeps host generation to seconds)."""
-    nj = 15_625_000
-    bases = [rng.standard_normal(nj, dtype=np.float32) for _ in range(4)]
-    g = np.empty(64 * nj, np.float32)
-    for j in range(64):
-        np.multiply(np.roll(bases[j % 4], 1009 * j), np.float32(scales[j]), out=g[j * nj:(j + 1) * nj])
-    return g
-
-
 @pytest.mark.parametrize("rho,K", [(1e-4, 100_032), (1e-2, 10_000_000)])
 def test_c5_one_billion_parameters(oracle, rho, K):
     """Config 5: 1e9 parameters in 64 equal tensors.  The oracle follows three
@@ -133,7 +122,7 @@ def test_c5_one_billion_parameters(oracle, rho, K):
     nj = 15_625_000
     scales = synth.tensor_scales(64, 5)
     rng = np.random.default_rng(5)
-    g = _billion_grads(scales, rng)
+    g = synth.tiled_gaussian_grads(off, scales, rng)
     ctx = dgs.Context(off, W=0)
     assert ctx.nnz(rho) == K
     w = Worker(ctx, density_max=rho)
