@@ -199,7 +199,8 @@ def main():
     dt = time.perf_counter() - t0
     ms_per_step = dt / steps * 1e3
 
-    # per-kernel durations: HIP events on the context's stream, same workload continuing
+    # per-kernel durations: HIP events attached to each kernel dispatch (begin to end of the
+    # kernel) on the context's stream, same workload continuing
     ctx.set_option(dgs.OPT_PROFILE, 1)
     for _ in range(min(steps, 200)):
         step(t)
@@ -207,7 +208,7 @@ def main():
     torch.cuda.synchronize()
     kinds = {"worker_stream": dgs.PROF_WORKER_STREAM, "worker_select": dgs.PROF_WORKER_SELECT,
              "pull_stream": dgs.PROF_PULL_STREAM, "pull_select": dgs.PROF_PULL_SELECT,
-             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA, "event_pair": dgs.PROF_EMPTY}
+             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA}
     kernel_us, dom_us = {}, None
     for kname, kind in kinds.items():
         cnt, ms = ctx.profile_read(kind)
@@ -217,17 +218,12 @@ def main():
     ctx.set_option(dgs.OPT_PROFILE, 0)
     st = ctx.stats()
 
-    # an event pair with nothing between its records still measures a few microseconds:
-    # take that bracket cost off the dominant kernel's bracketed time
-    raw_us = dom_us
-    if dom_us and kernel_us.get("event_pair"):
-        dom_us = dom_us - kernel_us["event_pair"]
     achieved = dom_bytes / (dom_us * 1e-6) / 1e9 if dom_us else None
     roofline = {"bound": "hbm", "kernel": dominant,
                 "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                 "frac": (achieved / HBM_PEAK_GBS) if achieved else None,
                 "traffic": MEASURED_TRAFFIC_BYTES[name], "algorithmic_bytes": dom_bytes,
-                "avg_launch_us": dom_us, "avg_bracketed_us": raw_us}
+                "avg_launch_us": dom_us}
 
     out = {
         "metric": "params/sec and HBM GB/s (% of peak) for dgs_worker_step + server push/pull",

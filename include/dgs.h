@@ -43,7 +43,7 @@ enum {
 /* Options for dgs_set_option(). */
 enum {
     DGS_OPT_FORCE_EXACT = 1, /* 1: never use the previous step's threshold as a prediction */
-    DGS_OPT_PROFILE = 2,     /* 1: bracket the kernels of each call with HIP events */
+    DGS_OPT_PROFILE = 2,     /* 1: attach start/stop HIP events to the kernels of each call */
     DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
     DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */
     DGS_OPT_STREAM_QUADS = 5 /* 4096-element groups per workgroup of the streaming kernel */
@@ -56,9 +56,8 @@ enum {
     DGS_PROF_PULL_STREAM = 2,   /* candidate pass over one difference row */
     DGS_PROF_PULL_SELECT = 3,
     DGS_PROF_PUSH = 4,
-    DGS_PROF_EXACT_EXTRA = 5,   /* histogram pick + second pass of the non-predicted path */
-    DGS_PROF_EMPTY = 6,         /* an event pair with nothing in between: the bracket's own cost */
-    DGS_PROF_KINDS = 7
+    DGS_PROF_EXACT_EXTRA = 5,   /* second (collecting) pass of the non-predicted path */
+    DGS_PROF_KINDS = 6
 };
 
 typedef struct dgs_stats {
@@ -192,9 +191,10 @@ int dgs_get_stats(dgs_ctx *ctx, dgs_stats *out /*host*/);
 
 /*
  * With DGS_OPT_PROFILE on: waits for the stream, then reports, for kernel class
- * `kind`, how many launches were bracketed since the last read and their summed
- * duration in milliseconds (HIP events on the context's stream); resets that
- * class.  At most 4096 launches per class are kept between reads.
+ * `kind`, how many launches were timed since the last read and their summed
+ * duration in milliseconds (HIP events attached to each kernel dispatch on the
+ * context's stream: begin to end of the kernel); resets that class.  At most
+ * 4096 launches per class are kept between reads.
  */
 int dgs_profile_read(dgs_ctx *ctx, int kind, uint64_t *launches /*host*/, double *total_ms /*host*/);
 

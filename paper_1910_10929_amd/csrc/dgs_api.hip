@@ -40,7 +40,7 @@ Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
     const size_t ntiles = (size_t)((n + TILE - 1) / TILE);
     Layout L;
     size_t o = 0;
-    L.tile_desc = o; o = align_up(o + ntiles * sizeof(uint4));
+    L.tile_desc = o; o = align_up(o + ((size_t)J + 1) * sizeof(uint32_t));   // tensor offsets
     L.tdesc = o;     o = align_up(o + (size_t)J * sizeof(TensorDesc));
     L.plans = o;     o = align_up(o + (size_t)NPLAN * J * sizeof(PlanEntry));
     L.tau = o;       o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
@@ -80,7 +80,7 @@ struct dgs_ctx {
     char *ws = nullptr;
     Layout L{};
     // device views
-    uint4 *tile_desc = nullptr;
+    uint32_t *toff = nullptr;
     TensorDesc *tdesc = nullptr;
     PlanEntry *plans = nullptr;
     uint32_t *tau = nullptr;
@@ -109,12 +109,12 @@ struct dgs_ctx {
 
 namespace {
 
-struct ProfScope {     // brackets launches with events when profiling is on
+// Event pair for one timed kernel launch (null events when profiling is off or full).
+struct ProfSlot {
     dgs_ctx *c;
     int kind;
-    bool on = false;
-    uint32_t slot = 0;
-    ProfScope(dgs_ctx *ctx, int k) : c(ctx), kind(k)
+    hipEvent_t ev0 = nullptr, ev1 = nullptr;
+    ProfSlot(dgs_ctx *ctx, int k) : c(ctx), kind(k)
     {
         if (!c->profile) return;
         ProfClass &p = c->prof[kind];
@@ -126,15 +126,10 @@ struct ProfScope {     // brackets launches with events when profiling is on
             p.start.push_back(a);
             p.stop.push_back(b);
         }
-        slot = p.used;
-        on = (hipEventRecord(p.start[slot], c->stream) == hipSuccess);
+        ev0 = p.start[p.used];
+        ev1 = p.stop[p.used];
     }
-    ~ProfScope()
-    {
-        if (!on) return;
-        ProfClass &p = c->prof[kind];
-        if (hipEventRecord(p.stop[slot], c->stream) == hipSuccess) p.used = slot + 1;
-    }
+    void launched() { if (ev0) ++c->prof[kind].used; }
 };
 
 // k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
@@ -239,7 +234,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     StreamArgs sa{};
     sa.grad = grad;
     sa.state = state;
-    sa.tile_desc = c->tile_desc;
+    sa.toff = c->toff;
+    sa.J = c->J;
     sa.tau = tau;
     sa.tile_cnt = c->tile_cnt;
     sa.slots = c->slots;
@@ -251,29 +247,33 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
 
     if (dense_req) {
         if (op_stream == OP_FMA) {
-            ProfScope ps(c, prof_stream);
+            ProfSlot ps(c, prof_stream);
             const uint32_t blocks = stream_blocks(c, MODE_PLAIN, &sa.quads_per_block);
-            launch_stream(OP_FMA, MODE_PLAIN, vec, sa, blocks, c->stream);
+            launch_stream(OP_FMA, MODE_PLAIN, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
+            ps.launched();
         }
     } else if (exact) {
         ++c->exact_calls;
         {
-            ProfScope ps(c, prof_stream);
+            ProfSlot ps(c, prof_stream);
             const uint32_t blocks = stream_blocks(c, MODE_HIST, &sa.quads_per_block);
-            launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream);
+            launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
+            ps.launched();
         }
         {
-            ProfScope ps(c, DGS_PROF_EXACT_EXTRA);
             launch_pick(c->tdesc, plan, c->ghist, tau, c->stats, c->J, c->stream);
+            ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
             StreamArgs sb = sa;
             sb.grad = nullptr;
             const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sb.quads_per_block);
-            launch_stream(OP_IDENT, MODE_COLLECT, aligned16(state), sb, blocks, c->stream);
+            launch_stream(OP_IDENT, MODE_COLLECT, aligned16(state), sb, blocks, c->stream, ps.ev0, ps.ev1);
+            ps.launched();
         }
     } else {
-        ProfScope ps(c, prof_stream);
+        ProfSlot ps(c, prof_stream);
         const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sa.quads_per_block);
-        launch_stream(op_stream, MODE_COLLECT, vec, sa, blocks, c->stream);
+        launch_stream(op_stream, MODE_COLLECT, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
+        ps.launched();
     }
 
     SelectArgs se{};
@@ -293,10 +293,10 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.force_dense = dense_req ? 1u : 0u;
     se.write_hint = dense_req ? 0u : 1u;
     {
-        ProfScope ps(c, prof_select);
-        launch_select(op_select, se, c->J, c->stream);
+        ProfSlot ps(c, prof_select);
+        launch_select(op_select, se, c->J, c->stream, ps.ev0, ps.ev1);
+        ps.launched();
     }
-    if (c->profile) { ProfScope empty(c, DGS_PROF_EMPTY); }
     if (!dense_req) c->hint_density[hint_set] = density;
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;
@@ -333,7 +333,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->offsets.assign(offsets, offsets + J + 1);
     c->ws = (char *)workspace;
     c->L = L;
-    c->tile_desc = (uint4 *)(c->ws + L.tile_desc);
+    c->toff = (uint32_t *)(c->ws + L.tile_desc);
     c->tdesc = (TensorDesc *)(c->ws + L.tdesc);
     c->plans = (PlanEntry *)(c->ws + L.plans);
     c->tau = (uint32_t *)(c->ws + L.tau);
@@ -366,28 +366,12 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
         td[j].pad = 0;
         for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
     }
-    std::vector<uint4> tiles(c->ntiles);
-    {
-        uint32_t j = 0;
-        for (uint32_t t = 0; t < c->ntiles; ++t) {
-            const uint64_t first = (uint64_t)t * TILE;
-            uint64_t last = first + TILE - 1;
-            if (last >= c->n) last = c->n - 1;
-            while (offsets[j + 1] <= first) ++j;
-            uint32_t jb = j;
-            while (offsets[jb + 1] <= last) ++jb;
-            uint4 d;
-            d.x = j | (td[j].big ? 0x80000000u : 0u);
-            d.y = jb | (td[jb].big ? 0x80000000u : 0u);
-            d.z = (jb != j) ? (uint32_t)offsets[j + 1] : 0xFFFFFFFFu;
-            d.w = (jb != j) ? (uint32_t)offsets[jb] : 0xFFFFFFFFu;
-            tiles[t] = d;
-        }
-    }
+    std::vector<uint32_t> toff(J + 1);
+    for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)offsets[j];
 
     bool ok = true;
     ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemcpyAsync(c->tile_desc, tiles.data(), tiles.size() * sizeof(uint4), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    ok = ok && hipMemcpyAsync(c->toff, toff.data(), toff.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tdesc, td.data(), td.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tau, tau0.data(), tau0.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     if (ok) {
@@ -480,8 +464,9 @@ int dgs_server_push(dgs_ctx *c, float *model, uint32_t worker_id, const uint32_t
     }
     ++c->calls_push;
     {
-        ProfScope ps(c, DGS_PROF_PUSH);
-        launch_push(model, c->diff, c->W, c->n, idx, val, (uint32_t)nnz, c->stream);
+        ProfSlot ps(c, DGS_PROF_PUSH);
+        launch_push(model, c->diff, c->W, c->n, idx, val, (uint32_t)nnz, c->stream, ps.ev0, ps.ev1);
+        if (nnz && c->W + (model ? 1u : 0u) > 0) ps.launched();
     }
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;

@@ -58,12 +58,12 @@ enum SelectOp { SEL_WORKER = 0, SEL_PULL = 1 };
 struct StreamArgs {
     const float *grad;            // OP_FMA only
     float *state;                 // OP_FMA: in/out.  OP_IDENT: read only.
-    const uint4 *tile_desc;       // per tile: leading tensor, trailing tensor (bit 31: big), end of leading part, begin of trailing part
+    const uint32_t *toff;         // J + 1 tensor offsets (elements)
     const uint32_t *tau;          // per tensor: candidate threshold (TAU_NEVER for small tensors)
     uint32_t *tile_cnt;           // per tile: low 16 = candidates of the leading tensor part, high 16 = trailing part
     uint2 *slots;                 // per tile CAPT x (index, value bits)
     uint32_t *ghist;              // per tensor HBINS counters
-    uint32_t n, ntiles, nquads, quads_per_block;
+    uint32_t n, ntiles, nquads, quads_per_block, J;
     float lr;
 };
 
@@ -86,12 +86,14 @@ struct SelectArgs {
 };
 
 // Host-callable launchers (defined next to the kernels).
-void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream);
+// ev0 / ev1: optional hipEvent_t recorded at the begin / end of the kernel (both or neither).
+void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream,
+                   void *ev0, void *ev1);
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
                  DevStats *stats, uint32_t J, void *stream);
-void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream);
+void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1);
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
-                 const float *val, uint32_t nnz, void *stream);
+                 const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1);
 void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t *flag, void *stream);
 void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream);

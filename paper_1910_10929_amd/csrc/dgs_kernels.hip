@@ -11,6 +11,7 @@
 //                   and the state fix-up of Eq. 12.
 // Push / apply    : atomic-free sparse scatter (Algorithm 2, "M <- M - decode(g)").
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include "dgs_device.h"
 
 namespace dgs {
@@ -50,8 +51,47 @@ __device__ __forceinline__ void flush_hist(uint32_t *lhist, uint32_t *ghist, int
     __syncthreads();
 }
 
+// Which tensors does a span [first, last] of the flat buffer touch?  Binary search
+// in the tensor offsets (uniform addresses: scalar loads that stay in the scalar
+// cache), so that no per-tile table has to be fetched from HBM.
+//   x = tensor of `first` (bit 31: that tensor is big), y = tensor of `last` (bit 31: big),
+//   z = end of the leading tensor part (0xFFFFFFFF when the span lies inside one tensor),
+//   w = begin of the trailing tensor part (0xFFFFFFFF when there is none)
+__device__ __forceinline__ uint32_t find_tensor(const uint32_t *__restrict__ toff, uint32_t lo,
+                                                uint32_t hi, uint32_t e)
+{
+    // largest j in [lo, hi) with toff[j] <= e
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (toff[mid] <= e) lo = mid;
+        else hi = mid;
+    }
+    return lo;
+}
+
+__device__ __forceinline__ uint4 span_desc(const uint32_t *__restrict__ toff, uint32_t J,
+                                           uint32_t first, uint32_t last)
+{
+    const uint32_t tA = find_tensor(toff, 0, J, first);
+    const uint32_t offA = toff[tA], endA = toff[tA + 1];
+    uint4 d;
+    d.x = tA | ((endA - offA > SMALL_N) ? 0x80000000u : 0u);
+    if (last < endA) {
+        d.y = d.x;
+        d.z = 0xFFFFFFFFu;
+        d.w = 0xFFFFFFFFu;
+    } else {
+        const uint32_t tB = find_tensor(toff, tA + 1, J, last);
+        const uint32_t offB = toff[tB], endB = toff[tB + 1];
+        d.y = tB | ((endB - offB > SMALL_N) ? 0x80000000u : 0u);
+        d.z = endA;
+        d.w = offB;
+    }
+    return d;
+}
+
 template <int OP, int MODE, bool VEC>
-__device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *__restrict__ tile_desc,
+__device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t *__restrict__ toff,
                                              const uint32_t *__restrict__ tau, uint32_t t,
                                              uint32_t *lhist, int cur)
 {
@@ -59,13 +99,9 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *_
     const uint32_t base = t * TILE;
     const bool full = (base + TILE <= A.n);
 
-    // Tile descriptor first: its (scalar) load overlaps the vector loads below.
-    //   x = tensor of the first element (bit 31: that tensor is big)
-    //   y = tensor of the last valid element (bit 31: big)
-    //   z = end of the leading tensor part (0xFFFFFFFF when the tile lies inside one tensor)
-    //   w = begin of the trailing tensor part (0xFFFFFFFF when there is none)
+    // Tensors touched by this tile: scalar work that overlaps the vector loads below.
     uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
-    if (MODE != MODE_PLAIN) d = tile_desc[t];
+    if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, min(base + TILE, A.n) - 1u);
 
     float a[4][4];
     if (VEC && full) {
@@ -126,19 +162,29 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *_
         const uint32_t tauB = (begB != 0xFFFFFFFFu) ? tau[tB] : TAU_NEVER;
         uint2 *myslots = A.slots + (size_t)t * CAPT;
         uint32_t run = 0, runA = 0;
+        const bool simple = full && !straddle;     // wave-uniform: one tensor, no ragged end
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
             const uint32_t e0 = base + r * 256 + lane * 4;
             bool f[4];
             uint64_t mk[4];
+            if (simple) {
+                // two VALU operations per element: clear the sign, compare into a lane mask
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t e = e0 + j;
-                const uint32_t key = __float_as_uint(a[r][j]) & 0x7FFFFFFFu;
-                uint32_t thr = tauA;
-                if (straddle) thr = (e < endA) ? tauA : ((e >= begB) ? tauB : TAU_NEVER);
-                f[j] = (key >= thr) && (full || e < A.n);
-                mk[j] = ballot64(f[j]);
+                for (int j = 0; j < 4; ++j) {
+                    f[j] = (__float_as_uint(a[r][j]) & 0x7FFFFFFFu) >= tauA;
+                    mk[j] = ballot64(f[j]);
+                }
+            } else {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t e = e0 + j;
+                    const uint32_t key = __float_as_uint(a[r][j]) & 0x7FFFFFFFu;
+                    uint32_t thr = tauA;
+                    if (straddle) thr = (e < endA) ? tauA : ((e >= begB) ? tauB : TAU_NEVER);
+                    f[j] = (key >= thr) && (full || e < A.n);
+                    mk[j] = ballot64(f[j]);
+                }
             }
             const uint64_t any = mk[0] | mk[1] | mk[2] | mk[3];
             if (any != 0) {
@@ -188,7 +234,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint4 *_
 
 template <int OP, int MODE, bool VEC>
 __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
-                                                           const uint4 *__restrict__ tile_desc,
+                                                           const uint32_t *__restrict__ toff,
                                                            const uint32_t *__restrict__ tau)
 {
     __shared__ uint32_t lhist[MODE == MODE_HIST ? HBINS : 1];
@@ -203,7 +249,8 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
     for (uint32_t q = q0; q < q1; ++q) {
         if (MODE == MODE_HIST) {
             // the LDS histogram belongs to the big tensor the quad starts in
-            const uint32_t fx = tile_desc[q * WAVES_PER_BLOCK].x;
+            const uint32_t qfirst = q * WAVES_PER_BLOCK * TILE;
+            const uint32_t fx = span_desc(toff, A.J, qfirst, qfirst).x;
             const int qt = (fx >> 31) ? (int)(fx & 0x7FFFFFFFu) : -1;
             if (qt != cur) {
                 flush_hist<MODE>(lhist, A.ghist, cur);
@@ -211,33 +258,45 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
             }
         }
         const uint32_t t = q * WAVES_PER_BLOCK + wave;
-        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, tile_desc, tau, t, lhist, cur);
+        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, toff, tau, t, lhist, cur);
     }
     flush_hist<MODE>(lhist, A.ghist, cur);
 }
 
-template <int OP, int MODE>
-static void launch_stream_t(bool vec, const StreamArgs &a, uint32_t blocks, hipStream_t st)
+// Plain launch, or a launch whose begin and end are stamped into two events.
+template <class K, class... Args>
+static void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t st, void *ev0, void *ev1, Args... args)
 {
-    if (vec)
-        hipLaunchKernelGGL((k_stream<OP, MODE, true>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a,
-                           a.tile_desc, a.tau);
+    if (ev0 && ev1)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, (hipEvent_t)ev0, (hipEvent_t)ev1, 0, args...);
     else
-        hipLaunchKernelGGL((k_stream<OP, MODE, false>), dim3(blocks), dim3(STREAM_THREADS), 0, st, a,
-                           a.tile_desc, a.tau);
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
 }
 
-void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream)
+template <int OP, int MODE>
+static void launch_stream_t(bool vec, const StreamArgs &a, uint32_t blocks, hipStream_t st, void *ev0,
+                            void *ev1)
+{
+    if (vec)
+        launch_k(k_stream<OP, MODE, true>, dim3(blocks), dim3(STREAM_THREADS), st, ev0, ev1, a,
+                 a.toff, a.tau);
+    else
+        launch_k(k_stream<OP, MODE, false>, dim3(blocks), dim3(STREAM_THREADS), st, ev0, ev1, a,
+                 a.toff, a.tau);
+}
+
+void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream,
+                   void *ev0, void *ev1)
 {
     hipStream_t st = (hipStream_t)stream;
     if (blocks == 0) return;
     if (op == OP_FMA) {
-        if (mode == MODE_PLAIN) launch_stream_t<OP_FMA, MODE_PLAIN>(vec, a, blocks, st);
-        else if (mode == MODE_COLLECT) launch_stream_t<OP_FMA, MODE_COLLECT>(vec, a, blocks, st);
-        else launch_stream_t<OP_FMA, MODE_HIST>(vec, a, blocks, st);
+        if (mode == MODE_PLAIN) launch_stream_t<OP_FMA, MODE_PLAIN>(vec, a, blocks, st, ev0, ev1);
+        else if (mode == MODE_COLLECT) launch_stream_t<OP_FMA, MODE_COLLECT>(vec, a, blocks, st, ev0, ev1);
+        else launch_stream_t<OP_FMA, MODE_HIST>(vec, a, blocks, st, ev0, ev1);
     } else {
-        if (mode == MODE_COLLECT) launch_stream_t<OP_IDENT, MODE_COLLECT>(vec, a, blocks, st);
-        else if (mode == MODE_HIST) launch_stream_t<OP_IDENT, MODE_HIST>(vec, a, blocks, st);
+        if (mode == MODE_COLLECT) launch_stream_t<OP_IDENT, MODE_COLLECT>(vec, a, blocks, st, ev0, ev1);
+        else if (mode == MODE_HIST) launch_stream_t<OP_IDENT, MODE_HIST>(vec, a, blocks, st, ev0, ev1);
     }
 }
 
@@ -871,13 +930,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     }
 }
 
-void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream)
+void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1)
 {
     hipStream_t st = (hipStream_t)stream;
     if (op == SEL_WORKER)
-        hipLaunchKernelGGL(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), 0, st, a, a.tile_cnt, a.slots);
+        launch_k(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.slots);
     else
-        hipLaunchKernelGGL(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), 0, st, a, a.tile_cnt, a.slots);
+        launch_k(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.slots);
 }
 
 // ---------------------------------------------------------------------------
@@ -900,7 +959,7 @@ __global__ __launch_bounds__(256) void k_push(float *model, float *diff, uint32_
 }
 
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
-                 const float *val, uint32_t nnz, void *stream)
+                 const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1)
 {
     if (nnz == 0) return;
     const uint32_t first = model ? 0u : 1u;
@@ -909,8 +968,10 @@ void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32
     // gridDim.y is limited to 65535: loop over slabs of buffers
     for (uint32_t b0 = 0; b0 < bufs; b0 += 32768) {
         const uint32_t nb = (bufs - b0 < 32768u) ? (bufs - b0) : 32768u;
-        hipLaunchKernelGGL(k_push, dim3((nnz + 255) / 256, nb), dim3(256), 0, (hipStream_t)stream,
-                           model, diff, n, idx, val, nnz, first + b0);
+        // events time the first slab only (one slab unless there are more than 32768 buffers)
+        launch_k(k_push, dim3((nnz + 255) / 256, nb), dim3(256), (hipStream_t)stream,
+                 b0 == 0 ? ev0 : nullptr, b0 == 0 ? ev1 : nullptr, model, diff, n, idx, val, nnz,
+                 first + b0);
     }
 }
 

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "libdgs.so")
 DGS_OK = 0
 DGS_EINVAL, DGS_ENOMEM, DGS_ENOTSUP, DGS_ECAPACITY, DGS_EHIP = -1, -2, -3, -4, -5
 OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS = 1, 2, 3, 4, 5
-PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA, PROF_EMPTY = range(7)
+PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA = range(6)
 
 EXPORTS = [
     "dgs_workspace_bytes", "dgs_create", "dgs_destroy", "dgs_nnz", "dgs_worker_step",
