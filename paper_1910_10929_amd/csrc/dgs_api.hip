@@ -22,7 +22,7 @@ constexpr uint32_t MAX_PROF = 4096;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
-    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, slots, ord, stats, flag, total;
+    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, heads, slots, ord, stats, flag, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -47,6 +47,7 @@ Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
     L.hint2 = o;     o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
     L.ghist = o;     o = align_up(o + (size_t)J * HBINS * sizeof(uint32_t));
     L.tile_cnt = o;  o = align_up(o + (ntiles + 4) * sizeof(uint32_t));
+    L.heads = o;     o = align_up(o + ntiles * HEAD * sizeof(uint2));
     L.slots = o;     o = align_up(o + ntiles * CAPT * sizeof(uint2));
     L.ord = o;       o = align_up(o + (ntiles + J) * CAPT * sizeof(uint2));
     L.stats = o;     o = align_up(o + sizeof(DevStats));
@@ -87,6 +88,7 @@ struct dgs_ctx {
     uint32_t *hint2 = nullptr;
     uint32_t *ghist = nullptr;
     uint32_t *tile_cnt = nullptr;
+    uint2 *heads = nullptr;
     uint2 *slots = nullptr;
     uint2 *ord = nullptr;
     DevStats *stats = nullptr;
@@ -238,6 +240,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     sa.J = c->J;
     sa.tau = tau;
     sa.tile_cnt = c->tile_cnt;
+    sa.heads = c->heads;
     sa.slots = c->slots;
     sa.ghist = c->ghist;
     sa.n = c->n;
@@ -282,6 +285,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.plan = plan;
     se.tau = tau;
     se.tile_cnt = c->tile_cnt;
+    se.heads = c->heads;
     se.slots = c->slots;
     se.ord = c->ord;
     se.hint2 = c->hint2 + (size_t)hint_set * c->J;
@@ -340,6 +344,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->hint2 = (uint32_t *)(c->ws + L.hint2);
     c->ghist = (uint32_t *)(c->ws + L.ghist);
     c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
+    c->heads = (uint2 *)(c->ws + L.heads);
     c->slots = (uint2 *)(c->ws + L.slots);
     c->ord = (uint2 *)(c->ws + L.ord);
     c->stats = (DevStats *)(c->ws + L.stats);

@@ -11,6 +11,11 @@ constexpr uint32_t TILE = 1024;
 // Candidate slots reserved per tile.  A tile that would need more marks itself
 // overflowed and its tensors are re-selected densely.
 constexpr uint32_t CAPT = 256;
+// The first HEAD candidates of every tile live in one 64-byte line of a dense
+// array (tile t at heads[HEAD * t]), so that the selection kernel fetches a
+// tensor's candidates with contiguous loads; candidate p >= HEAD of a crowded
+// tile goes to slots[CAPT * t + p].
+constexpr uint32_t HEAD = 8;
 constexpr uint32_t WAVES_PER_BLOCK = 4;            // one "quad" = 4 tiles = 4096 elements
 constexpr uint32_t STREAM_THREADS = 64 * WAVES_PER_BLOCK;
 // Tensors up to this size are selected directly from the state buffer by one
@@ -61,7 +66,8 @@ struct StreamArgs {
     const uint32_t *toff;         // J + 1 tensor offsets (elements)
     const uint32_t *tau;          // per tensor: candidate threshold (TAU_NEVER for small tensors)
     uint32_t *tile_cnt;           // per tile: low 16 = candidates of the leading tensor part, high 16 = trailing part
-    uint2 *slots;                 // per tile CAPT x (index, value bits)
+    uint2 *heads;                 // per tile HEAD x (index, value bits): candidates 0 .. HEAD-1
+    uint2 *slots;                 // per tile CAPT x (index, value bits): candidates HEAD .. CAPT-1
     uint32_t *ghist;              // per tensor HBINS counters
     uint32_t n, ntiles, nquads, quads_per_block, J;
     float lr;
@@ -73,6 +79,7 @@ struct SelectArgs {
     const PlanEntry *plan;
     uint32_t *tau;                // hints of this stream, updated
     const uint32_t *tile_cnt;
+    const uint2 *heads;
     const uint2 *slots;
     uint2 *ord;                   // ordered candidates of tensor j start at CAPT * (first tile + j)
     uint32_t *hint2;              // per tensor: candidates expected at the hinted threshold (0 = unknown)

@@ -160,6 +160,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
     if (MODE == MODE_COLLECT) {
         const uint32_t tauA = tau[tA];
         const uint32_t tauB = (begB != 0xFFFFFFFFu) ? tau[tB] : TAU_NEVER;
+        uint2 *myheads = A.heads + (size_t)t * HEAD;
         uint2 *myslots = A.slots + (size_t)t * CAPT;
         uint32_t run = 0, runA = 0;
         const bool simple = full && !straddle;     // wave-uniform: one tensor, no ragged end
@@ -192,7 +193,9 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
 #pragma unroll
                 for (int j = 0; j < 4; ++j) {
                     if (f[j]) {
-                        if (p < CAPT) myslots[p] = make_uint2(e0 + j, __float_as_uint(a[r][j]));
+                        const uint2 ent = make_uint2(e0 + j, __float_as_uint(a[r][j]));
+                        if (p < HEAD) myheads[p] = ent;
+                        else if (p < CAPT) myslots[p] = ent;
                         ++p;
                     }
                 }
@@ -751,6 +754,7 @@ constexpr uint32_t SEL_COPY_ITERS = SEL_BATCH_TILES / SEL_QUADS;
 template <int OP>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                                                         const uint32_t *__restrict__ tile_cnt,
+                                                        const uint2 *__restrict__ heads,
                                                         const uint2 *__restrict__ slots)
 {
     __shared__ SelShared S;
@@ -782,7 +786,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
             for (uint32_t it = 0; it < SEL_COPY_ITERS; ++it) {
                 const uint32_t tl = cb + it * SEL_QUADS + ql;
                 pf[it] = make_uint4(0, 0, 0, 0);
-                if (tl < ntl) pf[it] = ((const uint4 *)(slots + (size_t)(tlo + tl) * CAPT))[sub];
+                if (tl < ntl) pf[it] = ((const uint4 *)(heads + (size_t)(tlo + tl) * HEAD))[sub];
             }
             // counts, one tile per thread and chunk
             uint32_t w[SEL_BATCH];
@@ -827,15 +831,20 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                         put_entry(llist, glist, pos + 2 * sub + 1, make_uint2(pf[it].z, pf[it].w));
                         kmin = min(kmin, pf[it].w & 0x7FFFFFFFu);
                     }
-                    i0 = 8;
+                    i0 = HEAD;
                 }
                 if (sub == 0 && i0 < cnt) {
                     // the rest of a crowded tile, four independent loads at a time
-                    const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT + start;
+                    // (entry q of the tile: heads for q < HEAD, slots beyond)
+                    const uint2 *hd = heads + (size_t)(tlo + tl) * HEAD;
+                    const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT;
                     for (uint32_t i = i0; i < cnt; i += 4) {
                         uint2 e[4];
 #pragma unroll
-                        for (uint32_t v = 0; v < 4; ++v) e[v] = (i + v < cnt) ? sl[i + v] : make_uint2(0, 0);
+                        for (uint32_t v = 0; v < 4; ++v) {
+                            const uint32_t q = start + i + v;
+                            e[v] = (i + v < cnt) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
+                        }
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) {
                             if (i + v < cnt) {
@@ -934,9 +943,10 @@ void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *
 {
     hipStream_t st = (hipStream_t)stream;
     if (op == SEL_WORKER)
-        launch_k(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.slots);
+        launch_k(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads,
+                 a.slots);
     else
-        launch_k(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.slots);
+        launch_k(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads, a.slots);
 }
 
 // ---------------------------------------------------------------------------
