@@ -99,21 +99,27 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
     const uint32_t base = t * TILE;
     const bool full = (base + TILE <= A.n);
 
-    // Tensors touched by this tile: scalar work that overlaps the vector loads below.
-    uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
-    if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, min(base + TILE, A.n) - 1u);
-
+    // Issue the tile's vector loads first; the scalar search for the tensors touched by
+    // the tile then runs while they are in flight.
     float a[4][4];
-    if (VEC && full) {
-        f32x4 s[4];
+    f32x4 g[4], s[4];
+    const bool fast = VEC && full;
+    if (fast) {
         if (OP == OP_FMA) {
-            f32x4 g[4];
 #pragma unroll
             for (int r = 0; r < 4; ++r)
                 g[r] = __builtin_nontemporal_load((const f32x4 *)(A.grad + base + r * 256 + lane * 4));
+        }
 #pragma unroll
-            for (int r = 0; r < 4; ++r)
-                s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
+        for (int r = 0; r < 4; ++r)
+            s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
+    }
+
+    uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
+    if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, min(base + TILE, A.n) - 1u);
+
+    if (fast) {
+        if (OP == OP_FMA) {
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 f32x4 o;
@@ -125,9 +131,6 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
                 *(f32x4 *)(A.state + base + r * 256 + lane * 4) = o;
             }
         } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
 #pragma unroll
             for (int r = 0; r < 4; ++r)
 #pragma unroll
