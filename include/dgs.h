@@ -46,7 +46,10 @@ enum {
     DGS_OPT_PROFILE = 2,     /* 1: attach start/stop HIP events to the kernels of each call */
     DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
     DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */
-    DGS_OPT_STREAM_QUADS = 5 /* 4096-element groups per workgroup of the streaming kernel */
+    DGS_OPT_STREAM_QUADS = 5,/* 4096-element groups per workgroup of the streaming kernel */
+    DGS_OPT_SEGMENTED = 6    /* selection of large tensors by the multi-workgroup kernels:
+                                0 automatic (by tensor size and density), 1 every tensor of at
+                                least 65536 elements, 2 never */
 };
 
 /* Kernel classes reported by dgs_profile_read(). */
@@ -57,7 +60,9 @@ enum {
     DGS_PROF_PULL_SELECT = 3,
     DGS_PROF_PUSH = 4,
     DGS_PROF_EXACT_EXTRA = 5,   /* second (collecting) pass of the non-predicted path */
-    DGS_PROF_KINDS = 6
+    DGS_PROF_WORKER_SEGMENTED = 6, /* multi-workgroup selection kernels, first begin to last end */
+    DGS_PROF_PULL_SEGMENTED = 7,
+    DGS_PROF_KINDS = 8
 };
 
 typedef struct dgs_stats {
@@ -67,6 +72,7 @@ typedef struct dgs_stats {
     uint64_t fallback_elems;   /* elements re-read by those */
     uint64_t candidates;       /* candidates collected by streaming passes */
     uint64_t internal_errors;  /* must stay 0 */
+    uint64_t segmented_tensors; /* tensors resolved by the multi-workgroup selection kernels */
 } dgs_stats;
 
 /*

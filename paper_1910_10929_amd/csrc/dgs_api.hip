@@ -22,7 +22,8 @@ constexpr uint32_t MAX_PROF = 4096;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
-    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, heads, slots, ord, stats, flag, total;
+    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, heads, slots, ord, stats, flag;
+    size_t segtab, segcnt, segG1, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -35,9 +36,25 @@ bool check_offsets(const uint64_t *offsets, uint32_t J)
     return true;
 }
 
-Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
+// Segments of tensor [off, off + n): its tiles cut into runs of SEG_TILES.
+uint32_t tensor_segments(uint64_t off, uint64_t n)
 {
+    if (n < SEG_MIN_N) return 0;
+    const uint64_t tlo = off / TILE, thi = (off + n - 1) / TILE;
+    const uint64_t nseg = (thi - tlo + 1 + SEG_TILES - 1) / SEG_TILES;
+    return nseg <= SEG_MAX_PER_TENSOR ? (uint32_t)nseg : 0u;
+}
+
+Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
+{
+    const uint64_t n = offsets[J];
     const size_t ntiles = (size_t)((n + TILE - 1) / TILE);
+    size_t nseg_total = 0, ncap = 0;
+    for (uint32_t j = 0; j < J; ++j) {
+        const uint32_t ns = tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+        nseg_total += ns;
+        ncap += ns ? 1 : 0;
+    }
     Layout L;
     size_t o = 0;
     L.tile_desc = o; o = align_up(o + ((size_t)J + 1) * sizeof(uint32_t));   // tensor offsets
@@ -52,6 +69,12 @@ Layout make_layout(uint64_t n, uint32_t J, uint32_t W)
     L.ord = o;       o = align_up(o + (ntiles + J) * CAPT * sizeof(uint2));
     L.stats = o;     o = align_up(o + sizeof(DevStats));
     L.flag = o;      o = align_up(o + 64);
+    L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
+    L.segcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
+    L.segG1 = o;     o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
+    L.segOut = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint2));
+    L.segstate = o;  o = align_up(o + (size_t)J * sizeof(SegState));
+    L.pfxlist = o;   o = align_up(o + (ncap * PFX_CAP + 1) * sizeof(uint4));
     L.total = o;
     return L;
 }
@@ -60,6 +83,8 @@ struct PlanSlot {
     bool valid = false;
     double density = 0.0;
     int margin = 0;
+    int seg_mode = 0;
+    uint32_t nseg_active = 0;          // tensors planned as segmented
     uint64_t K = 0;
     uint64_t last_use = 0;
 };
@@ -93,6 +118,13 @@ struct dgs_ctx {
     uint2 *ord = nullptr;
     DevStats *stats = nullptr;
     uint32_t *flag = nullptr;
+    SegDesc *segtab = nullptr;
+    uint32_t *segcnt = nullptr, *segG1 = nullptr;
+    uint2 *segOut = nullptr;
+    SegState *segstate = nullptr;
+    uint4 *pfxlist = nullptr;
+    uint32_t nseg_total = 0;
+    std::vector<uint32_t> nseg;        // per tensor: segments (0 = never segmented)
     float *diff = nullptr;
     // plan cache
     PlanSlot plan_slot[NPLAN];
@@ -103,6 +135,7 @@ struct dgs_ctx {
     // options
     bool force_exact = false, profile = false, validate = false;
     int margin_pct = 50;
+    int seg_mode = SEG_MODE_AUTO;
     uint32_t stream_quads = 0;         // 0 = automatic
     // host counters
     uint64_t calls_worker = 0, calls_pull = 0, calls_push = 0, exact_calls = 0;
@@ -135,9 +168,11 @@ struct ProfSlot {
 };
 
 // k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
-void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out)
+void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out,
+               uint32_t *nseg_active)
 {
     uint64_t K = 0;
+    uint32_t active = 0;
     for (uint32_t j = 0; j < c->J; ++j) {
         const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
         uint64_t k = (uint64_t)std::ceil(density * (double)nj);
@@ -151,8 +186,18 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
         uint64_t k2p = 2 * k + 4ull * isqrt_u32((uint32_t)k) + 16;
         if (k2p > nj) k2p = nj;
         out[j].k2_pull = (uint32_t)k2p;
+        // segmented selection: always for very large tensors, and whenever the candidate
+        // list would not fit the single workgroup's LDS list
+        bool seg = false;
+        if (c->nseg[j] != 0 && density <= DENSE_DENSITY && c->seg_mode != SEG_MODE_NEVER)
+            seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
+                  (k2 > k2p ? k2 : k2p) > SEL_LDS_LIST;
+        out[j].seg = seg ? 1u : 0u;
+        out[j].pad0 = out[j].pad1 = out[j].pad2 = 0;
+        active += seg ? 1u : 0u;
         K += k;
     }
+    *nseg_active = active;
     *K_out = K;
 }
 
@@ -162,7 +207,7 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
     ++c->tick;
     for (uint32_t s = 0; s < NPLAN; ++s) {
         PlanSlot &p = c->plan_slot[s];
-        if (p.valid && p.density == density && p.margin == c->margin_pct) {
+        if (p.valid && p.density == density && p.margin == c->margin_pct && p.seg_mode == c->seg_mode) {
             p.last_use = c->tick;
             *slot_out = s;
             *K_out = p.K;
@@ -181,7 +226,8 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
     }
     PlanEntry *stage = c->plan_stage + (size_t)victim * c->J;
     uint64_t K = 0;
-    fill_plan(c, density, c->margin_pct, stage, &K);
+    uint32_t active = 0;
+    fill_plan(c, density, c->margin_pct, stage, &K, &active);
     if (K >= (1ull << 32)) return DGS_EINVAL;
     if (hipMemcpyAsync(c->plans + (size_t)victim * c->J, stage, (size_t)c->J * sizeof(PlanEntry),
                        hipMemcpyHostToDevice, c->stream) != hipSuccess)
@@ -190,6 +236,8 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
     p.valid = true;
     p.density = density;
     p.margin = c->margin_pct;
+    p.seg_mode = c->seg_mode;
+    p.nseg_active = active;
     p.K = K;
     p.last_use = c->tick;
     *slot_out = victim;
@@ -219,7 +267,7 @@ uint32_t stream_blocks(const dgs_ctx *c, int mode, uint32_t *qpb_out)
 //   op_stream: OP_FMA (worker: grad + state) or OP_IDENT (pull: a difference row)
 int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, float *state, float lr,
                   float m, double density, uint32_t hint_set, uint32_t *idx_out, float *val_out,
-                  uint64_t *nnz_out, int prof_stream, int prof_select)
+                  uint64_t *nnz_out, int prof_stream, int prof_select, int prof_seg)
 {
     uint32_t slot;
     uint64_t K;
@@ -296,6 +344,37 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.m = m;
     se.force_dense = dense_req ? 1u : 0u;
     se.write_hint = dense_req ? 0u : 1u;
+    se.segstate = c->segstate;
+    if (c->plan_slot[slot].nseg_active != 0) {
+        SegArgs sg{};
+        sg.state = state;
+        sg.tdesc = c->tdesc;
+        sg.plan = plan;
+        sg.segtab = c->segtab;
+        sg.tau = tau;
+        sg.hint2 = se.hint2;
+        sg.tile_cnt = c->tile_cnt;
+        sg.heads = c->heads;
+        sg.slots = c->slots;
+        sg.ord = c->ord;
+        sg.whist = c->ghist;
+        sg.segstate = c->segstate;
+        sg.segcnt = c->segcnt;
+        sg.segG1 = c->segG1;
+        sg.segOut = c->segOut;
+        sg.pfxlist = c->pfxlist;
+        sg.out_idx = idx_out;
+        sg.out_val = val_out;
+        sg.stats = c->stats;
+        sg.m = m;
+        sg.write_hint = 1u;
+        sg.exact_mode = exact ? 1u : 0u;
+        sg.nseg_total = c->nseg_total;
+        sg.J = c->J;
+        ProfSlot ps(c, prof_seg);
+        launch_segmented(op_select, sg, c->stream, ps.ev0, ps.ev1);
+        ps.launched();
+    }
     {
         ProfSlot ps(c, prof_select);
         launch_select(op_select, se, c->J, c->stream, ps.ev0, ps.ev1);
@@ -313,7 +392,7 @@ extern "C" {
 size_t dgs_workspace_bytes(const uint64_t *offsets, uint32_t J, uint32_t W)
 {
     if (!check_offsets(offsets, J)) return 0;
-    return make_layout(offsets[J], J, W).total;
+    return make_layout(offsets, J, W).total;
 }
 
 int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, void *workspace,
@@ -323,7 +402,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     *out = nullptr;
     if (!check_offsets(offsets, J) || !workspace) return DGS_EINVAL;
     if (((uintptr_t)workspace & (ALIGN - 1)) != 0) return DGS_EINVAL;
-    const Layout L = make_layout(offsets[J], J, W);
+    const Layout L = make_layout(offsets, J, W);
     if (workspace_bytes < L.total) return DGS_ENOMEM;
 
     dgs_ctx *c = new (std::nothrow) dgs_ctx();
@@ -349,6 +428,12 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->ord = (uint2 *)(c->ws + L.ord);
     c->stats = (DevStats *)(c->ws + L.stats);
     c->flag = (uint32_t *)(c->ws + L.flag);
+    c->segtab = (SegDesc *)(c->ws + L.segtab);
+    c->segcnt = (uint32_t *)(c->ws + L.segcnt);
+    c->segG1 = (uint32_t *)(c->ws + L.segG1);
+    c->segOut = (uint2 *)(c->ws + L.segOut);
+    c->segstate = (SegState *)(c->ws + L.segstate);
+    c->pfxlist = (uint4 *)(c->ws + L.pfxlist);
     c->hint_density.assign((size_t)W + 1, 0.0);
 
     int dev = 0;
@@ -358,17 +443,36 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
         c->cus = prop.multiProcessorCount;
     const char *env = std::getenv("DGS_FORCE_EXACT");
     if (env && env[0] == '1') c->force_exact = true;
+    env = std::getenv("DGS_SEGMENTED");
+    if (env && env[0] >= '0' && env[0] <= '2') c->seg_mode = env[0] - '0';
     env = std::getenv("DGS_STREAM_QUADS");
     if (env) c->stream_quads = (uint32_t)std::strtoul(env, nullptr, 10);
 
     // host-side plan: tensor and tile descriptors
     std::vector<TensorDesc> td(J);
     std::vector<uint32_t> tau0((size_t)(W + 1) * J);
+    std::vector<SegDesc> segs;
+    c->nseg.assign(J, 0u);
+    uint32_t pfx_slots = 0;
     for (uint32_t j = 0; j < J; ++j) {
         td[j].off = (uint32_t)offsets[j];
         td[j].n = (uint32_t)(offsets[j + 1] - offsets[j]);
         td[j].big = td[j].n > SMALL_N ? 1u : 0u;
-        td[j].pad = 0;
+        td[j].pad0 = td[j].pad1 = 0;
+        const uint32_t ns = tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+        td[j].seg_first = (uint32_t)segs.size();
+        td[j].nseg = ns;
+        td[j].pfx_slot = ns ? pfx_slots++ : 0u;
+        c->nseg[j] = ns;
+        const uint32_t tlo = td[j].off / TILE, thi = (td[j].off + td[j].n - 1) / TILE;
+        for (uint32_t sidx = 0; sidx < ns; ++sidx) {
+            SegDesc d;
+            d.j = j;
+            d.tile0 = tlo + sidx * SEG_TILES;
+            d.ntiles = (thi + 1 - d.tile0 < SEG_TILES) ? (thi + 1 - d.tile0) : SEG_TILES;
+            d.sidx = sidx;
+            segs.push_back(d);
+        }
         for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
     }
     std::vector<uint32_t> toff(J + 1);
@@ -379,12 +483,16 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     ok = ok && hipMemcpyAsync(c->toff, toff.data(), toff.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tdesc, td.data(), td.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     ok = ok && hipMemcpyAsync(c->tau, tau0.data(), tau0.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
+    c->nseg_total = (uint32_t)segs.size();
+    if (!segs.empty())
+        ok = ok && hipMemcpyAsync(c->segtab, segs.data(), segs.size() * sizeof(SegDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     if (ok) {
         launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
         launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
         launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
         launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);
         launch_fill_u32(c->flag, 0u, 16, c->stream);
+        launch_fill_u32((uint32_t *)c->segstate, 0u, (size_t)J * sizeof(SegState) / 4, c->stream);
     }
     ok = ok && hipStreamSynchronize(c->stream) == hipSuccess;
     ok = ok && hipGetLastError() == hipSuccess;
@@ -440,7 +548,7 @@ int dgs_worker_step(dgs_ctx *c, const float *grad, float *momentum, float *resid
     if (!aligned4(grad) || !aligned4(state) || !aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
     ++c->calls_worker;
     return run_selection(c, OP_FMA, SEL_WORKER, grad, state, lr, m, density, 0, idx_out, val_out, nnz_out,
-                         DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT);
+                         DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT, DGS_PROF_WORKER_SEGMENTED);
 }
 
 int dgs_server_attach(dgs_ctx *c, float *diff)
@@ -487,7 +595,7 @@ int dgs_server_pull(dgs_ctx *c, uint32_t worker_id, double density, uint32_t *id
     float *row = c->diff + (size_t)worker_id * c->n;
     ++c->calls_pull;
     return run_selection(c, OP_IDENT, SEL_PULL, nullptr, row, 0.0f, 0.0f, density, 1 + worker_id, idx_out,
-                         val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT);
+                         val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT, DGS_PROF_PULL_SEGMENTED);
 }
 
 int dgs_server_pull_all(dgs_ctx *c, uint32_t worker_id, uint32_t *idx_out, float *val_out,
@@ -532,6 +640,10 @@ int dgs_set_option(dgs_ctx *c, int option, int64_t value)
         if (value < 0 || value > 1000) return DGS_EINVAL;
         c->margin_pct = (int)value;
         return DGS_OK;
+    case DGS_OPT_SEGMENTED:
+        if (value < 0 || value > 2) return DGS_EINVAL;
+        c->seg_mode = (int)value;
+        return DGS_OK;
     case DGS_OPT_STREAM_QUADS:
         if (value < 0 || value > (1 << 20)) return DGS_EINVAL;
         c->stream_quads = (uint32_t)value;
@@ -554,6 +666,7 @@ int dgs_get_stats(dgs_ctx *c, dgs_stats *out)
     out->fallback_elems = d.fallback_elems;
     out->candidates = d.candidates;
     out->internal_errors = d.internal_errors;
+    out->segmented_tensors = d.segmented_tensors;
     return DGS_OK;
 }
 

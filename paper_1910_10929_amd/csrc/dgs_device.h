@@ -35,11 +35,29 @@ constexpr uint32_t SEL_LDS_LIST = 8192;            // candidates kept in LDS (64
 // Above this density candidates stop paying off; such requests select densely.
 constexpr double DENSE_DENSITY = 1.0 / 32.0;
 
+// Segmented selection: tensors too large (or requests too dense) for one workgroup
+// are cut into segments of SEG_TILES tiles, and the exact selection runs as a chain
+// of short kernels with one workgroup per segment.
+constexpr uint32_t SEG_TILES = 256;
+constexpr uint32_t SEG_THREADS = 256;
+constexpr uint32_t SEG_MIN_N = 65536;              // smaller tensors never go segmented
+constexpr uint32_t SEG_AUTO_N = 1u << 22;          // tensors this large always do
+constexpr uint32_t SEG_LOWBITS = 12;               // key bits resolved by the second level
+constexpr uint32_t SEG_WBINS = 2048;               // window of key >> SEG_LOWBITS above the threshold
+constexpr uint32_t SEG_LBINS = 1u << SEG_LOWBITS;
+constexpr uint32_t PFX_CAP = 8192;                 // candidates sharing the k-th key's prefix, per tensor
+constexpr uint32_t SEG_MAX_PER_TENSOR = 8192;      // per-segment counters kept in LDS by the ranking kernel
+enum SegStatus { SEG_IDLE = 0, SEG_ACTIVE = 1, SEG_FALLBACK = 2 };
+enum SegMode { SEG_MODE_AUTO = 0, SEG_MODE_ALWAYS = 1, SEG_MODE_NEVER = 2 };
+
 struct TensorDesc {
-    uint32_t off;   // first element
-    uint32_t n;     // elements
-    uint32_t big;   // n > SMALL_N
-    uint32_t pad;
+    uint32_t off;        // first element
+    uint32_t n;          // elements
+    uint32_t big;        // n > SMALL_N
+    uint32_t seg_first;  // first entry of this tensor in the segment table
+    uint32_t nseg;       // segments (0: the tensor never goes segmented)
+    uint32_t pfx_slot;   // which PFX_CAP-sized block of the prefix list belongs to it
+    uint32_t pad0, pad1;
 };
 
 struct PlanEntry {
@@ -47,6 +65,25 @@ struct PlanEntry {
     uint32_t k2;      // rank whose key becomes the next predicted threshold (>= k, <= n_j)
     uint32_t outoff;  // sum of k over earlier tensors
     uint32_t k2_pull; // same for a pull, whose sent entries vanish: about 2k (<= n_j)
+    uint32_t seg;     // 1: segmented selection at this density
+    uint32_t pad0, pad1, pad2;
+};
+
+struct SegDesc {
+    uint32_t j;       // tensor
+    uint32_t tile0;   // first tile (of the flat buffer) of the segment
+    uint32_t ntiles;  // tiles in the segment (<= SEG_TILES)
+    uint32_t sidx;    // index of the segment within its tensor
+};
+
+struct SegState {        // per tensor, rewritten by every segmented selection
+    uint32_t status;     // SegStatus
+    uint32_t pfx;        // key >> SEG_LOWBITS of the k-th entry
+    uint32_t r2;         // its rank among the entries sharing that prefix
+    uint32_t T;          // the k-th key
+    uint32_t pfxcount;   // entries appended to the prefix list
+    uint32_t ovf;        // a tile of the tensor overflowed its candidate slots
+    uint32_t pad0, pad1;
 };
 
 struct DevStats {
@@ -54,6 +91,7 @@ struct DevStats {
     unsigned long long fallback_elems;
     unsigned long long candidates;
     unsigned long long internal_errors;
+    unsigned long long segmented_tensors;
 };
 
 enum StreamOp { OP_FMA = 0, OP_IDENT = 1 };
@@ -90,6 +128,31 @@ struct SelectArgs {
     uint32_t force_dense;         // select every tensor straight from `state`
     uint32_t write_hint;
     uint32_t exact_mode;          // the threshold came from this step's histogram
+    const SegState *segstate;     // tensors planned as segmented are skipped unless they fell back
+};
+
+struct SegArgs {
+    float *state;
+    const TensorDesc *tdesc;
+    const PlanEntry *plan;
+    const SegDesc *segtab;
+    uint32_t *tau;                // hints of this stream, updated
+    uint32_t *hint2;
+    const uint32_t *tile_cnt;
+    const uint2 *heads;
+    const uint2 *slots;
+    uint2 *ord;                   // ordered candidates of a segment start at CAPT * (tile0 + j)
+    uint32_t *whist;              // per tensor HBINS counters, all zero between uses (first SEG_WBINS used)
+    SegState *segstate;
+    uint32_t *segcnt;             // per segment: candidates
+    uint32_t *segG1;              // per segment: candidates with a larger key prefix than the k-th
+    uint2 *segOut;                // per segment: (output position within the tensor, ties to take)
+    uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, segment, 0)
+    uint32_t *out_idx;
+    float *out_val;
+    DevStats *stats;
+    float m;
+    uint32_t write_hint, exact_mode, nseg_total, J;
 };
 
 // Host-callable launchers (defined next to the kernels).
@@ -99,6 +162,8 @@ void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blo
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
                  DevStats *stats, uint32_t J, void *stream);
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1);
+// The five kernels of the segmented selection, in order, on `stream`.
+void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1);
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
                  const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1);
 void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t *flag, void *stream);

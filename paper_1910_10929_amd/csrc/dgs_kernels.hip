@@ -269,11 +269,11 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
     flush_hist<MODE>(lhist, A.ghist, cur);
 }
 
-// Plain launch, or a launch whose begin and end are stamped into two events.
+// Plain launch, or a launch whose begin and / or end is stamped into an event.
 template <class K, class... Args>
 static void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t st, void *ev0, void *ev1, Args... args)
 {
-    if (ev0 && ev1)
+    if (ev0 || ev1)
         hipExtLaunchKernelGGL(kernel, grid, block, 0, st, (hipEvent_t)ev0, (hipEvent_t)ev1, 0, args...);
     else
         hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
@@ -714,6 +714,45 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
     if (run_sel != k && tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
 }
 
+// Rank (from the top) whose key becomes the next predicted threshold.
+//   c: candidates collected at the current threshold, E: candidates that threshold was
+//   expected to collect (0 = unknown); `drift` says whether the two are comparable.
+template <int OP>
+__device__ __forceinline__ uint32_t hint_rank(const TensorDesc &td, const PlanEntry &pe, bool drift,
+                                              uint32_t c, uint32_t E, float m)
+{
+    uint32_t R;
+    if (OP == SEL_WORKER) {
+        // sent entries stay large (they keep m * a), so the tail above a fixed key grows
+        // from step to step: scale the rank by the growth seen since the hint was set
+        float d = 1.0f;
+        if (drift && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
+        // without momentum the sent entries vanish, as in a pull: start from the wider rank
+        R = (uint32_t)((float)(m == 0.0f ? pe.k2_pull : pe.k2) / d);
+        const uint32_t rmin = max(1u, pe.k / 4u);
+        R = min(max(R, rmin), td.n);
+    } else {
+        // sent entries become zero: even with no new update before the next pull,
+        // k entries must remain above the hinted key
+        R = pe.k2_pull;
+    }
+    return R;
+}
+
+// Next threshold when rank R was not among the candidates: relax the current one by a
+// quarter, but not below half of the smallest candidate key (all of them already pass).
+__device__ __forceinline__ uint32_t hint_relaxed(uint32_t tau_cur, uint32_t kmin)
+{
+    const float f = __uint_as_float(tau_cur & 0x7FFFFFFFu) * 0.75f;
+    uint32_t tn = __float_as_uint(f) & 0x7FFFFFFFu;
+    if (!(tau_cur > 1u) || tn == 0) tn = 1;
+    if (kmin != 0xFFFFFFFFu && kmin < 0x7F800000u) {
+        const uint32_t half = __float_as_uint(__uint_as_float(kmin) * 0.5f) & 0x7FFFFFFFu;
+        if (half > tn) tn = half;
+    }
+    return tn;
+}
+
 // Minimum over the 64 lanes of a wavefront (DPP, same pattern as the scan);
 // the result is valid in lane 63.
 __device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
@@ -772,6 +811,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     const uint32_t thi = (td.off + td.n - 1) / TILE;
     const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
     bool dense = (!td.big) || A.force_dense;
+    if (pe.seg) {
+        // planned for the segmented kernels; only a tensor they gave up on is taken here
+        if (A.segstate[j].status != SEG_FALLBACK) return;
+        dense = true;
+    }
     uint32_t c = 0;
     uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
@@ -882,22 +926,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
 
     // ---- rank whose key becomes the next predicted threshold
     uint32_t R = 0;
-    if (td.big && A.write_hint) {
-        if (OP == SEL_WORKER) {
-            // sent entries stay large (they keep m * a), so the tail above a fixed key grows
-            // from step to step: scale the rank by the growth seen since the hint was set
-            float d = 1.0f;
-            const uint32_t E = A.hint2[j];
-            if (!dense && !A.exact_mode && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
-            R = (uint32_t)((float)pe.k2 / d);
-            const uint32_t rmin = max(1u, pe.k / 4u);
-            R = min(max(R, rmin), td.n);
-        } else {
-            // sent entries become zero: even with no new update before the next pull,
-            // k entries must remain above the hinted key
-            R = pe.k2_pull;
-        }
-    }
+    if (td.big && A.write_hint)
+        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, A.hint2[j], A.m);
 
     uint32_t tau_next = 0, expect = 0;
     // every candidate key is >= kmin (>= the collection threshold): the window starts there
@@ -925,21 +955,395 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     if (td.big && A.write_hint && tid == 0) {
         uint32_t tn = tau_next;
         if (tn == 0) {
-            // rank R was not among the candidates: relax the current threshold by a quarter,
-            // but not below half of the smallest candidate (all of them already pass)
-            const float f = __uint_as_float(tau_cur & 0x7FFFFFFFu) * 0.75f;
-            tn = __float_as_uint(f) & 0x7FFFFFFFu;
-            if (!(tau_cur > 1u) || tn == 0) tn = 1;
-            if (!dense && kmin != 0xFFFFFFFFu && kmin < 0x7F800000u) {
-                const uint32_t half = __float_as_uint(__uint_as_float(kmin) * 0.5f) & 0x7FFFFFFFu;
-                if (half > tn) tn = half;
-            }
+            tn = hint_relaxed(tau_cur, dense ? 0xFFFFFFFFu : kmin);
             expect = 0;
         }
         if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;   // keep the hint finite
         A.tau[j] = tn;
         A.hint2[j] = expect;
     }
+}
+
+
+// ---------------------------------------------------------------------------
+// segmented selection: one workgroup per segment of SEG_TILES tiles
+// ---------------------------------------------------------------------------
+//
+//   join    per segment : compact the tiles' candidates into one ordered list and
+//                         count them into the tensor's window histogram
+//                         (key >> 12, counted from the collection threshold)
+//   window  per tensor  : histogram -> 19-bit prefix of the k-th key, next threshold
+//   prefix  per segment : count entries above the prefix, append those sharing it
+//                         to the tensor's prefix list
+//   rank    per tensor  : low 12 bits of the k-th key among the prefix list, then the
+//                         output position and the tie budget of every segment
+//   emit    per segment : ordered emission ("encode()") and the state fix-up
+//
+// A tensor the chain cannot resolve (fewer candidates than k, an overflowed tile,
+// the k-th key beyond the window, a prefix list that outgrows PFX_CAP) is marked
+// SEG_FALLBACK and selected from the state buffer by k_select afterwards.
+
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *wsum, int nw)
+{
+    const uint32_t s = wave_sum(v);
+    __syncthreads();
+    if (lane_id() == 0) wsum[threadIdx.x >> 6] = s;
+    __syncthreads();
+    uint32_t tot = 0;
+    for (int w = 0; w < nw; ++w) tot += wsum[w];
+    return tot;
+}
+
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
+{
+    __shared__ uint32_t h[SEG_WBINS];
+    __shared__ uint32_t tpos[SEG_TILES];
+    __shared__ uint32_t tstart[SEG_TILES];
+    __shared__ uint32_t wsum[SEG_THREADS / 64];
+    const SegDesc sd = A.segtab[blockIdx.x];
+    if (!A.plan[sd.j].seg) return;
+    const TensorDesc td = A.tdesc[sd.j];
+    const uint32_t tid = threadIdx.x;
+    for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) h[b] = 0;
+    const uint32_t tlo = td.off / TILE;
+    const bool head_shared = (td.off % TILE) != 0;
+
+    // this tensor's candidates in every tile of the segment: count and first slot
+    uint32_t cnt = 0, start = 0;
+    int ovf = 0;
+    if (tid < sd.ntiles) {
+        uint32_t ww = A.tile_cnt[sd.tile0 + tid];
+        if (ww == CNT_OVERFLOW) { ovf = 1; ww = 0; }
+        const bool hs = head_shared && (sd.tile0 + tid == tlo);
+        cnt = hs ? (ww >> 16) : (ww & 0xFFFFu);
+        start = hs ? (ww & 0xFFFFu) : 0u;
+    }
+    uint32_t cs;
+    const uint32_t pos = block_excl_scan<SEG_THREADS / 64>(cnt, wsum, cs);
+    tpos[tid] = (tid < sd.ntiles) ? pos : cs;
+    tstart[tid] = start;
+    const bool any_ovf = __syncthreads_or(ovf) != 0;
+
+    uint2 *dst = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    const uint32_t win_base = A.tau[sd.j] >> SEG_LOWBITS;
+    // entry e of the segment: tile = last one whose first position is <= e
+    for (uint32_t eb = 0; eb < cs; eb += 4 * SEG_THREADS) {
+        uint2 ent[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = eb + u * SEG_THREADS + tid;
+            ent[u] = make_uint2(0, 0);
+            if (e < cs) {
+                uint32_t lo = 0, hi = sd.ntiles;
+                while (hi - lo > 1) {
+                    const uint32_t mid = (lo + hi) >> 1;
+                    if (tpos[mid] <= e) lo = mid;
+                    else hi = mid;
+                }
+                const uint32_t q = tstart[lo] + (e - tpos[lo]);
+                const size_t t = (size_t)sd.tile0 + lo;
+                ent[u] = (q < HEAD) ? A.heads[t * HEAD + q] : A.slots[t * CAPT + q];
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = eb + u * SEG_THREADS + tid;
+            if (e < cs) {
+                dst[e] = ent[u];
+                const uint32_t hi12 = (ent[u].y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+                const uint32_t w = (hi12 > win_base) ? (hi12 - win_base) : 0u;
+                atomicAdd(&h[min(w, SEG_WBINS - 1u)], 1u);
+            }
+        }
+    }
+    __syncthreads();
+    uint32_t *gh = A.whist + (size_t)sd.j * HBINS;
+    for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) {
+        const uint32_t v = h[b];
+        if (v) atomicAdd(&gh[b], v);
+    }
+    if (tid == 0) {
+        A.segcnt[blockIdx.x] = cs;
+        if (any_ovf) atomicOr(&A.segstate[sd.j].ovf, 1u);
+    }
+}
+
+template <int OP>
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
+{
+    __shared__ uint32_t h[SEG_WBINS];
+    __shared__ uint32_t rowsum[64];
+    __shared__ int res[4];
+    __shared__ uint32_t wsum[SEG_THREADS / 64];
+    __shared__ uint32_t lowest;
+    const uint32_t j = blockIdx.x;
+    const PlanEntry pe = A.plan[j];
+    if (!pe.seg) return;
+    const TensorDesc td = A.tdesc[j];
+    const uint32_t tid = threadIdx.x;
+    uint32_t *gh = A.whist + (size_t)j * HBINS;
+    uint32_t mine = 0, mylow = 0xFFFFFFFFu;
+    if (tid == 0) lowest = 0xFFFFFFFFu;
+    for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) {
+        const uint32_t v = gh[b];
+        h[b] = v;
+        gh[b] = 0;   // clean for the next use
+        mine += v;
+        if (v && mylow == 0xFFFFFFFFu) mylow = b;
+    }
+    const uint32_t c = block_sum(mine, wsum, SEG_THREADS / 64);
+    if (mylow != 0xFFFFFFFFu) atomicMin(&lowest, mylow);
+    const uint32_t tau_cur = A.tau[j];
+    const uint32_t win_base = tau_cur >> SEG_LOWBITS;
+    uint32_t R = 0;
+    if (A.write_hint) R = hint_rank<OP>(td, pe, !A.exact_mode, c, A.hint2[j], A.m);
+    const bool measurable = (R != 0) && (c >= R);
+    find_ranks<SEG_WBINS, SEG_THREADS / 64>(h, pe.k, measurable ? R : pe.k, rowsum, res);
+    if (tid == 0) {
+        SegState *st = &A.segstate[j];
+        const int bk = res[0], bR = res[2];
+        const bool ok = (st->ovf == 0) && (c >= pe.k) && bk >= 0 && bk < (int)SEG_WBINS - 1;
+        st->ovf = 0;
+        st->pfxcount = 0;
+        st->pfx = win_base + (uint32_t)max(bk, 0);
+        st->r2 = (uint32_t)res[1];
+        st->T = 0;
+        st->status = ok ? SEG_ACTIVE : SEG_FALLBACK;
+        if (!ok) {
+            atomicAdd(&A.stats->fallback_tensors, 1ull);
+            atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+        } else {
+            atomicAdd(&A.stats->candidates, (unsigned long long)c);
+            atomicAdd(&A.stats->segmented_tensors, 1ull);
+            if (A.write_hint) {
+                uint32_t tn = 0, expect = 0;
+                if (measurable && bR >= 0 && bR < (int)SEG_WBINS - 1) {
+                    const uint32_t edge = (win_base + (uint32_t)bR) << SEG_LOWBITS;
+                    tn = edge ? edge : 1u;
+                    expect = R - (uint32_t)res[3] + h[bR];
+                }
+                if (tn == 0) {
+                    const uint32_t kmin = (lowest == 0xFFFFFFFFu) ? 0xFFFFFFFFu
+                                                                 : max((win_base + lowest) << SEG_LOWBITS, tau_cur);
+                    tn = hint_relaxed(tau_cur, kmin);
+                    expect = 0;
+                }
+                if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;
+                A.tau[j] = tn;
+                A.hint2[j] = expect;
+            }
+        }
+    }
+}
+
+constexpr uint32_t PFX_STAGE = 1024;   // entries sharing the prefix that one segment can stage in LDS
+
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
+{
+    __shared__ uint32_t wsum[SEG_THREADS / 64];
+    __shared__ uint2 stage[PFX_STAGE];
+    __shared__ uint32_t nstage, base;
+    const SegDesc sd = A.segtab[blockIdx.x];
+    if (!A.plan[sd.j].seg) return;
+    SegState *st = &A.segstate[sd.j];
+    if (st->status != SEG_ACTIVE) return;
+    const uint32_t pfx = st->pfx;
+    const uint32_t cs = A.segcnt[blockIdx.x];
+    const uint2 *src = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    uint4 *plist = A.pfxlist + (size_t)A.tdesc[sd.j].pfx_slot * PFX_CAP;
+    const uint32_t tid = threadIdx.x;
+    if (tid == 0) nstage = 0;
+    __syncthreads();
+    uint32_t g1 = 0;
+    for (uint32_t eb = 0; eb < cs; eb += 4 * SEG_THREADS) {
+        uint2 ent[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = eb + u * SEG_THREADS + tid;
+            ent[u] = (e < cs) ? src[e] : make_uint2(0, 0);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const uint32_t e = eb + u * SEG_THREADS + tid;
+            if (e < cs) {
+                const uint32_t hi12 = (ent[u].y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+                if (hi12 > pfx) {
+                    ++g1;
+                } else if (hi12 == pfx) {
+                    const uint32_t p = atomicAdd(&nstage, 1u);
+                    if (p < PFX_STAGE) stage[p] = ent[u];
+                }
+            }
+        }
+    }
+    const uint32_t G1 = block_sum(g1, wsum, SEG_THREADS / 64);   // its barriers also complete `stage`
+    const uint32_t ns = nstage;
+    if (tid == 0) {
+        A.segG1[blockIdx.x] = G1;
+        // one reservation per segment in the tensor's prefix list; a segment that could not
+        // stage all of its entries pushes the count past the capacity, which the ranking
+        // kernel turns into a fallback
+        if (ns) base = atomicAdd(&st->pfxcount, ns > PFX_STAGE ? PFX_CAP + 1u : ns);
+    }
+    __syncthreads();
+    if (ns && ns <= PFX_STAGE) {
+        const uint32_t b0 = base;
+        for (uint32_t i = tid; i < ns; i += SEG_THREADS)
+            if (b0 + i < PFX_CAP) plist[b0 + i] = make_uint4(stage[i].x, stage[i].y, sd.sidx, 0u);
+    }
+}
+
+constexpr uint32_t RANK_THREADS = 1024;
+
+__global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
+{
+    __shared__ uint32_t h[SEG_LBINS];
+    __shared__ uint32_t sG[SEG_MAX_PER_TENSOR];
+    __shared__ uint32_t sQ[SEG_MAX_PER_TENSOR];
+    __shared__ uint32_t rowsum[64];
+    __shared__ int res[4];
+    __shared__ uint32_t wsum[RANK_THREADS / 64];
+    const uint32_t j = blockIdx.x;
+    const PlanEntry pe = A.plan[j];
+    if (!pe.seg) return;
+    SegState *st = &A.segstate[j];
+    if (st->status != SEG_ACTIVE) return;
+    const TensorDesc td = A.tdesc[j];
+    const uint32_t tid = threadIdx.x;
+    const uint32_t m = st->pfxcount;
+    const uint32_t r2 = st->r2, pfx = st->pfx;
+    if (m > PFX_CAP || m < r2) {
+        // too many keys share the prefix (or an inconsistent count): leave it to k_select
+        if (tid == 0) {
+            st->status = SEG_FALLBACK;
+            atomicAdd(&A.stats->fallback_tensors, 1ull);
+            atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+            if (m < r2) atomicAdd(&A.stats->internal_errors, 1ull);
+        }
+        return;
+    }
+    const uint4 *plist = A.pfxlist + (size_t)td.pfx_slot * PFX_CAP;
+    for (uint32_t b = tid; b < SEG_LBINS; b += RANK_THREADS) h[b] = 0;
+    for (uint32_t s = tid; s < td.nseg; s += RANK_THREADS) { sG[s] = 0; sQ[s] = 0; }
+    __syncthreads();
+    for (uint32_t p = tid; p < m; p += RANK_THREADS) atomicAdd(&h[plist[p].y & (SEG_LBINS - 1u)], 1u);
+    find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, r2, rowsum, res);
+    const int b3 = res[0];
+    const uint32_t rT = (uint32_t)res[1];   // entries equal to T that are taken, lowest index first
+    if (b3 < 0) {
+        if (tid == 0) {
+            st->status = SEG_FALLBACK;
+            atomicAdd(&A.stats->internal_errors, 1ull);
+        }
+        return;
+    }
+    for (uint32_t p = tid; p < m; p += RANK_THREADS) {
+        const uint4 e = plist[p];
+        const uint32_t low = e.y & (SEG_LBINS - 1u);
+        if (low > (uint32_t)b3) atomicAdd(&sG[e.z], 1u);
+        else if (low == (uint32_t)b3) atomicAdd(&sQ[e.z], 1u);
+    }
+    __syncthreads();
+    // segments in order: ties are taken lowest index first, i.e. earlier segments first
+    uint32_t carry_q = 0, carry_o = 0;
+    for (uint32_t sb = 0; sb < td.nseg; sb += RANK_THREADS) {
+        const uint32_t s = sb + tid;
+        const bool in = s < td.nseg;
+        const uint32_t G = in ? (A.segG1[td.seg_first + s] + sG[s]) : 0u;
+        const uint32_t Q = in ? sQ[s] : 0u;
+        uint32_t totq, toto;
+        const uint32_t qb = carry_q + block_excl_scan<RANK_THREADS / 64>(Q, wsum, totq);
+        const uint32_t take = min(Q, (rT > qb) ? (rT - qb) : 0u);
+        const uint32_t ob = carry_o + block_excl_scan<RANK_THREADS / 64>(G + take, wsum, toto);
+        if (in) A.segOut[td.seg_first + s] = make_uint2(ob, take);
+        carry_q += totq;
+        carry_o += toto;
+    }
+    if (tid == 0) {
+        st->T = (pfx << SEG_LOWBITS) | (uint32_t)b3;
+        if (carry_o != pe.k) atomicAdd(&A.stats->internal_errors, 1ull);
+    }
+}
+
+template <int OP>
+__global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
+{
+    __shared__ uint32_t wsum[SEG_THREADS / 64];
+    const SegDesc sd = A.segtab[blockIdx.x];
+    const PlanEntry pe = A.plan[sd.j];
+    if (!pe.seg) return;
+    const SegState *st = &A.segstate[sd.j];
+    if (st->status != SEG_ACTIVE) return;
+    const uint32_t T = st->T;
+    const uint32_t seg = A.tdesc[sd.j].seg_first + sd.sidx;
+    const uint2 so = A.segOut[seg];
+    const uint32_t cs = A.segcnt[seg];
+    const uint2 *src = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    const uint32_t tid = threadIdx.x;
+    constexpr uint32_t ITEMS = 4;
+    uint32_t run_sel = so.x, run_eq = 0;
+    const uint32_t rT = so.y;
+    for (uint32_t cb = 0; cb < cs; cb += SEG_THREADS * ITEMS) {
+        const uint32_t p0 = cb + tid * ITEMS;
+        uint2 v[ITEMS];
+        uint32_t g = 0, q = 0;
+#pragma unroll
+        for (uint32_t i = 0; i < ITEMS; ++i) v[i] = (p0 + i < cs) ? src[p0 + i] : make_uint2(0, 0);
+#pragma unroll
+        for (uint32_t i = 0; i < ITEMS; ++i) {
+            const uint32_t key = v[i].y & 0x7FFFFFFFu;
+            if (p0 + i < cs) {
+                g += (key > T);
+                q += (key == T);
+            }
+        }
+        uint32_t total;
+        const uint32_t before = block_excl_scan<SEG_THREADS / 64>(g | (q << 16), wsum, total);
+        const uint32_t g_before = before & 0xFFFFu, q_before = before >> 16;
+        const uint32_t G = total & 0xFFFFu, Q = total >> 16;
+        const uint32_t rem = (rT > run_eq) ? (rT - run_eq) : 0u;
+        uint32_t pos = run_sel + g_before + min(q_before, rem);
+        uint32_t eq_seen = q_before;
+        if (g | q) {
+#pragma unroll
+            for (uint32_t i = 0; i < ITEMS; ++i) {
+                if (p0 + i >= cs) break;
+                const uint32_t key = v[i].y & 0x7FFFFFFFu;
+                bool sel = key > T;
+                if (key == T) {
+                    sel = eq_seen < rem;
+                    ++eq_seen;
+                }
+                if (sel) {
+                    if (pos < pe.k) {
+                        A.out_idx[pe.outoff + pos] = v[i].x;
+                        A.out_val[pe.outoff + pos] = __uint_as_float(v[i].y);
+                        A.state[v[i].x] = (OP == SEL_WORKER) ? (A.m * __uint_as_float(v[i].y)) : 0.0f;
+                    }
+                    ++pos;
+                }
+            }
+        }
+        run_sel += G + min(Q, rem);
+        run_eq += Q;
+    }
+}
+
+void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (a.nseg_total == 0) return;
+    launch_k(k_seg_join, dim3(a.nseg_total), dim3(SEG_THREADS), st, ev0, nullptr, a);
+    if (op == SEL_WORKER)
+        launch_k(k_seg_window<SEL_WORKER>, dim3(a.J), dim3(SEG_THREADS), st, nullptr, nullptr, a);
+    else
+        launch_k(k_seg_window<SEL_PULL>, dim3(a.J), dim3(SEG_THREADS), st, nullptr, nullptr, a);
+    launch_k(k_seg_prefix, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, nullptr, a);
+    launch_k(k_seg_rank, dim3(a.J), dim3(RANK_THREADS), st, nullptr, nullptr, a);
+    if (op == SEL_WORKER)
+        launch_k(k_seg_emit<SEL_WORKER>, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, ev1, a);
+    else
+        launch_k(k_seg_emit<SEL_PULL>, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, ev1, a);
 }
 
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1)

@@ -17,8 +17,10 @@ LIB_PATH = os.path.join(_HERE, "libdgs.so")
 
 DGS_OK = 0
 DGS_EINVAL, DGS_ENOMEM, DGS_ENOTSUP, DGS_ECAPACITY, DGS_EHIP = -1, -2, -3, -4, -5
-OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS = 1, 2, 3, 4, 5
-PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA = range(6)
+OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS, OPT_SEGMENTED = 1, 2, 3, 4, 5, 6
+SEG_AUTO, SEG_ALWAYS, SEG_NEVER = 0, 1, 2
+(PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA,
+ PROF_WORKER_SEGMENTED, PROF_PULL_SEGMENTED) = range(8)
 
 EXPORTS = [
     "dgs_workspace_bytes", "dgs_create", "dgs_destroy", "dgs_nnz", "dgs_worker_step",
@@ -36,7 +38,7 @@ class DgsError(RuntimeError):
 class _Stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
         "calls_worker", "calls_pull", "calls_push", "exact_calls", "fallback_tensors",
-        "fallback_elems", "candidates", "internal_errors")]
+        "fallback_elems", "candidates", "internal_errors", "segmented_tensors")]
 
 
 _lib = None
@@ -108,6 +110,7 @@ class Stats:
     fallback_elems: int
     candidates: int
     internal_errors: int
+    segmented_tensors: int = 0
 
 
 class Context:

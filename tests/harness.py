@@ -97,3 +97,31 @@ def assert_state_match(got: np.ndarray, want: np.ndarray, what=""):
     if not np.array_equal(bits(got), bits(want)):
         bad = np.nonzero(bits(got) != bits(want))[0]
         raise AssertionError(f"{what}: {bad.size} state words differ in bits, first at {bad[0]}")
+
+
+def run_worker_parity(oracle, off, grads, lr, m, rho, *, force_exact=False, residual=False,
+                      misalign=0, margin=None, init_state=None, seg_mode=None):
+    """Several steps of dgs_worker_step vs the oracle; returns the GPU context stats."""
+    from paper_1910_10929_amd import dgs
+    ctx = dgs.Context(off, W=0)
+    if force_exact:
+        ctx.set_option(dgs.OPT_FORCE_EXACT, 1)
+    if margin is not None:
+        ctx.set_option(dgs.OPT_MARGIN_PCT, margin)
+    if seg_mode is not None:
+        ctx.set_option(dgs.OPT_SEGMENTED, seg_mode)
+    w = Worker(ctx, density_max=rho, misalign=misalign)
+    n = int(off[-1])
+    s_ref = np.zeros(n, np.float32) if init_state is None else init_state.copy()
+    if init_state is not None:
+        import torch
+        w.state.copy_(torch.from_numpy(init_state))
+    for t, g in enumerate(grads):
+        want_i, want_v = oracle.worker_step(g, s_ref, off, lr, m, rho)
+        got_i, got_v = w.step(g, lr, m, rho, residual_mode=residual)
+        assert_pairs_match(got_i, got_v, want_i, want_v, f"step {t}")
+        assert_state_match(w.state_host(), s_ref, f"state after step {t}")
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    ctx.close()
+    return st

@@ -6,7 +6,8 @@ import numpy as np
 import pytest
 
 from paper_1910_10929_amd import dgs, synth
-from harness import Server, Worker, assert_pairs_match, assert_state_match, to_dev, to_host_u32
+from harness import (Server, Worker, assert_pairs_match, assert_state_match, run_worker_parity, to_dev,
+                     to_host_u32)
 
 pytestmark = pytest.mark.gpu
 
@@ -17,31 +18,6 @@ def torch_mod():
     assert torch.cuda.is_available(), "needs a GPU"
     dgs.lib()   # fails loudly if libdgs.so is missing
     return torch
-
-
-def run_worker_parity(oracle, off, grads, lr, m, rho, *, force_exact=False, residual=False,
-                      misalign=0, margin=None, init_state=None):
-    """Several steps of dgs_worker_step vs the oracle; returns the GPU context stats."""
-    ctx = dgs.Context(off, W=0)
-    if force_exact:
-        ctx.set_option(dgs.OPT_FORCE_EXACT, 1)
-    if margin is not None:
-        ctx.set_option(dgs.OPT_MARGIN_PCT, margin)
-    w = Worker(ctx, density_max=rho, misalign=misalign)
-    n = int(off[-1])
-    s_ref = np.zeros(n, np.float32) if init_state is None else init_state.copy()
-    if init_state is not None:
-        import torch
-        w.state.copy_(torch.from_numpy(init_state))
-    for t, g in enumerate(grads):
-        want_i, want_v = oracle.worker_step(g, s_ref, off, lr, m, rho)
-        got_i, got_v = w.step(g, lr, m, rho, residual_mode=residual)
-        assert_pairs_match(got_i, got_v, want_i, want_v, f"step {t}")
-        assert_state_match(w.state_host(), s_ref, f"state after step {t}")
-    st = ctx.stats()
-    assert st.internal_errors == 0
-    ctx.close()
-    return st
 
 
 RAGGED_SIZES = [1, 7, 64, 1000, 8192, 8193, 9408, 3, 100_003, 50_000, 1 << 18, 17, 65_537, 12_345]

@@ -1,0 +1,149 @@
+"""GPU parity of the multi-workgroup ("segmented") selection, which takes over
+for very large tensors and for candidate lists that outgrow one workgroup.
+Small layouts are forced through it with DGS_OPT_SEGMENTED = always; the results
+must equal the oracle's, and therefore the single-workgroup path's, bit for bit."""
+import numpy as np
+import pytest
+
+from paper_1910_10929_amd import dgs, synth
+from harness import Server, Worker, assert_pairs_match, assert_state_match, run_worker_parity
+
+pytestmark = pytest.mark.gpu
+
+# several tensors of at least 65536 elements (segmented when forced) with unaligned
+# borders, between small ones that stay on the single-workgroup path
+SEG_SIZES = [100_003, 7, 1 << 18, 65_537, 300_001, 64, 70_001, 600_000, 9000, 65_536]
+
+
+@pytest.mark.parametrize("force_exact", [False, True], ids=["predicted", "exact"])
+@pytest.mark.parametrize("rho", [0.001, 0.01, 0.03])
+def test_segmented_ragged_multi_tensor(oracle, rho, force_exact):
+    off = synth.offsets_from_sizes(SEG_SIZES)
+    scales = synth.tensor_scales(len(SEG_SIZES), 41)
+    rng = np.random.default_rng(42)
+    grads = [synth.gaussian_grads(off, scales, rng) for _ in range(6)]
+    st = run_worker_parity(oracle, off, grads, np.float32(0.5), np.float32(0.9), rho,
+                           force_exact=force_exact, seg_mode=dgs.SEG_ALWAYS)
+    assert st.exact_calls == (6 if force_exact else 1)
+    assert st.segmented_tensors == 7 * 6 and st.fallback_tensors == 0   # seven tensors of >= 65536 elements
+
+
+def test_segmented_and_single_workgroup_paths_agree_bytewise(oracle):
+    off = synth.offsets_from_sizes([700_000, 64, 70_001])
+    rng = np.random.default_rng(43)
+    grads = [synth.gaussian(int(off[-1]), rng) for _ in range(5)]
+    outs = []
+    for mode in (dgs.SEG_NEVER, dgs.SEG_ALWAYS):
+        ctx = dgs.Context(off, W=0)
+        ctx.set_option(dgs.OPT_SEGMENTED, mode)
+        w = Worker(ctx, density_max=0.005)
+        run = []
+        for g in grads:
+            i, v = w.step(g, 0.1, 0.7, 0.005)
+            run.append((i.copy(), v.copy(), w.state_host()))
+        outs.append(run)
+        assert ctx.stats().internal_errors == 0
+        ctx.close()
+    for (i1, v1, s1), (i2, v2, s2) in zip(*outs):
+        assert np.array_equal(i1, i2)
+        assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))
+        assert np.array_equal(s1.view(np.uint32), s2.view(np.uint32))
+
+
+def _patterns(n):
+    rng = np.random.default_rng(44)
+    cases = {}
+    cases["all_equal"] = np.full(n, 1.5, np.float32)          # prefix list overflows: falls back
+    cases["all_zero"] = np.zeros(n, np.float32)
+    few = np.zeros(n, np.float32)
+    few[rng.choice(n, 40, replace=False)] = rng.standard_normal(40).astype(np.float32)
+    cases["fewer_nonzeros_than_k"] = few
+    cases["few_levels"] = rng.integers(-3, 4, size=n).astype(np.float32)
+    # a tie class at the k-th key that spans all segments and is cut by the tie budget
+    t = rng.standard_normal(n).astype(np.float32)
+    t[rng.choice(n, 2000, replace=False)] = np.float32(3.0)
+    t[rng.choice(n, 500, replace=False)] = np.float32(-3.0)
+    cases["tie_class_across_segments"] = t
+    cases["subnormals"] = rng.integers(-1000, 1000, size=n).astype(np.float32) * np.float32(1e-45)
+    return cases
+
+
+@pytest.mark.parametrize("name", ["all_equal", "all_zero", "fewer_nonzeros_than_k", "few_levels",
+                                  "tie_class_across_segments", "subnormals"])
+def test_segmented_degenerate_value_patterns(oracle, name):
+    n_big = 600_000                     # three segments
+    g_big = _patterns(n_big)[name]
+    off = synth.offsets_from_sizes([n_big, 100, 9000])
+    rng = np.random.default_rng(45)
+    tail = synth.gaussian(9100, rng)
+    g1 = np.concatenate([g_big, tail])
+    g2 = np.concatenate([g_big[::-1].copy(), -tail])
+    run_worker_parity(oracle, off, [g1, g2, g1], 1.0, np.float32(0.5), 0.005, seg_mode=dgs.SEG_ALWAYS)
+    run_worker_parity(oracle, off, [g1, g2], 1.0, np.float32(0.5), 0.005, force_exact=True,
+                      seg_mode=dgs.SEG_ALWAYS)
+
+
+def test_segmented_threshold_jump_falls_back_and_recovers(oracle):
+    """A gradient scale that jumps by 1e3 puts the k-th key far beyond the window
+    above the predicted threshold; a collapse leaves fewer candidates than k.  Both
+    must give the exact result and the following steps must recover."""
+    off = synth.offsets_from_sizes([400_000, 64])
+    n = int(off[-1])
+    rng = np.random.default_rng(46)
+    g = [synth.gaussian(n, rng) for _ in range(8)]
+    grads = [g[0], g[1], g[2] * np.float32(1e3), g[3] * np.float32(1e3), g[4] * np.float32(1e-6),
+             g[5] * np.float32(1e-6), g[6], g[7]]
+    st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.002, residual=True,
+                           seg_mode=dgs.SEG_ALWAYS)
+    assert st.fallback_tensors >= 1 and st.segmented_tensors >= 3
+
+
+def test_segmented_server_pull(oracle):
+    import torch
+    sizes = [320_000, 64, 9408, 140_000, 7]
+    off = synth.offsets_from_sizes(sizes)
+    n = int(off[-1])
+    W = 4
+    rho_up, rho_down = 0.004, 0.002
+    scales = synth.tensor_scales(len(sizes), 47)
+    rng = np.random.default_rng(48)
+    kj, K = oracle.nnz(off, rho_up)
+    ctx = dgs.Context(off, W=W)
+    ctx.set_option(dgs.OPT_SEGMENTED, dgs.SEG_ALWAYS)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=1.0)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((W, n), np.float32)
+    order = synth.event_schedule(W, 24, 49)
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = synth.sparse_payload(off, kj, scales, rng)
+        oracle.server_push(model_ref, diff_ref, idx, val)
+        srv.push(k, idx, val)
+        wi, wv = oracle.server_pull(diff_ref, k, off, rho_down)
+        gi, gv = srv.pull(k, rho_down)
+        assert_pairs_match(gi, gv, wi, wv, f"event {e} pull({k})")
+    # a second pull with nothing new in between, and a pull on a nearly empty row
+    for k in (int(order[-1]), int(order[-1])):
+        wi, wv = oracle.server_pull(diff_ref, k, off, rho_down)
+        gi, gv = srv.pull(k, rho_down)
+        assert_pairs_match(gi, gv, wi, wv, f"repeated pull({k})")
+    torch.cuda.synchronize()
+    assert_state_match(srv.model.cpu().numpy(), model_ref, "model")
+    assert_state_match(srv.diff.cpu().numpy().ravel(), diff_ref.ravel(), "diff")
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
+
+
+def test_automatic_mode_mixes_both_selections(oracle):
+    """Default mode: the 4.2M-element tensor goes segmented by size, the 300k one stays
+    on the single-workgroup path at density 1e-3 and goes segmented at 0.02 (its
+    candidate list no longer fits one workgroup's LDS)."""
+    off = synth.offsets_from_sizes([4_200_000, 64, 300_000])
+    n = int(off[-1])
+    scales = synth.tensor_scales(3, 50)
+    rng = np.random.default_rng(51)
+    grads = [synth.gaussian_grads(off, scales, rng) for _ in range(3)]
+    for rho in (1e-3, 0.02):
+        st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), rho)
+        assert st.fallback_tensors == 0
+        assert st.segmented_tensors == (3 if rho == 1e-3 else 6)
