@@ -351,16 +351,17 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wsum, 
 }
 
 // In an LDS histogram h[NB] (NB a multiple of 64, at most 4096), find for each of
-// two ranks RA, RB (counted from the top bin, >= 1) the bin holding it and the
-// rank inside that bin:  res = {binA, rankA, binB, rankB}, bin -1 if the rank
-// exceeds the histogram total.  Every wavefront sums rows of 64 bins, then
-// wavefront 0 scans the row sums and the two rows it lands in.
+// three ranks R[0..2] (counted from the top bin, >= 1) the bin holding it and the
+// rank inside that bin:  res[2 i] = bin, res[2 i + 1] = rank in the bin; bin -1 if the
+// rank exceeds the histogram total (or is 0).  Every wavefront sums rows of 64 bins,
+// then up to three wavefronts each scan the row sums and the row their rank lands in.
 // Barriers: one on entry (h complete), one in the middle, one on exit.
 template <int NB, int NW>
-__device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t RA, uint32_t RB, uint32_t *rowsum,
-                                           int *res)
+__device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t R0, uint32_t R1, uint32_t R2,
+                                           uint32_t *rowsum, int *res)
 {
     constexpr int ROWS = NB / 64;
+    constexpr int SEARCHERS = NW < 3 ? NW : 3;
     static_assert(ROWS * 64 == NB && ROWS <= 64, "histogram shape");
     const uint32_t lane = lane_id();
     const uint32_t wave = threadIdx.x >> 6;
@@ -370,14 +371,12 @@ __device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t RA, uint3
         if (lane == 0) rowsum[r] = s;
     }
     __syncthreads();
-    if (wave < 2) {
-        // wavefront 0 searches RA, wavefront 1 searches RB (one wavefront does both if alone);
+    if (wave < (uint32_t)SEARCHERS) {
         // lane l looks at row ROWS-1-l: the top row first
         const uint32_t rs = (lane < (uint32_t)ROWS) ? rowsum[ROWS - 1 - lane] : 0u;
         const uint32_t rincl = wave_incl_scan(rs);
-        const int first = (NW >= 2) ? (int)wave : 0, last = (NW >= 2) ? (int)wave : 1;
-        for (int which = first; which <= last; ++which) {
-            const uint32_t R = which ? RB : RA;
+        for (int which = (int)wave; which < 3; which += SEARCHERS) {
+            const uint32_t R = which == 0 ? R0 : (which == 1 ? R1 : R2);
             int bin = -1;
             uint32_t rin = 0;
             const uint64_t hit = ballot64(lane < (uint32_t)ROWS && rincl >= R);
@@ -414,14 +413,14 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
     if (!tdesc[j].big) return;
     __shared__ uint32_t h[HBINS];
     __shared__ uint32_t rowsum[64];
-    __shared__ int res[4];
+    __shared__ int res[6];
     uint32_t *g = ghist + (size_t)j * HBINS;
     for (uint32_t b = threadIdx.x; b < HBINS; b += 256) {
         h[b] = g[b];
         g[b] = 0;   // leave the histogram clean for the next use
     }
     const PlanEntry pe = plan[j];
-    find_ranks<HBINS, 4>(h, pe.k2, pe.k, rowsum, res);
+    find_ranks<HBINS, 4>(h, pe.k2, pe.k, 0u, rowsum, res);
     if (threadIdx.x == 0) {
         const int b2 = res[0], b1 = res[2];
         // the histogram holds the nonzero keys only: a rank beyond its total means
@@ -479,7 +478,7 @@ struct SelShared {
     uint32_t h[2048];
     uint32_t wsum[SEL_WAVES];
     uint32_t rowsum[64];
-    int res[4];
+    int res[6];
     uint32_t kmin;
 };
 
@@ -509,14 +508,15 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
 // win_base: (collection threshold >> 11) for candidate lists, 0xFFFFFFFF otherwise.
 template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
-                                            const uint32_t R, const uint32_t win_base, SelShared &S,
-                                            const SelectArgs &A, const uint32_t outoff,
-                                            uint32_t *tau_next, uint32_t *expect)
+                                            const uint32_t R, const uint32_t Eq, const uint32_t win_base,
+                                            SelShared &S, const SelectArgs &A, const uint32_t outoff,
+                                            uint32_t *tau_next, uint32_t *expect, uint32_t *q_e)
 {
     const uint32_t tid = threadIdx.x;
     const bool measurable = (R != 0) && (cN >= R);
     *tau_next = 0;
     *expect = 0;
+    *q_e = 0;
 
     uint32_t pfx = 0;        // key prefix of the k-th entry, `lowbits` bits still unresolved
     uint32_t r2 = 0;         // its rank among the entries sharing that prefix
@@ -546,8 +546,9 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 }
             }
         }
-        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
-        const int bk = S.res[0], bR = S.res[2];
+        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, (measurable && Eq <= cN) ? Eq : 0u, S.rowsum,
+                                    S.res);
+        const int bk = S.res[0], bR = S.res[2], bE = S.res[4];
         const uint32_t rk = (uint32_t)S.res[1], rR = (uint32_t)S.res[3];
         if (bk >= 0 && bk < 2047 && bR >= 0 && bR < 2047) {
             have_prefix = true;
@@ -558,6 +559,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 const uint32_t edge = (win_base + (uint32_t)bR) << 11;
                 *tau_next = edge ? edge : 1u;
                 *expect = R - rR + S.h[bR];
+                if (bE >= 0 && bE < 2047) *q_e = (win_base + (uint32_t)bE) << 11;
             }
         }
         __syncthreads();
@@ -578,7 +580,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
             for (int i = 0; i < 4; ++i)
                 hist_add<Src::AGG>(S.h, kk[i] >> 20, pb + i * SEL_THREADS + tid < cN);
         }
-        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, S.rowsum, S.res);
+        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, 0u, S.rowsum, S.res);
         const int b1 = S.res[0];
         const uint32_t r1 = (uint32_t)S.res[1];
         const int c1 = S.res[2];
@@ -607,14 +609,14 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 else if (two && top == c1) atomicAdd(&S.h[1024u + ((kk[i] >> 10) & 1023u)], 1u);
             }
         }
-        find_ranks<1024, SEL_WAVES>(S.h, r1, (measurable && !two) ? q1 : r1, S.rowsum, S.res);
+        find_ranks<1024, SEL_WAVES>(S.h, r1, (measurable && !two) ? q1 : r1, 0u, S.rowsum, S.res);
         const int b2 = S.res[0];
         r2 = (uint32_t)S.res[1];
         int c2 = S.res[2];
         uint32_t q2 = (uint32_t)S.res[3];
         __syncthreads();
         if (two) {
-            find_ranks<1024, SEL_WAVES>(S.h + 1024, q1, q1, S.rowsum, S.res);
+            find_ranks<1024, SEL_WAVES>(S.h + 1024, q1, 0u, 0u, S.rowsum, S.res);
             c2 = S.res[0];
             q2 = (uint32_t)S.res[1];
             __syncthreads();
@@ -648,7 +650,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
         for (int i = 0; i < 4; ++i)
             if ((kk[i] >> lowbits) == pfx) atomicAdd(&S.h[kk[i] & lowmask], 1u);
     }
-    find_ranks<2048, SEL_WAVES>(S.h, r2, r2, S.rowsum, S.res);
+    find_ranks<2048, SEL_WAVES>(S.h, r2, 0u, 0u, S.rowsum, S.res);
     const int b3 = S.res[0];
     const uint32_t rT = (uint32_t)S.res[1];   // how many entries equal to T are taken (lowest index first)
     __syncthreads();
@@ -714,29 +716,47 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
     if (run_sel != k && tid == 0) atomicAdd(&A.stats->internal_errors, 1ull);
 }
 
-// Rank (from the top) whose key becomes the next predicted threshold.
-//   c: candidates collected at the current threshold, E: candidates that threshold was
-//   expected to collect (0 = unknown); `drift` says whether the two are comparable.
+// Rank (from the top) whose key becomes the next predicted threshold, and how the
+// drift since the current threshold was set is measured.
+//   c: candidates collected at the current threshold; E: candidates that threshold was
+//   expected to collect when it was set (0 = unknown); `drift`: the two are comparable.
+// Worker: sent entries stay large (they keep m * a) and unsent ones keep growing, so
+// the keys of the tail move from step to step.  If the tail grew (c >= E), *Eq = E asks
+// for the key of rank E among the present candidates: the old threshold's quantile has
+// moved there, and the next threshold is scaled by the same ratio (hint_scaled).  If it
+// shrank, the quantile lies below every candidate and cannot be read off: the rank is
+// widened by the ratio of the counts instead.
 template <int OP>
 __device__ __forceinline__ uint32_t hint_rank(const TensorDesc &td, const PlanEntry &pe, bool drift,
-                                              uint32_t c, uint32_t E, float m)
+                                              uint32_t c, uint32_t E, float m, uint32_t *Eq)
 {
-    uint32_t R;
-    if (OP == SEL_WORKER) {
-        // sent entries stay large (they keep m * a), so the tail above a fixed key grows
-        // from step to step: scale the rank by the growth seen since the hint was set
-        float d = 1.0f;
-        if (drift && E != 0) d = fminf(fmaxf((float)c / (float)E, 0.5f), 4.0f);
-        // without momentum the sent entries vanish, as in a pull: start from the wider rank
-        R = (uint32_t)((float)(m == 0.0f ? pe.k2_pull : pe.k2) / d);
-        const uint32_t rmin = max(1u, pe.k / 4u);
-        R = min(max(R, rmin), td.n);
-    } else {
-        // sent entries become zero: even with no new update before the next pull,
-        // k entries must remain above the hinted key
-        R = pe.k2_pull;
+    *Eq = 0;
+    // a pull, or a worker without momentum: sent entries vanish, so even with nothing new
+    // before the next call k entries must remain above the hinted key (about 2k)
+    uint32_t R = (OP == SEL_PULL || m == 0.0f) ? pe.k2_pull : pe.k2;
+    if (OP == SEL_WORKER && drift && E != 0) {
+        if (c >= E) {
+            *Eq = E;
+        } else {
+            const float d = fmaxf((float)c / (float)E, 0.5f);
+            R = (uint32_t)((float)R / d);
+        }
     }
-    return R;
+    const uint32_t rmin = max(1u, pe.k / 4u);
+    return min(max(R, rmin), td.n);
+}
+
+// Threshold for the next step: the key `edge` of the hinted rank, moved by half of the
+// relative shift that the previous threshold's quantile showed (q_e / tau_cur, between 1
+// and 2).  Half: growth usually slows down, and a threshold that is too high costs a
+// dense re-selection while one that is too low only costs extra candidates.
+__device__ __forceinline__ uint32_t hint_scaled(uint32_t edge, uint32_t q_e, uint32_t tau_cur)
+{
+    if (q_e <= tau_cur || tau_cur < 0x00800000u || q_e >= 0x7F800000u) return edge;   // no growth / not normal
+    const float f = 1.0f + 0.5f * (fminf(__uint_as_float(q_e) / __uint_as_float(tau_cur), 2.0f) - 1.0f);
+    const float x = __uint_as_float(edge) * f;
+    const uint32_t t = __float_as_uint(x) & 0x7FFFFFFFu;
+    return (t > edge && t < 0x7F800000u) ? t : edge;
 }
 
 // Next threshold when rank R was not among the candidates: relax the current one by a
@@ -925,11 +945,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     }
 
     // ---- rank whose key becomes the next predicted threshold
-    uint32_t R = 0;
+    uint32_t R = 0, Eq = 0;
     if (td.big && A.write_hint)
-        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, A.hint2[j], A.m);
+        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, A.hint2[j], A.m, &Eq);
 
-    uint32_t tau_next = 0, expect = 0;
+    uint32_t tau_next = 0, expect = 0, q_e = 0;
     // every candidate key is >= kmin (>= the collection threshold): the window starts there
     const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (kmin >> 11);
     if (dense) {
@@ -939,17 +959,17 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
             for (uint32_t p = tid; p < td.n; p += SEL_THREADS) lv[p] = __float_as_uint(A.state[td.off + p]);
             __syncthreads();
             SrcDenseLds src{lv, td.off};
-            select_emit<OP, 4>(src, td.n, pe.k, R, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect);
+            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e);
         } else {
             SrcDense src{A.state, td.off};
-            select_emit<OP, 8>(src, td.n, pe.k, R, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect);
+            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e);
         }
     } else if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, R, win_base, S, A, pe.outoff, &tau_next, &expect);
+        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e);
     } else {
         SrcList src{glist};
-        select_emit<OP, 8>(src, c, pe.k, R, win_base, S, A, pe.outoff, &tau_next, &expect);
+        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e);
     }
 
     if (td.big && A.write_hint && tid == 0) {
@@ -957,6 +977,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
         if (tn == 0) {
             tn = hint_relaxed(tau_cur, dense ? 0xFFFFFFFFu : kmin);
             expect = 0;
+        } else if (q_e != 0) {
+            tn = hint_scaled(tn, q_e, tau_cur);
         }
         if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;   // keep the hint finite
         A.tau[j] = tn;
@@ -1073,7 +1095,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
 {
     __shared__ uint32_t h[SEG_WBINS];
     __shared__ uint32_t rowsum[64];
-    __shared__ int res[4];
+    __shared__ int res[6];
     __shared__ uint32_t wsum[SEG_THREADS / 64];
     __shared__ uint32_t lowest;
     const uint32_t j = blockIdx.x;
@@ -1095,10 +1117,10 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     if (mylow != 0xFFFFFFFFu) atomicMin(&lowest, mylow);
     const uint32_t tau_cur = A.tau[j];
     const uint32_t win_base = tau_cur >> SEG_LOWBITS;
-    uint32_t R = 0;
-    if (A.write_hint) R = hint_rank<OP>(td, pe, !A.exact_mode, c, A.hint2[j], A.m);
+    uint32_t R = 0, Eq = 0;
+    if (A.write_hint) R = hint_rank<OP>(td, pe, !A.exact_mode, c, A.hint2[j], A.m, &Eq);
     const bool measurable = (R != 0) && (c >= R);
-    find_ranks<SEG_WBINS, SEG_THREADS / 64>(h, pe.k, measurable ? R : pe.k, rowsum, res);
+    find_ranks<SEG_WBINS, SEG_THREADS / 64>(h, pe.k, measurable ? R : pe.k, measurable ? Eq : 0u, rowsum, res);
     if (tid == 0) {
         SegState *st = &A.segstate[j];
         const int bk = res[0], bR = res[2];
@@ -1121,6 +1143,9 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
                     const uint32_t edge = (win_base + (uint32_t)bR) << SEG_LOWBITS;
                     tn = edge ? edge : 1u;
                     expect = R - (uint32_t)res[3] + h[bR];
+                    const int bE = res[4];
+                    if (bE >= 0 && bE < (int)SEG_WBINS - 1)
+                        tn = hint_scaled(tn, (win_base + (uint32_t)bE) << SEG_LOWBITS, tau_cur);
                 }
                 if (tn == 0) {
                     const uint32_t kmin = (lowest == 0xFFFFFFFFu) ? 0xFFFFFFFFu
@@ -1201,7 +1226,7 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
     __shared__ uint32_t sG[SEG_MAX_PER_TENSOR];
     __shared__ uint32_t sQ[SEG_MAX_PER_TENSOR];
     __shared__ uint32_t rowsum[64];
-    __shared__ int res[4];
+    __shared__ int res[6];
     __shared__ uint32_t wsum[RANK_THREADS / 64];
     const uint32_t j = blockIdx.x;
     const PlanEntry pe = A.plan[j];
@@ -1227,7 +1252,7 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
     for (uint32_t s = tid; s < td.nseg; s += RANK_THREADS) { sG[s] = 0; sQ[s] = 0; }
     __syncthreads();
     for (uint32_t p = tid; p < m; p += RANK_THREADS) atomicAdd(&h[plist[p].y & (SEG_LBINS - 1u)], 1u);
-    find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, r2, rowsum, res);
+    find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, 0u, 0u, rowsum, res);
     const int b3 = res[0];
     const uint32_t rT = (uint32_t)res[1];   // entries equal to T that are taken, lowest index first
     if (b3 < 0) {
