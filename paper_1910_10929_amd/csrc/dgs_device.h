@@ -47,7 +47,7 @@ constexpr uint32_t SEG_WBINS = 2048;               // window of key >> SEG_LOWBI
 constexpr uint32_t SEG_LBINS = 1u << SEG_LOWBITS;
 constexpr uint32_t PFX_CAP = 8192;                 // candidates sharing the k-th key's prefix, per tensor
 constexpr uint32_t SEG_MAX_PER_TENSOR = 8192;      // per-segment counters kept in LDS by the ranking kernel
-enum SegStatus { SEG_IDLE = 0, SEG_ACTIVE = 1, SEG_FALLBACK = 2 };
+enum SegStatus { SEG_IDLE = 0, SEG_ACTIVE = 1, SEG_FALLBACK = 2, SEG_ZEROFILL = 3 };
 enum SegMode { SEG_MODE_AUTO = 0, SEG_MODE_ALWAYS = 1, SEG_MODE_NEVER = 2 };
 
 struct TensorDesc {

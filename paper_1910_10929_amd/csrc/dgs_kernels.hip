@@ -350,6 +350,18 @@ __device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wsum, 
     return before + incl - v;
 }
 
+// Workgroup sum.  wsum: LDS scratch of nw words.  Contains two barriers.
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *wsum, int nw)
+{
+    const uint32_t s = wave_sum(v);
+    __syncthreads();
+    if (lane_id() == 0) wsum[threadIdx.x >> 6] = s;
+    __syncthreads();
+    uint32_t tot = 0;
+    for (int w = 0; w < nw; ++w) tot += wsum[w];
+    return tot;
+}
+
 // In an LDS histogram h[NB] (NB a multiple of 64, at most 4096), find for each of
 // three ranks R[0..2] (counted from the top bin, >= 1) the bin holding it and the
 // rank inside that bin:  res[2 i] = bin, res[2 i + 1] = rank in the bin; bin -1 if the
@@ -773,6 +785,37 @@ __device__ __forceinline__ uint32_t hint_relaxed(uint32_t tau_cur, uint32_t kmin
     return tn;
 }
 
+// Fewer candidates than k although every nonzero key was collected: the message is
+// completed with the tensor's lowest-index zero-key entries.  With z = k - c zeros to
+// add and candidate i (in index order) at x_i, the zeros below x_i number x_i - off - i;
+// the P candidates for which that is < z lie inside the leading run [off, off + z + P),
+// which is sent whole (z zeros and P candidates); the other candidates follow.
+template <int OP>
+__device__ __forceinline__ void zero_fill_emit(const SrcList src, const uint32_t c, const TensorDesc &td,
+                                               const PlanEntry &pe, const SelectArgs &A, uint32_t *wsum)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t z = pe.k - c;
+    uint32_t mine = 0;
+    for (uint32_t p = tid; p < c; p += SEL_THREADS) mine += ((src.index(p) - td.off - p) < z) ? 1u : 0u;
+    const uint32_t P = block_sum(mine, wsum, SEL_WAVES);
+    const uint32_t X = z + P;
+    for (uint32_t q = tid; q < X; q += SEL_THREADS) {
+        const uint32_t ix = td.off + q;
+        const float v = A.state[ix];
+        A.out_idx[pe.outoff + q] = ix;
+        A.out_val[pe.outoff + q] = v;
+        A.state[ix] = (OP == SEL_WORKER) ? (A.m * v) : 0.0f;
+    }
+    for (uint32_t p = P + tid; p < c; p += SEL_THREADS) {
+        const uint32_t ix = src.index(p);
+        const float v = __uint_as_float(src.bits(p));
+        A.out_idx[pe.outoff + z + p] = ix;
+        A.out_val[pe.outoff + z + p] = v;
+        A.state[ix] = (OP == SEL_WORKER) ? (A.m * v) : 0.0f;
+    }
+}
+
 // Minimum over the 64 lanes of a wavefront (DPP, same pattern as the scan);
 // the result is valid in lane 63.
 __device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
@@ -832,10 +875,12 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
     bool dense = (!td.big) || A.force_dense;
     if (pe.seg) {
-        // planned for the segmented kernels; only a tensor they gave up on is taken here
-        if (A.segstate[j].status != SEG_FALLBACK) return;
-        dense = true;
+        // planned for the segmented kernels; only a tensor they handed over is taken here
+        const uint32_t status = A.segstate[j].status;
+        if (status == SEG_FALLBACK) dense = true;
+        else if (status != SEG_ZEROFILL) return;
     }
+    bool zerofill = false;
     uint32_t c = 0;
     uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
@@ -928,7 +973,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
         if (lane_id() == 63) atomicMin(&S.kmin, kmin);
         const bool any_ovf = __syncthreads_or((int)ovf) != 0;   // also orders the list writes
         kmin = S.kmin;
-        if (any_ovf || c < pe.k) dense = true;
+        if (!any_ovf && c < pe.k && tau_cur <= 1u) zerofill = true;   // every nonzero is already here
+        else if (any_ovf || c < pe.k) dense = true;
         if (!dense && c > SEL_LDS_LIST) {
             // the list outgrew LDS: complete the global copy
             for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
@@ -942,6 +988,16 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                 atomicAdd(&A.stats->candidates, (unsigned long long)c);
             }
         }
+    }
+
+    if (zerofill) {
+        if (c <= SEL_LDS_LIST) zero_fill_emit<OP>(SrcList{llist}, c, td, pe, A, S.wsum);
+        else zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, S.wsum);
+        if (A.write_hint && tid == 0) {
+            A.tau[j] = 1u;
+            A.hint2[j] = 0u;
+        }
+        return;
     }
 
     // ---- rank whose key becomes the next predicted threshold
@@ -1004,17 +1060,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
 // A tensor the chain cannot resolve (fewer candidates than k, an overflowed tile,
 // the k-th key beyond the window, a prefix list that outgrows PFX_CAP) is marked
 // SEG_FALLBACK and selected from the state buffer by k_select afterwards.
-
-__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *wsum, int nw)
-{
-    const uint32_t s = wave_sum(v);
-    __syncthreads();
-    if (lane_id() == 0) wsum[threadIdx.x >> 6] = s;
-    __syncthreads();
-    uint32_t tot = 0;
-    for (int w = 0; w < nw; ++w) tot += wsum[w];
-    return tot;
-}
 
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
 {
@@ -1125,16 +1170,18 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
         SegState *st = &A.segstate[j];
         const int bk = res[0], bR = res[2];
         const bool ok = (st->ovf == 0) && (c >= pe.k) && bk >= 0 && bk < (int)SEG_WBINS - 1;
+        // fewer candidates than k with every nonzero collected: k_select completes with zeros
+        const bool zf = (st->ovf == 0) && (c < pe.k) && (tau_cur <= 1u);
         st->ovf = 0;
         st->pfxcount = 0;
         st->pfx = win_base + (uint32_t)max(bk, 0);
         st->r2 = (uint32_t)res[1];
         st->T = 0;
-        st->status = ok ? SEG_ACTIVE : SEG_FALLBACK;
-        if (!ok) {
+        st->status = ok ? SEG_ACTIVE : (zf ? SEG_ZEROFILL : SEG_FALLBACK);
+        if (!ok && !zf) {
             atomicAdd(&A.stats->fallback_tensors, 1ull);
             atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
-        } else {
+        } else if (ok) {
             atomicAdd(&A.stats->candidates, (unsigned long long)c);
             atomicAdd(&A.stats->segmented_tensors, 1ull);
             if (A.write_hint) {

@@ -310,3 +310,37 @@ def test_checkpoint_resume_is_bit_identical(oracle, torch_mod):
         assert np.array_equal(v.view(np.uint32), full[5 + t][1].view(np.uint32))
     assert np.array_equal(w.state_host().view(np.uint32), final.view(np.uint32))
     ctx.close()
+
+
+def test_repeated_pulls_without_pushes(oracle, torch_mod):
+    """Pulls that find fewer nonzeros than k: zero-valued entries at the lowest indices
+    complete each message (also -0.0, which keeps its sign bit in the message).  After
+    the threshold hint has dropped to 'every nonzero', no dense re-selection is needed."""
+    sizes = [90_000, 64, 20_000, 150_001]
+    off = synth.offsets_from_sizes(sizes)
+    n = int(off[-1])
+    scales = synth.tensor_scales(len(sizes), 35)
+    rng = np.random.default_rng(36)
+    kj, K = oracle.nnz(off, 0.002)
+    ctx = dgs.Context(off, W=2)
+    srv = Server(ctx, None, density_max=0.01)
+    diff_ref = np.zeros((2, n), np.float32)
+    # a few negative zeros inside the leading run of the first tensor
+    import torch
+    diff_ref[0, [3, 11, 95_000]] = np.float32(-0.0)
+    srv.diff.copy_(torch.from_numpy(diff_ref))
+    idx, val = synth.sparse_payload(off, kj, scales, rng)
+    oracle.server_push(None, diff_ref, idx, val)
+    srv.push(0, idx, val)
+    fallbacks = []
+    for t in range(6):
+        rho = 0.002 if t < 2 else 0.004        # more than was pushed
+        wi, wv = oracle.server_pull(diff_ref, 0, off, rho)
+        gi, gv = srv.pull(0, rho)
+        assert np.array_equal(gi, wi), f"pull {t}"
+        assert np.array_equal(gv.view(np.uint32), wv.view(np.uint32)), f"pull {t}"
+        fallbacks.append(ctx.stats().fallback_tensors)
+    assert_state_match(srv.diff.cpu().numpy()[0], diff_ref[0], "diff row 0")
+    assert fallbacks[-1] == fallbacks[-3], "later empty pulls must not re-select densely"
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
