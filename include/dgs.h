@@ -73,6 +73,7 @@ typedef struct dgs_stats {
     uint64_t candidates;       /* candidates collected by streaming passes */
     uint64_t internal_errors;  /* must stay 0 */
     uint64_t segmented_tensors; /* tensors resolved by the multi-workgroup selection kernels */
+    uint64_t repaired_tensors;  /* of those, after a second collection with a fresh threshold */
 } dgs_stats;
 
 /*

@@ -22,8 +22,8 @@ constexpr uint32_t MAX_PROF = 4096;
 size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
-    size_t tile_desc, tdesc, plans, tau, hint2, ghist, tile_cnt, heads, slots, ord, stats, flag;
-    size_t segtab, segcnt, segG1, segOut, segstate, pfxlist, total;
+    size_t tile_desc, tdesc, plans, tau, hint2, tprev, ghist, tile_cnt, heads, slots, ord, stats, flag;
+    size_t segtab, segcnt, segG1, segQ, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -62,6 +62,7 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.plans = o;     o = align_up(o + (size_t)NPLAN * J * sizeof(PlanEntry));
     L.tau = o;       o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
     L.hint2 = o;     o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
+    L.tprev = o;     o = align_up(o + (size_t)(W + 1) * J * sizeof(uint32_t));
     L.ghist = o;     o = align_up(o + (size_t)J * HBINS * sizeof(uint32_t));
     L.tile_cnt = o;  o = align_up(o + (ntiles + 4) * sizeof(uint32_t));
     L.heads = o;     o = align_up(o + ntiles * HEAD * sizeof(uint2));
@@ -72,6 +73,7 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
     L.segcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segG1 = o;     o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
+    L.segQ = o;      o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segOut = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint2));
     L.segstate = o;  o = align_up(o + (size_t)J * sizeof(SegState));
     L.pfxlist = o;   o = align_up(o + (ncap * PFX_CAP + 1) * sizeof(uint4));
@@ -111,6 +113,7 @@ struct dgs_ctx {
     PlanEntry *plans = nullptr;
     uint32_t *tau = nullptr;
     uint32_t *hint2 = nullptr;
+    uint32_t *tprev = nullptr;
     uint32_t *ghist = nullptr;
     uint32_t *tile_cnt = nullptr;
     uint2 *heads = nullptr;
@@ -119,7 +122,7 @@ struct dgs_ctx {
     DevStats *stats = nullptr;
     uint32_t *flag = nullptr;
     SegDesc *segtab = nullptr;
-    uint32_t *segcnt = nullptr, *segG1 = nullptr;
+    uint32_t *segcnt = nullptr, *segG1 = nullptr, *segQ = nullptr;
     uint2 *segOut = nullptr;
     SegState *segstate = nullptr;
     uint4 *pfxlist = nullptr;
@@ -312,7 +315,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
             ps.launched();
         }
         {
-            launch_pick(c->tdesc, plan, c->ghist, tau, c->stats, c->J, c->stream);
+            launch_pick(c->tdesc, plan, c->ghist, tau, c->tprev + (size_t)hint_set * c->J, c->stats, c->J, c->stream,
+                        nullptr, nullptr);
             ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
             StreamArgs sb = sa;
             sb.grad = nullptr;
@@ -337,6 +341,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.slots = c->slots;
     se.ord = c->ord;
     se.hint2 = c->hint2 + (size_t)hint_set * c->J;
+    se.tprev = c->tprev + (size_t)hint_set * c->J;
     se.exact_mode = exact ? 1u : 0u;
     se.out_idx = idx_out;
     se.out_val = val_out;
@@ -353,6 +358,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sg.segtab = c->segtab;
         sg.tau = tau;
         sg.hint2 = se.hint2;
+        sg.tprev = se.tprev;
         sg.tile_cnt = c->tile_cnt;
         sg.heads = c->heads;
         sg.slots = c->slots;
@@ -361,6 +367,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sg.segstate = c->segstate;
         sg.segcnt = c->segcnt;
         sg.segG1 = c->segG1;
+        sg.segQ = c->segQ;
         sg.segOut = c->segOut;
         sg.pfxlist = c->pfxlist;
         sg.out_idx = idx_out;
@@ -371,8 +378,20 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sg.exact_mode = exact ? 1u : 0u;
         sg.nseg_total = c->nseg_total;
         sg.J = c->J;
+        sg.round = 0;
+        sg.pending = c->flag + 8;
+        se.pending = sg.pending;
         ProfSlot ps(c, prof_seg);
-        launch_segmented(op_select, sg, c->stream, ps.ev0, ps.ev1);
+        launch_segmented(op_select, sg, c->stream, ps.ev0, nullptr);
+        // repair round for the tensors whose prediction failed: collect again from `state`
+        // with a threshold taken from a fresh histogram, then the same chain once more
+        // (all of these kernels return at once when nothing is pending)
+        StreamArgs sr = sa;
+        sr.grad = nullptr;
+        launch_seg_recollect(sr, aligned16(state), sg, c->stream);
+        sg.round = 1;
+        sg.exact_mode = 1u;
+        launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
         ps.launched();
     }
     {
@@ -421,6 +440,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->plans = (PlanEntry *)(c->ws + L.plans);
     c->tau = (uint32_t *)(c->ws + L.tau);
     c->hint2 = (uint32_t *)(c->ws + L.hint2);
+    c->tprev = (uint32_t *)(c->ws + L.tprev);
     c->ghist = (uint32_t *)(c->ws + L.ghist);
     c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
     c->heads = (uint2 *)(c->ws + L.heads);
@@ -431,6 +451,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->segtab = (SegDesc *)(c->ws + L.segtab);
     c->segcnt = (uint32_t *)(c->ws + L.segcnt);
     c->segG1 = (uint32_t *)(c->ws + L.segG1);
+    c->segQ = (uint32_t *)(c->ws + L.segQ);
     c->segOut = (uint2 *)(c->ws + L.segOut);
     c->segstate = (SegState *)(c->ws + L.segstate);
     c->pfxlist = (uint4 *)(c->ws + L.pfxlist);
@@ -488,6 +509,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
         ok = ok && hipMemcpyAsync(c->segtab, segs.data(), segs.size() * sizeof(SegDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
     if (ok) {
         launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
+        launch_fill_u32(c->tprev, 0u, (size_t)(W + 1) * J, c->stream);
         launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
         launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
         launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);
@@ -667,6 +689,7 @@ int dgs_get_stats(dgs_ctx *c, dgs_stats *out)
     out->candidates = d.candidates;
     out->internal_errors = d.internal_errors;
     out->segmented_tensors = d.segmented_tensors;
+    out->repaired_tensors = d.repaired_tensors;
     return DGS_OK;
 }
 

@@ -47,7 +47,12 @@ constexpr uint32_t SEG_WBINS = 2048;               // window of key >> SEG_LOWBI
 constexpr uint32_t SEG_LBINS = 1u << SEG_LOWBITS;
 constexpr uint32_t PFX_CAP = 8192;                 // candidates sharing the k-th key's prefix, per tensor
 constexpr uint32_t SEG_MAX_PER_TENSOR = 8192;      // per-segment counters kept in LDS by the ranking kernel
-enum SegStatus { SEG_IDLE = 0, SEG_ACTIVE = 1, SEG_FALLBACK = 2, SEG_ZEROFILL = 3 };
+// SEG_ACTIVE + r: being resolved by round r of the chain (0 = first attempt, 1 = repair);
+// SEG_PENDING: the first attempt failed, the repair round collects again with a threshold
+// taken from a fresh histogram; SEG_COUNT: the k-th key is known but too many entries share
+// its prefix, the repair round counts the segments against it; SEG_FALLBACK / SEG_ZEROFILL:
+// left to k_select.
+enum SegStatus { SEG_IDLE = 0, SEG_FALLBACK = 2, SEG_ZEROFILL = 3, SEG_PENDING = 4, SEG_COUNT = 5, SEG_ACTIVE = 8 };
 enum SegMode { SEG_MODE_AUTO = 0, SEG_MODE_ALWAYS = 1, SEG_MODE_NEVER = 2 };
 
 struct TensorDesc {
@@ -92,6 +97,7 @@ struct DevStats {
     unsigned long long candidates;
     unsigned long long internal_errors;
     unsigned long long segmented_tensors;
+    unsigned long long repaired_tensors;
 };
 
 enum StreamOp { OP_FMA = 0, OP_IDENT = 1 };
@@ -121,6 +127,7 @@ struct SelectArgs {
     const uint2 *slots;
     uint2 *ord;                   // ordered candidates of tensor j start at CAPT * (first tile + j)
     uint32_t *hint2;              // per tensor: candidates expected at the hinted threshold (0 = unknown)
+    uint32_t *tprev;              // per tensor: k-th key of the previous selection on this stream (0 = unknown)
     uint32_t *out_idx;
     float *out_val;
     DevStats *stats;
@@ -129,6 +136,7 @@ struct SelectArgs {
     uint32_t write_hint;
     uint32_t exact_mode;          // the threshold came from this step's histogram
     const SegState *segstate;     // tensors planned as segmented are skipped unless they fell back
+    uint32_t *pending;            // cleared for the next call
 };
 
 struct SegArgs {
@@ -138,6 +146,7 @@ struct SegArgs {
     const SegDesc *segtab;
     uint32_t *tau;                // hints of this stream, updated
     uint32_t *hint2;
+    uint32_t *tprev;              // per tensor: k-th key of the previous selection on this stream
     const uint32_t *tile_cnt;
     const uint2 *heads;
     const uint2 *slots;
@@ -146,6 +155,7 @@ struct SegArgs {
     SegState *segstate;
     uint32_t *segcnt;             // per segment: candidates
     uint32_t *segG1;              // per segment: candidates with a larger key prefix than the k-th
+    uint32_t *segQ;               // per segment: candidates equal to the k-th key (SEG_COUNT only)
     uint2 *segOut;                // per segment: (output position within the tensor, ties to take)
     uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, segment, 0)
     uint32_t *out_idx;
@@ -153,6 +163,8 @@ struct SegArgs {
     DevStats *stats;
     float m;
     uint32_t write_hint, exact_mode, nseg_total, J;
+    uint32_t round;               // 0: first attempt, 1: repair of the tensors left SEG_PENDING
+    uint32_t *pending;            // number of tensors left SEG_PENDING by round 0 (reset by k_select)
 };
 
 // Host-callable launchers (defined next to the kernels).
@@ -160,7 +172,11 @@ struct SegArgs {
 void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream,
                    void *ev0, void *ev1);
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 DevStats *stats, uint32_t J, void *stream);
+                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream, const SegState *only_pending,
+                 const uint32_t *pending);
+// Repair round, first half: histogram pass, pick and collecting pass over the segments
+// of the tensors left SEG_PENDING (reads `state` only).
+void launch_seg_recollect(const StreamArgs &a, bool vec, const SegArgs &g, void *stream);
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1);
 // The five kernels of the segmented selection, in order, on `stream`.
 void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1);

@@ -93,7 +93,7 @@ __device__ __forceinline__ uint4 span_desc(const uint32_t *__restrict__ toff, ui
 template <int OP, int MODE, bool VEC>
 __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t *__restrict__ toff,
                                              const uint32_t *__restrict__ tau, uint32_t t,
-                                             uint32_t *lhist, int cur)
+                                             uint32_t *lhist, int cur, int only = -1)
 {
     const uint32_t lane = lane_id();
     const uint32_t base = t * TILE;
@@ -227,7 +227,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
                 } else if (e >= begB) {
                     if (bigB) tt = (int)tB;
                 }
-                if (tt < 0) continue;
+                if (tt < 0 || (only >= 0 && tt != only)) continue;
                 const uint32_t key = __float_as_uint(a[r][j]) & 0x7FFFFFFFu;
                 if (key == 0) continue;            // zeros (often the bulk of a difference row) are implied
                 const uint32_t bin = key >> HSHIFT;
@@ -419,10 +419,13 @@ __device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t R0, uint3
 // ---------------------------------------------------------------------------
 
 __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const PlanEntry *plan,
-                                              uint32_t *ghist, uint32_t *tau, DevStats *stats)
+                                              uint32_t *ghist, uint32_t *tau, uint32_t *tprev,
+                                              DevStats *stats, const SegState *only_pending,
+                                              const uint32_t *pending)
 {
     const uint32_t j = blockIdx.x;
     if (!tdesc[j].big) return;
+    if (only_pending && (*pending == 0 || only_pending[j].status != SEG_PENDING)) return;
     __shared__ uint32_t h[HBINS];
     __shared__ uint32_t rowsum[64];
     __shared__ int res[6];
@@ -450,13 +453,18 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
             t = 1;   // the k-th key is tiny or zero: collect every nonzero
         }
         tau[j] = t;
+        // where the k-th key lies (middle of its bucket): anchors the window histogram of
+        // the segmented selection
+        tprev[j] = (b1 >= 0) ? (((uint32_t)b1 << HSHIFT) + (1u << (HSHIFT - 1))) : 0u;
     }
 }
 
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 DevStats *stats, uint32_t J, void *stream)
+                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream, const SegState *only_pending,
+                 const uint32_t *pending)
 {
-    hipLaunchKernelGGL(k_pick, dim3(J), dim3(256), 0, (hipStream_t)stream, tdesc, plan, ghist, tau, stats);
+    hipLaunchKernelGGL(k_pick, dim3(J), dim3(256), 0, (hipStream_t)stream, tdesc, plan, ghist, tau, tprev,
+                       stats, only_pending, pending);
 }
 
 // ---------------------------------------------------------------------------
@@ -522,7 +530,8 @@ template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
                                             const uint32_t R, const uint32_t Eq, const uint32_t win_base,
                                             SelShared &S, const SelectArgs &A, const uint32_t outoff,
-                                            uint32_t *tau_next, uint32_t *expect, uint32_t *q_e)
+                                            uint32_t *tau_next, uint32_t *expect, uint32_t *q_e,
+                                            uint32_t *t_out)
 {
     const uint32_t tid = threadIdx.x;
     const bool measurable = (R != 0) && (cN >= R);
@@ -671,6 +680,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
         return;
     }
     const uint32_t T = (pfx << lowbits) | (uint32_t)b3;
+    *t_out = T;
 
     // ---- ordered emission
     uint32_t run_sel = 0, run_eq = 0;
@@ -874,6 +884,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     const uint32_t thi = (td.off + td.n - 1) / TILE;
     const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
     bool dense = (!td.big) || A.force_dense;
+    if (j == 0 && tid == 0 && A.pending) *A.pending = 0;   // every reader of this call has finished
     if (pe.seg) {
         // planned for the segmented kernels; only a tensor they handed over is taken here
         const uint32_t status = A.segstate[j].status;
@@ -996,6 +1007,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
         if (A.write_hint && tid == 0) {
             A.tau[j] = 1u;
             A.hint2[j] = 0u;
+            A.tprev[j] = 0u;
         }
         return;
     }
@@ -1005,7 +1017,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     if (td.big && A.write_hint)
         R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, A.hint2[j], A.m, &Eq);
 
-    uint32_t tau_next = 0, expect = 0, q_e = 0;
+    uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
     // every candidate key is >= kmin (>= the collection threshold): the window starts there
     const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (kmin >> 11);
     if (dense) {
@@ -1015,17 +1027,17 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
             for (uint32_t p = tid; p < td.n; p += SEL_THREADS) lv[p] = __float_as_uint(A.state[td.off + p]);
             __syncthreads();
             SrcDenseLds src{lv, td.off};
-            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e);
+            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
         } else {
             SrcDense src{A.state, td.off};
-            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e);
+            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
         }
     } else if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e);
+        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
     } else {
         SrcList src{glist};
-        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e);
+        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
     }
 
     if (td.big && A.write_hint && tid == 0) {
@@ -1039,6 +1051,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
         if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;   // keep the hint finite
         A.tau[j] = tn;
         A.hint2[j] = expect;
+        A.tprev[j] = t_k;
     }
 }
 
@@ -1061,14 +1074,29 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
 // the k-th key beyond the window, a prefix list that outgrows PFX_CAP) is marked
 // SEG_FALLBACK and selected from the state buffer by k_select afterwards.
 
+// First bin (key >> SEG_LOWBITS) of a tensor's window histogram.  Candidates start at
+// the collection threshold; when that lies far below the k-th key of the previous
+// selection on this stream (a relaxed hint), the window is centred on that key instead,
+// so that it reaches half an octave to either side of it.  Keys below the window are
+// counted into bin 0, which then holds no usable rank.
+__device__ __forceinline__ uint32_t seg_window_base(uint32_t tau_cur, uint32_t t_prev)
+{
+    const uint32_t b_tau = tau_cur >> SEG_LOWBITS;
+    const uint32_t b_prev = t_prev >> SEG_LOWBITS;
+    const uint32_t b_mid = (b_prev > SEG_WBINS / 2) ? (b_prev - SEG_WBINS / 2) : 0u;
+    return max(b_tau, b_mid);
+}
+
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
 {
     __shared__ uint32_t h[SEG_WBINS];
     __shared__ uint32_t tpos[SEG_TILES];
     __shared__ uint32_t tstart[SEG_TILES];
     __shared__ uint32_t wsum[SEG_THREADS / 64];
+    if (A.round != 0 && *A.pending == 0) return;
     const SegDesc sd = A.segtab[blockIdx.x];
     if (!A.plan[sd.j].seg) return;
+    if (A.round != 0 && A.segstate[sd.j].status != SEG_PENDING) return;
     const TensorDesc td = A.tdesc[sd.j];
     const uint32_t tid = threadIdx.x;
     for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) h[b] = 0;
@@ -1092,7 +1120,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
     const bool any_ovf = __syncthreads_or(ovf) != 0;
 
     uint2 *dst = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
-    const uint32_t win_base = A.tau[sd.j] >> SEG_LOWBITS;
+    const uint32_t win_base = seg_window_base(A.tau[sd.j], A.tprev[sd.j]);
     // entry e of the segment: tile = last one whose first position is <= e
     for (uint32_t eb = 0; eb < cs; eb += 4 * SEG_THREADS) {
         uint2 ent[4];
@@ -1143,9 +1171,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     __shared__ int res[6];
     __shared__ uint32_t wsum[SEG_THREADS / 64];
     __shared__ uint32_t lowest;
+    if (A.round != 0 && *A.pending == 0) return;
     const uint32_t j = blockIdx.x;
     const PlanEntry pe = A.plan[j];
     if (!pe.seg) return;
+    if (A.round != 0 && A.segstate[j].status != SEG_PENDING) return;
     const TensorDesc td = A.tdesc[j];
     const uint32_t tid = threadIdx.x;
     uint32_t *gh = A.whist + (size_t)j * HBINS;
@@ -1161,7 +1191,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     const uint32_t c = block_sum(mine, wsum, SEG_THREADS / 64);
     if (mylow != 0xFFFFFFFFu) atomicMin(&lowest, mylow);
     const uint32_t tau_cur = A.tau[j];
-    const uint32_t win_base = tau_cur >> SEG_LOWBITS;
+    const uint32_t win_base = seg_window_base(tau_cur, A.tprev[j]);
+    const int bin_min = (win_base > (tau_cur >> SEG_LOWBITS)) ? 1 : 0;   // bin 0 mixes in lower keys
     uint32_t R = 0, Eq = 0;
     if (A.write_hint) R = hint_rank<OP>(td, pe, !A.exact_mode, c, A.hint2[j], A.m, &Eq);
     const bool measurable = (R != 0) && (c >= R);
@@ -1169,7 +1200,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     if (tid == 0) {
         SegState *st = &A.segstate[j];
         const int bk = res[0], bR = res[2];
-        const bool ok = (st->ovf == 0) && (c >= pe.k) && bk >= 0 && bk < (int)SEG_WBINS - 1;
+        const bool ok = (st->ovf == 0) && (c >= pe.k) && bk >= bin_min && bk < (int)SEG_WBINS - 1;
         // fewer candidates than k with every nonzero collected: k_select completes with zeros
         const bool zf = (st->ovf == 0) && (c < pe.k) && (tau_cur <= 1u);
         st->ovf = 0;
@@ -1177,25 +1208,33 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
         st->pfx = win_base + (uint32_t)max(bk, 0);
         st->r2 = (uint32_t)res[1];
         st->T = 0;
-        st->status = ok ? SEG_ACTIVE : (zf ? SEG_ZEROFILL : SEG_FALLBACK);
+        // a failed first attempt is collected again by the repair round; a failed repair
+        // (e.g. one value filling a whole histogram bucket) is left to k_select
+        const uint32_t bad = (A.round == 0) ? SEG_PENDING : SEG_FALLBACK;
+        st->status = ok ? (SEG_ACTIVE + A.round) : (zf ? SEG_ZEROFILL : bad);
         if (!ok && !zf) {
-            atomicAdd(&A.stats->fallback_tensors, 1ull);
-            atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+            if (A.round == 0) {
+                atomicAdd(A.pending, 1u);
+            } else {
+                atomicAdd(&A.stats->fallback_tensors, 1ull);
+                atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+            }
         } else if (ok) {
             atomicAdd(&A.stats->candidates, (unsigned long long)c);
             atomicAdd(&A.stats->segmented_tensors, 1ull);
+            if (A.round != 0) atomicAdd(&A.stats->repaired_tensors, 1ull);
             if (A.write_hint) {
                 uint32_t tn = 0, expect = 0;
-                if (measurable && bR >= 0 && bR < (int)SEG_WBINS - 1) {
+                if (measurable && bR >= bin_min && bR < (int)SEG_WBINS - 1) {
                     const uint32_t edge = (win_base + (uint32_t)bR) << SEG_LOWBITS;
                     tn = edge ? edge : 1u;
                     expect = R - (uint32_t)res[3] + h[bR];
                     const int bE = res[4];
-                    if (bE >= 0 && bE < (int)SEG_WBINS - 1)
+                    if (bE >= bin_min && bE < (int)SEG_WBINS - 1)
                         tn = hint_scaled(tn, (win_base + (uint32_t)bE) << SEG_LOWBITS, tau_cur);
                 }
                 if (tn == 0) {
-                    const uint32_t kmin = (lowest == 0xFFFFFFFFu) ? 0xFFFFFFFFu
+                    const uint32_t kmin = (lowest == 0xFFFFFFFFu || (int)lowest < bin_min) ? 0xFFFFFFFFu
                                                                  : max((win_base + lowest) << SEG_LOWBITS, tau_cur);
                     tn = hint_relaxed(tau_cur, kmin);
                     expect = 0;
@@ -1216,14 +1255,35 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
     __shared__ uint2 stage[PFX_STAGE];
     __shared__ uint32_t nstage, base;
     const SegDesc sd = A.segtab[blockIdx.x];
+    if (A.round != 0 && *A.pending == 0) return;
     if (!A.plan[sd.j].seg) return;
     SegState *st = &A.segstate[sd.j];
-    if (st->status != SEG_ACTIVE) return;
-    const uint32_t pfx = st->pfx;
+    const uint32_t status = st->status;
     const uint32_t cs = A.segcnt[blockIdx.x];
     const uint2 *src = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
-    uint4 *plist = A.pfxlist + (size_t)A.tdesc[sd.j].pfx_slot * PFX_CAP;
     const uint32_t tid = threadIdx.x;
+    if (A.round != 0 && status == SEG_COUNT) {
+        // the k-th key T is known (the prefix list had overflowed): count this segment's
+        // entries above T and equal to T
+        const uint32_t T = st->T;
+        uint32_t g = 0, q = 0;
+        for (uint32_t e = tid; e < cs; e += SEG_THREADS) {
+            const uint32_t key = src[e].y & 0x7FFFFFFFu;
+            g += (key > T) ? 1u : 0u;
+            q += (key == T) ? 1u : 0u;
+        }
+        const uint32_t G = block_sum(g, wsum, SEG_THREADS / 64);
+        const uint32_t Q = block_sum(q, wsum, SEG_THREADS / 64);
+        if (tid == 0) {
+            A.segG1[blockIdx.x] = G;
+            A.segQ[blockIdx.x] = Q;
+        }
+        return;
+    }
+    if (status != SEG_ACTIVE + A.round) return;
+    const uint32_t pfx = st->pfx;
+    uint4 *plist = A.pfxlist + (size_t)A.tdesc[sd.j].pfx_slot * PFX_CAP;
+    uint32_t *glow = A.whist + (size_t)sd.j * HBINS;   // low key bits of the entries sharing the prefix
     if (tid == 0) nstage = 0;
     __syncthreads();
     uint32_t g1 = 0;
@@ -1242,6 +1302,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
                 if (hi12 > pfx) {
                     ++g1;
                 } else if (hi12 == pfx) {
+                    atomicAdd(&glow[ent[u].y & (SEG_LBINS - 1u)], 1u);
                     const uint32_t p = atomicAdd(&nstage, 1u);
                     if (p < PFX_STAGE) stage[p] = ent[u];
                 }
@@ -1275,47 +1336,74 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
     __shared__ uint32_t rowsum[64];
     __shared__ int res[6];
     __shared__ uint32_t wsum[RANK_THREADS / 64];
+    if (A.round != 0 && *A.pending == 0) return;
     const uint32_t j = blockIdx.x;
     const PlanEntry pe = A.plan[j];
     if (!pe.seg) return;
     SegState *st = &A.segstate[j];
-    if (st->status != SEG_ACTIVE) return;
+    const uint32_t status = st->status;
+    // SEG_COUNT (repair round only): the k-th key is known, the prefix kernel has just
+    // counted every segment against it
+    const bool counted = (A.round != 0) && (status == SEG_COUNT);
+    if (status != SEG_ACTIVE + A.round && !counted) return;
     const TensorDesc td = A.tdesc[j];
     const uint32_t tid = threadIdx.x;
     const uint32_t m = st->pfxcount;
     const uint32_t r2 = st->r2, pfx = st->pfx;
-    if (m > PFX_CAP || m < r2) {
-        // too many keys share the prefix (or an inconsistent count): leave it to k_select
-        if (tid == 0) {
-            st->status = SEG_FALLBACK;
-            atomicAdd(&A.stats->fallback_tensors, 1ull);
-            atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
-            if (m < r2) atomicAdd(&A.stats->internal_errors, 1ull);
-        }
-        return;
-    }
-    const uint4 *plist = A.pfxlist + (size_t)td.pfx_slot * PFX_CAP;
-    for (uint32_t b = tid; b < SEG_LBINS; b += RANK_THREADS) h[b] = 0;
+    uint32_t T, rT;   // the k-th key; entries equal to it that are taken, lowest index first
     for (uint32_t s = tid; s < td.nseg; s += RANK_THREADS) { sG[s] = 0; sQ[s] = 0; }
-    __syncthreads();
-    for (uint32_t p = tid; p < m; p += RANK_THREADS) atomicAdd(&h[plist[p].y & (SEG_LBINS - 1u)], 1u);
-    find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, 0u, 0u, rowsum, res);
-    const int b3 = res[0];
-    const uint32_t rT = (uint32_t)res[1];   // entries equal to T that are taken, lowest index first
-    if (b3 < 0) {
-        if (tid == 0) {
-            st->status = SEG_FALLBACK;
-            atomicAdd(&A.stats->internal_errors, 1ull);
+    if (counted) {
+        T = st->T;
+        rT = r2;
+        for (uint32_t s = tid; s < td.nseg; s += RANK_THREADS) sQ[s] = A.segQ[td.seg_first + s];
+        __syncthreads();
+    } else {
+        // low key bits of the entries sharing the prefix: counted by the prefix kernel
+        uint32_t *gl = A.whist + (size_t)j * HBINS;
+        for (uint32_t b = tid; b < SEG_LBINS; b += RANK_THREADS) {
+            h[b] = gl[b];
+            gl[b] = 0;   // clean for the next use
         }
-        return;
+        find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, 0u, 0u, rowsum, res);
+        const int b3 = res[0];
+        if (b3 < 0 || m < r2) {
+            if (tid == 0) {
+                st->status = SEG_FALLBACK;
+                atomicAdd(&A.stats->fallback_tensors, 1ull);
+                atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+                atomicAdd(&A.stats->internal_errors, 1ull);
+            }
+            return;
+        }
+        T = (pfx << SEG_LOWBITS) | (uint32_t)b3;
+        rT = (uint32_t)res[1];
+        if (m > PFX_CAP) {
+            // too many entries share the prefix for the list: the repair round counts every
+            // segment against T instead (a second overflow cannot happen there)
+            if (tid == 0) {
+                st->T = T;
+                st->r2 = rT;
+                A.tprev[j] = T;
+                if (A.round == 0) {
+                    st->status = SEG_COUNT;
+                    atomicAdd(A.pending, 1u);
+                } else {
+                    st->status = SEG_FALLBACK;
+                    atomicAdd(&A.stats->fallback_tensors, 1ull);
+                    atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+                }
+            }
+            return;
+        }
+        const uint4 *plist = A.pfxlist + (size_t)td.pfx_slot * PFX_CAP;
+        for (uint32_t p = tid; p < m; p += RANK_THREADS) {
+            const uint4 e = plist[p];
+            const uint32_t low = e.y & (SEG_LBINS - 1u);
+            if (low > (uint32_t)b3) atomicAdd(&sG[e.z], 1u);
+            else if (low == (uint32_t)b3) atomicAdd(&sQ[e.z], 1u);
+        }
+        __syncthreads();
     }
-    for (uint32_t p = tid; p < m; p += RANK_THREADS) {
-        const uint4 e = plist[p];
-        const uint32_t low = e.y & (SEG_LBINS - 1u);
-        if (low > (uint32_t)b3) atomicAdd(&sG[e.z], 1u);
-        else if (low == (uint32_t)b3) atomicAdd(&sQ[e.z], 1u);
-    }
-    __syncthreads();
     // segments in order: ties are taken lowest index first, i.e. earlier segments first
     uint32_t carry_q = 0, carry_o = 0;
     for (uint32_t sb = 0; sb < td.nseg; sb += RANK_THREADS) {
@@ -1332,7 +1420,12 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
         carry_o += toto;
     }
     if (tid == 0) {
-        st->T = (pfx << SEG_LOWBITS) | (uint32_t)b3;
+        st->T = T;
+        A.tprev[j] = T;
+        if (counted) {
+            st->status = SEG_ACTIVE + A.round;
+            atomicAdd(&A.stats->repaired_tensors, 1ull);
+        }
         if (carry_o != pe.k) atomicAdd(&A.stats->internal_errors, 1ull);
     }
 }
@@ -1342,10 +1435,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
 {
     __shared__ uint32_t wsum[SEG_THREADS / 64];
     const SegDesc sd = A.segtab[blockIdx.x];
+    if (A.round != 0 && *A.pending == 0) return;
     const PlanEntry pe = A.plan[sd.j];
     if (!pe.seg) return;
     const SegState *st = &A.segstate[sd.j];
-    if (st->status != SEG_ACTIVE) return;
+    if (st->status != SEG_ACTIVE + A.round) return;
     const uint32_t T = st->T;
     const uint32_t seg = A.tdesc[sd.j].seg_first + sd.sidx;
     const uint2 so = A.segOut[seg];
@@ -1399,6 +1493,43 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
         run_sel += G + min(Q, rem);
         run_eq += Q;
     }
+}
+
+// Repair round: the streaming pass again, read-only, over the segments of the tensors
+// left SEG_PENDING -- a histogram pass (MODE_HIST, counting the segment's own tensor
+// only) and, after k_pick, a collecting pass (MODE_COLLECT) with the fresh threshold.
+// A border tile shared with a neighbouring tensor is rewritten whole; the neighbour's
+// candidates in it are no longer needed by then (its selection is complete, or it is
+// pending too and rewrites the same values).
+template <int MODE, bool VEC>
+__global__ __launch_bounds__(STREAM_THREADS) void k_seg_restream(const StreamArgs A, const SegArgs G,
+                                                                const uint32_t *__restrict__ toff,
+                                                                const uint32_t *__restrict__ tau)
+{
+    __shared__ uint32_t lhist[MODE == MODE_HIST ? HBINS : 1];
+    if (*G.pending == 0) return;
+    const SegDesc sd = G.segtab[blockIdx.x];
+    if (!G.plan[sd.j].seg || G.segstate[sd.j].status != SEG_PENDING) return;
+    if (MODE == MODE_HIST) {
+        for (uint32_t b = threadIdx.x; b < HBINS; b += STREAM_THREADS) lhist[b] = 0;
+        __syncthreads();
+    }
+    const uint32_t wave = uniform(threadIdx.x >> 6);
+    for (uint32_t i = wave; i < sd.ntiles; i += WAVES_PER_BLOCK)
+        process_tile<OP_IDENT, MODE, VEC>(A, toff, tau, sd.tile0 + i, lhist, (int)sd.j, (int)sd.j);
+    flush_hist<MODE>(lhist, A.ghist, (int)sd.j);
+}
+
+void launch_seg_recollect(const StreamArgs &a, bool vec, const SegArgs &g, void *stream)
+{
+    hipStream_t st = (hipStream_t)stream;
+    if (g.nseg_total == 0) return;
+    const dim3 grid(g.nseg_total), block(STREAM_THREADS);
+    if (vec) hipLaunchKernelGGL((k_seg_restream<MODE_HIST, true>), grid, block, 0, st, a, g, a.toff, a.tau);
+    else hipLaunchKernelGGL((k_seg_restream<MODE_HIST, false>), grid, block, 0, st, a, g, a.toff, a.tau);
+    launch_pick(g.tdesc, g.plan, a.ghist, g.tau, g.tprev, g.stats, g.J, stream, g.segstate, g.pending);
+    if (vec) hipLaunchKernelGGL((k_seg_restream<MODE_COLLECT, true>), grid, block, 0, st, a, g, a.toff, a.tau);
+    else hipLaunchKernelGGL((k_seg_restream<MODE_COLLECT, false>), grid, block, 0, st, a, g, a.toff, a.tau);
 }
 
 void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1)

@@ -38,7 +38,7 @@ class DgsError(RuntimeError):
 class _Stats(ctypes.Structure):
     _fields_ = [(n, ctypes.c_uint64) for n in (
         "calls_worker", "calls_pull", "calls_push", "exact_calls", "fallback_tensors",
-        "fallback_elems", "candidates", "internal_errors", "segmented_tensors")]
+        "fallback_elems", "candidates", "internal_errors", "segmented_tensors", "repaired_tensors")]
 
 
 _lib = None
@@ -111,6 +111,7 @@ class Stats:
     candidates: int
     internal_errors: int
     segmented_tensors: int = 0
+    repaired_tensors: int = 0
 
 
 class Context:

@@ -83,10 +83,12 @@ def test_segmented_degenerate_value_patterns(oracle, name):
                       seg_mode=dgs.SEG_ALWAYS)
 
 
-def test_segmented_threshold_jump_falls_back_and_recovers(oracle):
+def test_segmented_threshold_jump_is_repaired(oracle):
     """A gradient scale that jumps by 1e3 puts the k-th key far beyond the window
     above the predicted threshold; a collapse leaves fewer candidates than k.  Both
-    must give the exact result and the following steps must recover."""
+    must give the exact result -- through the repair round (second collection with a
+    threshold from a fresh histogram), not through a dense re-selection -- and the
+    following steps must recover."""
     off = synth.offsets_from_sizes([400_000, 64])
     n = int(off[-1])
     rng = np.random.default_rng(46)
@@ -95,7 +97,7 @@ def test_segmented_threshold_jump_falls_back_and_recovers(oracle):
              g[5] * np.float32(1e-6), g[6], g[7]]
     st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.002, residual=True,
                            seg_mode=dgs.SEG_ALWAYS)
-    assert st.fallback_tensors >= 1 and st.segmented_tensors >= 3
+    assert st.repaired_tensors >= 2 and st.fallback_tensors == 0 and st.segmented_tensors == 8
 
 
 def test_segmented_server_pull(oracle):
