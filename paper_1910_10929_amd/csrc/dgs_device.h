@@ -31,7 +31,7 @@ constexpr uint32_t HSHIFT = 31 - HBITS;
 // Selection workgroup.
 constexpr uint32_t SEL_THREADS = 1024;
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
-constexpr uint32_t SEL_LDS_LIST = 8192;            // candidates kept in LDS (64 KB)
+constexpr uint32_t SEL_LDS_LIST = 16384;           // candidates kept in LDS (128 KB)
 // Above this density candidates stop paying off; such requests select densely.
 constexpr double DENSE_DENSITY = 1.0 / 32.0;
 

@@ -875,7 +875,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     __shared__ SelShared S;
     __shared__ uint2 llist[SEL_LDS_LIST];
     __shared__ uint32_t tpos[SEL_BATCH_TILES];   // per tile of the batch: position in the list
-    __shared__ uint32_t tcw[SEL_BATCH_TILES];    // per tile of the batch: count | first slot << 16
+    __shared__ uint16_t tcnt[SEL_BATCH_TILES];   // per tile of the batch: this tensor's candidates
+    __shared__ uint32_t start0;                  // first slot of the tensor in a first tile shared with its predecessor
     const uint32_t j = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const TensorDesc td = A.tdesc[j];
@@ -930,7 +931,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                 uint32_t ctot;
                 const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
                 tpos[u * SEL_THREADS + tid] = pos;
-                tcw[u * SEL_THREADS + tid] = cnt | (start << 16);
+                tcnt[u * SEL_THREADS + tid] = (uint16_t)cnt;
+                if (hs) start0 = start;
                 c += ctot;
             }
             __syncthreads();
@@ -940,8 +942,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                 const uint32_t li = it * SEL_QUADS + ql;
                 const uint32_t tl = cb + li;
                 if (tl >= ntl) continue;
-                const uint32_t cw = tcw[li];
-                const uint32_t cnt = cw & 0xFFFFu, start = cw >> 16;
+                const uint32_t cnt = tcnt[li];
+                const uint32_t start = (head_shared && tl == 0) ? start0 : 0u;
                 const uint32_t pos = tpos[li];
                 if (cnt == 0) continue;
                 uint32_t i0 = 0;
@@ -956,29 +958,30 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                     }
                     i0 = HEAD;
                 }
-                if (sub == 0 && i0 < cnt) {
-                    // the rest of a crowded tile, four independent loads at a time
-                    // (entry q of the tile: heads for q < HEAD, slots beyond)
+                if (i0 < cnt) {
+                    // the rest of a crowded tile: the four lanes interleave, each with four
+                    // independent loads at a time (entry q of the tile: heads for q < HEAD,
+                    // slots beyond)
                     const uint2 *hd = heads + (size_t)(tlo + tl) * HEAD;
                     const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT;
-                    for (uint32_t i = i0; i < cnt; i += 4) {
+                    for (uint32_t i = i0 + sub; i < cnt; i += 16) {
                         uint2 e[4];
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) {
-                            const uint32_t q = start + i + v;
-                            e[v] = (i + v < cnt) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
+                            const uint32_t q = start + i + 4 * v;
+                            e[v] = (i + 4 * v < cnt) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
                         }
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) {
-                            if (i + v < cnt) {
-                                put_entry(llist, glist, pos + i + v, e[v]);
+                            if (i + 4 * v < cnt) {
+                                put_entry(llist, glist, pos + i + 4 * v, e[v]);
                                 kmin = min(kmin, e[v].y & 0x7FFFFFFFu);
                             }
                         }
                     }
                 }
             }
-            __syncthreads();   // tpos / tcw are reused by the next batch
+            __syncthreads();   // tpos / tcnt are reused by the next batch
         }
         kmin = wave_min_to_last(kmin);
         if (lane_id() == 63) atomicMin(&S.kmin, kmin);

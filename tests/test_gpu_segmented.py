@@ -138,14 +138,14 @@ def test_segmented_server_pull(oracle):
 
 def test_automatic_mode_mixes_both_selections(oracle):
     """Default mode: the 4.2M-element tensor goes segmented by size, the 300k one stays
-    on the single-workgroup path at density 1e-3 and goes segmented at 0.02 (its
+    on the single-workgroup path at density 1e-3 and goes segmented at 0.03 (its
     candidate list no longer fits one workgroup's LDS)."""
     off = synth.offsets_from_sizes([4_200_000, 64, 300_000])
     n = int(off[-1])
     scales = synth.tensor_scales(3, 50)
     rng = np.random.default_rng(51)
     grads = [synth.gaussian_grads(off, scales, rng) for _ in range(3)]
-    for rho in (1e-3, 0.02):
+    for rho in (1e-3, 0.03):
         st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), rho)
         assert st.fallback_tensors == 0
         assert st.segmented_tensors == (3 if rho == 1e-3 else 6)
