@@ -526,6 +526,22 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
 // 21-bit key prefix of the entry of rank R: *tau_next = its lower edge (>= 1)
 // and *expect = how many entries lie at or above that edge; otherwise both 0.
 // win_base: (collection threshold >> 11) for candidate lists, 0xFFFFFFFF otherwise.
+// Next threshold when fewer candidates (c) than the hinted rank R were collected, all at
+// or above `kmin`: the lowest q of them span `width` keys; the same density is assumed
+// below kmin (it is higher in fact, so this errs towards more candidates), with half as
+// much again for safety, and never below half of the smallest candidate key.
+__device__ __forceinline__ uint32_t hint_extrapolated(uint32_t kmin, uint32_t c, uint32_t R, uint32_t q,
+                                                      uint32_t width)
+{
+    const float delta = 1.5f * (float)(R - c) * (float)width / (float)max(q, 1u);
+    uint32_t tn = (delta < (float)kmin) ? (kmin - (uint32_t)delta) : 1u;
+    if (kmin < 0x7F800000u) {
+        const uint32_t half = __float_as_uint(__uint_as_float(kmin) * 0.5f) & 0x7FFFFFFFu;
+        tn = max(tn, half);
+    }
+    return max(tn, 1u);
+}
+
 template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
                                             const uint32_t R, const uint32_t Eq, const uint32_t win_base,
@@ -567,8 +583,11 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 }
             }
         }
-        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, (measurable && Eq <= cN) ? Eq : 0u, S.rowsum,
-                                    S.res);
+        // third rank: the drift quantile if R is among the candidates; otherwise the entry
+        // below which the lowest quarter of the candidates lies (for the extrapolated hint)
+        const uint32_t qlow = max(cN / 4u, min(cN, 16u));
+        const uint32_t third = measurable ? ((Eq <= cN) ? Eq : 0u) : ((R != 0) ? (cN - qlow + 1u) : 0u);
+        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, third, S.rowsum, S.res);
         const int bk = S.res[0], bR = S.res[2], bE = S.res[4];
         const uint32_t rk = (uint32_t)S.res[1], rR = (uint32_t)S.res[3];
         if (bk >= 0 && bk < 2047 && bR >= 0 && bR < 2047) {
@@ -581,6 +600,9 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 *tau_next = edge ? edge : 1u;
                 *expect = R - rR + S.h[bR];
                 if (bE >= 0 && bE < 2047) *q_e = (win_base + (uint32_t)bE) << 11;
+            } else if (R != 0 && bE >= 0 && bE < 2047) {
+                *tau_next = hint_extrapolated(max(win_base << 11, 1u), cN, R, qlow, ((uint32_t)bE + 1u) << 11);
+                *expect = R;
             }
         }
         __syncthreads();
@@ -1199,7 +1221,9 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     uint32_t R = 0, Eq = 0;
     if (A.write_hint) R = hint_rank<OP>(td, pe, !A.exact_mode, c, A.hint2[j], A.m, &Eq);
     const bool measurable = (R != 0) && (c >= R);
-    find_ranks<SEG_WBINS, SEG_THREADS / 64>(h, pe.k, measurable ? R : pe.k, measurable ? Eq : 0u, rowsum, res);
+    const uint32_t qlow = max(c / 4u, min(c, 16u));
+    const uint32_t third = measurable ? Eq : ((R != 0 && c != 0) ? (c - qlow + 1u) : 0u);
+    find_ranks<SEG_WBINS, SEG_THREADS / 64>(h, pe.k, measurable ? R : pe.k, third, rowsum, res);
     if (tid == 0) {
         SegState *st = &A.segstate[j];
         const int bk = res[0], bR = res[2];
@@ -1235,6 +1259,12 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
                     const int bE = res[4];
                     if (bE >= bin_min && bE < (int)SEG_WBINS - 1)
                         tn = hint_scaled(tn, (win_base + (uint32_t)bE) << SEG_LOWBITS, tau_cur);
+                }
+                if (tn == 0 && !measurable && R != 0 && lowest != 0xFFFFFFFFu && (int)lowest >= bin_min &&
+                    res[4] >= (int)lowest && res[4] < (int)SEG_WBINS - 1) {
+                    const uint32_t kmin = max((win_base + lowest) << SEG_LOWBITS, tau_cur);
+                    tn = hint_extrapolated(kmin, c, R, qlow, ((uint32_t)res[4] - lowest + 1u) << SEG_LOWBITS);
+                    expect = R;
                 }
                 if (tn == 0) {
                     const uint32_t kmin = (lowest == 0xFFFFFFFFu || (int)lowest < bin_min) ? 0xFFFFFFFFu
