@@ -36,7 +36,7 @@ LR, MOMENTUM = 1.0, 0.9
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE, scaled by the same counters on a copy kernel of known size); the
 # summaries are under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 308.47e6, "c3": None, "c5": None}
+MEASURED_TRAFFIC_BYTES = {"c2": 307.98e6, "c3": None, "c5": None}
 
 
 def make_workload(name, density):
@@ -208,7 +208,8 @@ def main():
     torch.cuda.synchronize()
     kinds = {"worker_stream": dgs.PROF_WORKER_STREAM, "worker_select": dgs.PROF_WORKER_SELECT,
              "pull_stream": dgs.PROF_PULL_STREAM, "pull_select": dgs.PROF_PULL_SELECT,
-             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA}
+             "push": dgs.PROF_PUSH, "exact_extra": dgs.PROF_EXACT_EXTRA,
+             "worker_segmented": dgs.PROF_WORKER_SEGMENTED, "pull_segmented": dgs.PROF_PULL_SEGMENTED}
     kernel_us, dom_us = {}, None
     for kname, kind in kinds.items():
         cnt, ms = ctx.profile_read(kind)
@@ -240,6 +241,7 @@ def main():
         "kernel_us": kernel_us,
         "step_algorithmic_GBs": step_bytes / (dt / steps) / 1e9,
         "stats": {"exact_calls": st.exact_calls, "fallback_tensors": st.fallback_tensors,
+                  "segmented_tensors": st.segmented_tensors, "repaired_tensors": st.repaired_tensors,
                   "internal_errors": st.internal_errors},
     }
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(wl, name)
