@@ -16,6 +16,9 @@ constexpr uint32_t CAPT = 256;
 // tensor's candidates with contiguous loads; candidate p >= HEAD of a crowded
 // tile goes to slots[CAPT * t + p].
 constexpr uint32_t HEAD = 8;
+// Candidates of a tile that the streaming wavefront stages in LDS and writes out as
+// whole 64-byte lines (later ones are stored one by one).
+constexpr uint32_t STAGE = 64;
 constexpr uint32_t WAVES_PER_BLOCK = 4;            // one "quad" = 4 tiles = 4096 elements
 constexpr uint32_t STREAM_THREADS = 64 * WAVES_PER_BLOCK;
 // Tensors up to this size are selected directly from the state buffer by one

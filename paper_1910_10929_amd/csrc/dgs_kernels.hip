@@ -30,6 +30,13 @@ __device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_b
 
 __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
 
+// Isolated 4-byte store into a large buffer that a later streaming pass will sweep
+// (state fix-ups, pull zero-writes, the push scatter).  Non-temporal: plain stores
+// leave partially written lines behind in the cache hierarchy, and 1e5 of them were
+// measured to slow the NEXT streaming pass over a 4 GB buffer by 130 us (6 %);
+// non-temporal ones by 15 us.
+__device__ __forceinline__ void store_scattered(float *p, float v) { __builtin_nontemporal_store(v, p); }
+
 // ---------------------------------------------------------------------------
 // streaming pass
 // ---------------------------------------------------------------------------
@@ -90,72 +97,16 @@ __device__ __forceinline__ uint4 span_desc(const uint32_t *__restrict__ toff, ui
     return d;
 }
 
-template <int OP, int MODE, bool VEC>
-__device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t *__restrict__ toff,
-                                             const uint32_t *__restrict__ tau, uint32_t t,
-                                             uint32_t *lhist, int cur, int only = -1)
+// What follows the accumulate for one tile whose 16 values per lane are in `a`:
+// candidate collection against the per-tensor thresholds, or the key histogram.
+template <int MODE>
+__device__ __forceinline__ void tile_tail(const StreamArgs &A, const uint32_t *__restrict__ tau, uint32_t t,
+                                          const uint4 d, const float (&a)[4][4], uint32_t *lhist, int cur,
+                                          uint2 *stage, int only)
 {
     const uint32_t lane = lane_id();
     const uint32_t base = t * TILE;
     const bool full = (base + TILE <= A.n);
-
-    // Issue the tile's vector loads first; the scalar search for the tensors touched by
-    // the tile then runs while they are in flight.
-    float a[4][4];
-    f32x4 g[4], s[4];
-    const bool fast = VEC && full;
-    if (fast) {
-        if (OP == OP_FMA) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-                g[r] = __builtin_nontemporal_load((const f32x4 *)(A.grad + base + r * 256 + lane * 4));
-        }
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-            s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
-    }
-
-    uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
-    if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, min(base + TILE, A.n) - 1u);
-
-    if (fast) {
-        if (OP == OP_FMA) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                f32x4 o;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    a[r][j] = __builtin_fmaf(A.lr, g[r][j], s[r][j]);
-                    o[j] = a[r][j];
-                }
-                *(f32x4 *)(A.state + base + r * 256 + lane * 4) = o;
-            }
-        } else {
-#pragma unroll
-            for (int r = 0; r < 4; ++r)
-#pragma unroll
-                for (int j = 0; j < 4; ++j) a[r][j] = s[r][j];
-        }
-    } else {
-#pragma unroll
-        for (int r = 0; r < 4; ++r)
-#pragma unroll
-            for (int j = 0; j < 4; ++j) {
-                const uint32_t e = base + r * 256 + lane * 4 + j;
-                float v = 0.0f;
-                if (e < A.n) {
-                    if (OP == OP_FMA) {
-                        v = __builtin_fmaf(A.lr, A.grad[e], A.state[e]);
-                        A.state[e] = v;
-                    } else {
-                        v = A.state[e];
-                    }
-                }
-                a[r][j] = v;
-            }
-    }
-    if (MODE == MODE_PLAIN) return;
-
     const uint32_t tA = d.x & 0x7FFFFFFFu, tB = d.y & 0x7FFFFFFFu;
     const uint32_t endA = d.z, begB = d.w;
     const bool straddle = (endA != 0xFFFFFFFFu);
@@ -197,7 +148,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
                 for (int j = 0; j < 4; ++j) {
                     if (f[j]) {
                         const uint2 ent = make_uint2(e0 + j, __float_as_uint(a[r][j]));
-                        if (p < HEAD) myheads[p] = ent;
+                        if (p < STAGE) stage[p] = ent;
                         else if (p < CAPT) myslots[p] = ent;
                         ++p;
                     }
@@ -209,6 +160,17 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
                         runA += (uint32_t)__popcll(ballot64(f[j] && (e0 + j < endA)));
                 }
             }
+        }
+        // The staged candidates leave as whole 64-byte lines (8 entries; the head line
+        // always, also when empty): a full-line store needs no fill from memory, while
+        // scattered 8-byte stores into cold lines were measured to cost the pass 15 %.
+        __builtin_amdgcn_wave_barrier();
+        const uint32_t nst = min(run, STAGE);
+        if (lane < HEAD) myheads[lane] = (lane < nst) ? stage[lane] : make_uint2(0u, 0u);
+        if (nst > HEAD) {   // wave-uniform and rare: the spill lines of a crowded tile
+            const uint32_t nlines = (nst + HEAD - 1u) / HEAD;
+            if (lane >= HEAD && lane < nlines * HEAD)
+                myslots[lane] = (lane < nst) ? stage[lane] : make_uint2(0u, 0u);
         }
         if (!straddle) runA = run;
         if (lane == 0)
@@ -239,12 +201,80 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
 }
 
 template <int OP, int MODE, bool VEC>
+__device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t *__restrict__ toff,
+                                             const uint32_t *__restrict__ tau, uint32_t t,
+                                             uint32_t *lhist, int cur, uint2 *stage, int only = -1)
+{
+    const uint32_t lane = lane_id();
+    const uint32_t base = t * TILE;
+    const bool full = (base + TILE <= A.n);
+    float a[4][4];
+    uint4 d = make_uint4(0, 0, 0xFFFFFFFFu, 0xFFFFFFFFu);
+
+    if (VEC && full) {
+        // Issue the tile's vector loads first; the scalar search for the tensors touched by
+        // the tile then runs while they are in flight.
+        f32x4 g[4], s[4];
+        if (OP == OP_FMA) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                g[r] = __builtin_nontemporal_load((const f32x4 *)(A.grad + base + r * 256 + lane * 4));
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+            s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
+        if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, base + TILE - 1u);
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+                a[r][j] = (OP == OP_FMA) ? __builtin_fmaf(A.lr, g[r][j], s[r][j]) : s[r][j];
+        if (MODE != MODE_PLAIN) tile_tail<MODE>(A, tau, t, d, a, lhist, cur, stage, only);
+        // The state goes out last: this wave never has to wait for the stores to be
+        // acknowledged (the memory counter it would wait on also counts stores).
+        if (OP == OP_FMA) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                f32x4 o;
+#pragma unroll
+                for (int j = 0; j < 4; ++j) o[j] = a[r][j];
+                *(f32x4 *)(A.state + base + r * 256 + lane * 4) = o;
+            }
+        }
+        return;
+    }
+
+    // ragged last tile, or buffers that are only 4-byte aligned
+#pragma unroll
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const uint32_t e = base + r * 256 + lane * 4 + j;
+            float v = 0.0f;
+            if (e < A.n) {
+                if (OP == OP_FMA) {
+                    v = __builtin_fmaf(A.lr, A.grad[e], A.state[e]);
+                    A.state[e] = v;
+                } else {
+                    v = A.state[e];
+                }
+            }
+            a[r][j] = v;
+        }
+    if (MODE == MODE_PLAIN) return;
+    d = span_desc(toff, A.J, base, min(base + TILE, A.n) - 1u);
+    tile_tail<MODE>(A, tau, t, d, a, lhist, cur, stage, only);
+}
+
+template <int OP, int MODE, bool VEC>
 __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
                                                            const uint32_t *__restrict__ toff,
                                                            const uint32_t *__restrict__ tau)
 {
     __shared__ uint32_t lhist[MODE == MODE_HIST ? HBINS : 1];
+    __shared__ uint2 stage_all[MODE == MODE_COLLECT ? WAVES_PER_BLOCK * STAGE : 1];
     const uint32_t wave = uniform(threadIdx.x >> 6);
+    uint2 *stage = stage_all + (MODE == MODE_COLLECT ? wave * STAGE : 0u);
     const uint32_t q0 = blockIdx.x * A.quads_per_block;
     const uint32_t q1 = min(q0 + A.quads_per_block, A.nquads);
     int cur = -1;
@@ -264,7 +294,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_stream(const StreamArgs A,
             }
         }
         const uint32_t t = q * WAVES_PER_BLOCK + wave;
-        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, toff, tau, t, lhist, cur);
+        if (t < A.ntiles) process_tile<OP, MODE, VEC>(A, toff, tau, t, lhist, cur, stage);
     }
     flush_hist<MODE>(lhist, A.ghist, cur);
 }
@@ -748,7 +778,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                     if (pos < k) {
                         A.out_idx[outoff + pos] = ix;
                         A.out_val[outoff + pos] = __uint_as_float(vb[i]);
-                        A.state[ix] = (OP == SEL_WORKER) ? (A.m * __uint_as_float(vb[i])) : 0.0f;
+                        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * __uint_as_float(vb[i])) : 0.0f);
                     }
                     ++pos;
                 }
@@ -837,14 +867,14 @@ __device__ __forceinline__ void zero_fill_emit(const SrcList src, const uint32_t
         const float v = A.state[ix];
         A.out_idx[pe.outoff + q] = ix;
         A.out_val[pe.outoff + q] = v;
-        A.state[ix] = (OP == SEL_WORKER) ? (A.m * v) : 0.0f;
+        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * v) : 0.0f);
     }
     for (uint32_t p = P + tid; p < c; p += SEL_THREADS) {
         const uint32_t ix = src.index(p);
         const float v = __uint_as_float(src.bits(p));
         A.out_idx[pe.outoff + z + p] = ix;
         A.out_val[pe.outoff + z + p] = v;
-        A.state[ix] = (OP == SEL_WORKER) ? (A.m * v) : 0.0f;
+        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * v) : 0.0f);
     }
 }
 
@@ -1517,7 +1547,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
                     if (pos < pe.k) {
                         A.out_idx[pe.outoff + pos] = v[i].x;
                         A.out_val[pe.outoff + pos] = __uint_as_float(v[i].y);
-                        A.state[v[i].x] = (OP == SEL_WORKER) ? (A.m * __uint_as_float(v[i].y)) : 0.0f;
+                        store_scattered(&A.state[v[i].x], (OP == SEL_WORKER) ? (A.m * __uint_as_float(v[i].y)) : 0.0f);
                     }
                     ++pos;
                 }
@@ -1540,6 +1570,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_seg_restream(const StreamArg
                                                                 const uint32_t *__restrict__ tau)
 {
     __shared__ uint32_t lhist[MODE == MODE_HIST ? HBINS : 1];
+    __shared__ uint2 stage_all[MODE == MODE_COLLECT ? WAVES_PER_BLOCK * STAGE : 1];
     if (*G.pending == 0) return;
     const SegDesc sd = G.segtab[blockIdx.x];
     if (!G.plan[sd.j].seg || G.segstate[sd.j].status != SEG_PENDING) return;
@@ -1548,8 +1579,9 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_seg_restream(const StreamArg
         __syncthreads();
     }
     const uint32_t wave = uniform(threadIdx.x >> 6);
+    uint2 *stage = stage_all + (MODE == MODE_COLLECT ? wave * STAGE : 0u);
     for (uint32_t i = wave; i < sd.ntiles; i += WAVES_PER_BLOCK)
-        process_tile<OP_IDENT, MODE, VEC>(A, toff, tau, sd.tile0 + i, lhist, (int)sd.j, (int)sd.j);
+        process_tile<OP_IDENT, MODE, VEC>(A, toff, tau, sd.tile0 + i, lhist, (int)sd.j, stage, (int)sd.j);
     flush_hist<MODE>(lhist, A.ghist, (int)sd.j);
 }
 
@@ -1608,7 +1640,7 @@ __global__ __launch_bounds__(256) void k_push(float *model, float *diff, uint32_
     const uint32_t b = blockIdx.y + first_buf;
     float *dst = (b == 0) ? model : diff + (size_t)(b - 1) * n;
     const uint32_t i = idx[e];
-    if (i < n) dst[i] = dst[i] - val[e];
+    if (i < n) store_scattered(&dst[i], dst[i] - val[e]);
 }
 
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
@@ -1757,7 +1789,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, ui
                     const uint32_t e = base + r * 256 + lane * 4 + j;
                     out_idx[p] = e;
                     out_val[p] = a[r][j];
-                    row[e] = 0.0f;
+                    store_scattered(&row[e], 0.0f);
                     ++p;
                 }
             }
