@@ -173,6 +173,33 @@ int dgs_server_pull(dgs_ctx *ctx, uint32_t worker_id, double density,
                     uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/);
 
 /*
+ * The server state as Algorithm 2 prints it (Eq. 3-6), an alternative to the
+ * difference rows above: one global model (theta_0 + M) and, per worker, what that
+ * worker has been sent so far, sent_k = theta_0 + v_k.  A push then touches the model
+ * only (nnz read-modify-writes, independent of W); a pull streams two buffers
+ * (8 bytes per parameter instead of 4).  Worth it for many workers or dense pushes.
+ *
+ *   dgs_server_attach_sent   W rows of n floats, row-major, caller-allocated, each row
+ *                            initialised by the caller to the initial model theta_0.
+ *   dgs_server_push_model    model[idx] -= val  ("M <- M - decode(g)", Eq. 1); idx strictly
+ *                            ascending; DGS_OPT_VALIDATE as for dgs_server_push.
+ *   dgs_server_pull_sent     G = per tensor the k_j largest-magnitude entries of
+ *                            model - sent_k (one fp32 subtraction per element; the
+ *                            printed "G <- M - v_k" followed by the threshold loop), then
+ *                            sent_k[idx] += val ("v_k <- v_k + G", the sign Eq. 4 and
+ *                            Eq. 6 require; one fp32 addition).  Outputs as in
+ *                            dgs_server_pull.  In exact arithmetic this is the same message
+ *                            as dgs_server_pull's; in fp32 the two forms round differently.
+ * A context uses one of the two forms for a given worker id: they share that worker's
+ * threshold hints.
+ */
+int dgs_server_attach_sent(dgs_ctx *ctx, float *sent);
+int dgs_server_push_model(dgs_ctx *ctx, float *model, const uint32_t *idx, const float *val,
+                          uint64_t nnz);
+int dgs_server_pull_sent(dgs_ctx *ctx, const float *model, uint32_t worker_id, double density,
+                         uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/);
+
+/*
  * The server answers `worker_id` without secondary compression (Algorithm 2 with
  * the switch off; Eq. 3-4): G = every entry of D_k with a nonzero magnitude,
  * ascending; afterwards D_k == 0.  nnz is data dependent: the call waits for

@@ -27,7 +27,8 @@
  *   - the server keeps, per worker k, D_k = M - v_k (the part of the accumulated
  *     update M not yet sent to k).  A push subtracts the decoded update from the
  *     model and from every D_w (Eq. 1, Eq. 3); a pull sends the top-k of D_k and
- *     zeroes what it sent (Eq. 6: v_k += G  <=>  D_k -= G).
+ *     zeroes what it sent (Eq. 6: v_k += G  <=>  D_k -= G).  The printed form (global
+ *     model and v_k per worker) is given as well, see dgs_oracle_server_pull_sent.
  */
 #include <math.h>
 #include <stdint.h>
@@ -251,6 +252,58 @@ int dgs_oracle_server_pull(float *diff_k, const uint64_t *offsets, uint32_t J,
         *nnz = o;
     }
     free(sel);
+    return rc;
+}
+
+/*
+ * The same server step with the state Algorithm 2 prints: one global model
+ * (theta_0 + M) and sent_k = theta_0 + v_k per worker.
+ *   push:  M <- M - decode(g)  (Eq. 1) touches the model only;
+ *   pull:  G <- M - v_k (dense, one fp32 subtraction per element), per tensor keep the
+ *          k_j largest magnitudes of G (the threshold loop), send them, then
+ *          v_k <- v_k + G on what was sent (Eq. 6; Eq. 4 fixes the sign).
+ */
+int dgs_oracle_server_push_model(float *model, uint64_t n, const uint32_t *idx, const float *val,
+                                 uint64_t nnz)
+{
+    uint64_t e;
+    for (e = 0; e < nnz; ++e) {
+        if (idx[e] >= n) return ORACLE_EINVAL;
+        model[idx[e]] = model[idx[e]] - val[e];
+    }
+    return ORACLE_OK;
+}
+
+int dgs_oracle_server_pull_sent(const float *model, float *sent_k, const uint64_t *offsets, uint32_t J,
+                                double density, uint32_t *idx, float *val, uint64_t *nnz)
+{
+    uint64_t n = offsets[J], i, o = 0;
+    uint32_t j;
+    uint8_t *sel;
+    float *G;
+    int rc = ORACLE_OK;
+    if (!(density > 0.0) || density > 1.0) return ORACLE_EINVAL;
+    sel = (uint8_t *)malloc(n ? n : 1);
+    G = (float *)malloc((n ? n : 1) * sizeof(float));
+    if (!sel || !G) { free(sel); free(G); return ORACLE_ENOMEM; }
+    for (i = 0; i < n; ++i) G[i] = model[i] - sent_k[i];
+    for (j = 0; j < J && rc == ORACLE_OK; ++j) {
+        uint64_t b = offsets[j], nj = offsets[j + 1] - b;
+        rc = select_topk(G + b, nj, dgs_oracle_k(density, nj), sel + b);
+    }
+    if (rc == ORACLE_OK) {
+        for (i = 0; i < n; ++i) {
+            if (sel[i]) {
+                idx[o] = (uint32_t)i;
+                val[o] = G[i];
+                ++o;
+                sent_k[i] = sent_k[i] + G[i];
+            }
+        }
+        *nnz = o;
+    }
+    free(sel);
+    free(G);
     return rc;
 }
 

@@ -54,6 +54,10 @@ def lib():
                                                  ctypes.c_uint64, _c_u64p]
         L.dgs_oracle_apply_sparse.argtypes = [_c_f32p, ctypes.c_uint64, _c_u32p, _c_f32p,
                                               ctypes.c_uint64, ctypes.c_float]
+        L.dgs_oracle_server_push_model.argtypes = [_c_f32p, ctypes.c_uint64, _c_u32p, _c_f32p,
+                                                   ctypes.c_uint64]
+        L.dgs_oracle_server_pull_sent.argtypes = [_c_f32p, _c_f32p, _c_u64p, ctypes.c_uint32,
+                                                  ctypes.c_double, _c_u32p, _c_f32p, _c_u64p]
         _lib = L
     return _lib
 
@@ -137,6 +141,27 @@ def server_pull(diff: np.ndarray, k: int, offsets: np.ndarray, density: float):
     assert row.flags.c_contiguous
     _check(lib().dgs_oracle_server_pull(_f32(row), _u64(offsets), J, float(density), _u32(idx),
                                         _f32(val), ctypes.byref(out)), "server_pull")
+    assert out.value == K
+    return idx, val
+
+
+def server_push_model(model: np.ndarray, idx: np.ndarray, val: np.ndarray) -> None:
+    """Printed form of Algorithm 2: the push touches the global model only."""
+    _check(lib().dgs_oracle_server_push_model(_f32(model), model.size, _u32(idx), _f32(val), idx.size),
+           "server_push_model")
+
+
+def server_pull_sent(model: np.ndarray, sent: np.ndarray, k: int, offsets: np.ndarray, density: float):
+    """Printed form of Algorithm 2: G = top-k of model - sent[k]; sent[k] += G.  Returns (idx, val)."""
+    J = len(offsets) - 1
+    _, K = nnz(offsets, density)
+    idx = np.zeros(K, dtype=np.uint32)
+    val = np.zeros(K, dtype=np.float32)
+    out = ctypes.c_uint64(0)
+    row = sent[k]
+    assert row.flags.c_contiguous
+    _check(lib().dgs_oracle_server_pull_sent(_f32(model), _f32(row), _u64(offsets), J, float(density),
+                                             _u32(idx), _f32(val), ctypes.byref(out)), "server_pull_sent")
     assert out.value == K
     return idx, val
 

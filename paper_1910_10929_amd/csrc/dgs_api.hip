@@ -129,6 +129,7 @@ struct dgs_ctx {
     uint32_t nseg_total = 0;
     std::vector<uint32_t> nseg;        // per tensor: segments (0 = never segmented)
     float *diff = nullptr;
+    float *sent = nullptr;             // W rows: what each worker has been sent (model - sent_k form)
     // plan cache
     PlanSlot plan_slot[NPLAN];
     PlanEntry *plan_stage = nullptr;   // pinned host, NPLAN * J
@@ -279,6 +280,9 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     if (nnz_out) *nnz_out = K;
 
     const bool vec = aligned16(state) && (op_stream == OP_IDENT || aligned16(grad));
+    // the read-only pass that sees the same values again (second pass of the non-predicted path,
+    // repair round): the worker's are in `state` by then, a model - sent_k pull recomputes them
+    const int op_again = (op_stream == OP_SUB) ? OP_SUB : OP_IDENT;
     const bool dense_req = density > DENSE_DENSITY;
     const bool exact = !dense_req && (c->force_exact || c->hint_density[hint_set] != density);
     uint32_t *tau = c->tau + (size_t)hint_set * c->J;
@@ -319,9 +323,10 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
                         nullptr, nullptr);
             ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
             StreamArgs sb = sa;
-            sb.grad = nullptr;
+            if (op_again == OP_IDENT) sb.grad = nullptr;
             const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sb.quads_per_block);
-            launch_stream(OP_IDENT, MODE_COLLECT, aligned16(state), sb, blocks, c->stream, ps.ev0, ps.ev1);
+            launch_stream(op_again, MODE_COLLECT, op_again == OP_IDENT ? aligned16(state) : vec, sb, blocks,
+                          c->stream, ps.ev0, ps.ev1);
             ps.launched();
         }
     } else {
@@ -333,6 +338,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
 
     SelectArgs se{};
     se.state = state;
+    se.model = (op_stream == OP_SUB) ? grad : nullptr;
     se.tdesc = c->tdesc;
     se.plan = plan;
     se.tau = tau;
@@ -353,6 +359,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     if (c->plan_slot[slot].nseg_active != 0) {
         SegArgs sg{};
         sg.state = state;
+        sg.model = se.model;
         sg.tdesc = c->tdesc;
         sg.plan = plan;
         sg.segtab = c->segtab;
@@ -387,8 +394,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         // with a threshold taken from a fresh histogram, then the same chain once more
         // (all of these kernels return at once when nothing is pending)
         StreamArgs sr = sa;
-        sr.grad = nullptr;
-        launch_seg_recollect(sr, aligned16(state), sg, c->stream);
+        if (op_again == OP_IDENT) sr.grad = nullptr;
+        launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
         sg.round = 1;
         sg.exact_mode = 1u;
         launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
@@ -617,6 +624,51 @@ int dgs_server_pull(dgs_ctx *c, uint32_t worker_id, double density, uint32_t *id
     float *row = c->diff + (size_t)worker_id * c->n;
     ++c->calls_pull;
     return run_selection(c, OP_IDENT, SEL_PULL, nullptr, row, 0.0f, 0.0f, density, 1 + worker_id, idx_out,
+                         val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT, DGS_PROF_PULL_SEGMENTED);
+}
+
+int dgs_server_attach_sent(dgs_ctx *c, float *sent)
+{
+    if (!c || !sent || c->W == 0) return DGS_EINVAL;
+    if (!aligned4(sent)) return DGS_EINVAL;
+    c->sent = sent;
+    return DGS_OK;
+}
+
+int dgs_server_push_model(dgs_ctx *c, float *model, const uint32_t *idx, const float *val, uint64_t nnz)
+{
+    if (!c || !model) return DGS_EINVAL;
+    if (nnz > c->n) return DGS_EINVAL;
+    if (nnz && (!idx || !val)) return DGS_EINVAL;
+    if (!aligned4(model)) return DGS_EINVAL;
+    if (c->validate && nnz) {
+        launch_fill_u32(c->flag, 0u, 1, c->stream);
+        launch_validate_idx(idx, (uint32_t)nnz, c->n, c->flag, c->stream);
+        uint32_t bad = 0;
+        if (hipMemcpyAsync(&bad, c->flag, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
+        if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+        if (bad) return DGS_EINVAL;
+    }
+    ++c->calls_push;
+    {
+        ProfSlot ps(c, DGS_PROF_PUSH);
+        launch_push(model, nullptr, 0, c->n, idx, val, (uint32_t)nnz, c->stream, ps.ev0, ps.ev1);
+        if (nnz) ps.launched();
+    }
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+int dgs_server_pull_sent(dgs_ctx *c, const float *model, uint32_t worker_id, double density,
+                         uint32_t *idx_out, float *val_out, uint64_t *nnz_out)
+{
+    if (!c || !c->sent || !model || !idx_out || !val_out) return DGS_EINVAL;
+    if (worker_id >= c->W) return DGS_EINVAL;
+    if (!(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!aligned4(model) || !aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
+    float *row = c->sent + (size_t)worker_id * c->n;
+    ++c->calls_pull;
+    return run_selection(c, OP_SUB, SEL_PULL_V, model, row, 0.0f, 0.0f, density, 1 + worker_id, idx_out,
                          val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT, DGS_PROF_PULL_SEGMENTED);
 }
 

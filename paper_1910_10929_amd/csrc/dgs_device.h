@@ -103,9 +103,13 @@ struct DevStats {
     unsigned long long repaired_tensors;
 };
 
-enum StreamOp { OP_FMA = 0, OP_IDENT = 1 };
+// OP_FMA: a = fmaf(lr, grad, state), state <- a (worker);  OP_IDENT: a = state (pull on a
+// difference row);  OP_SUB: a = grad - state, nothing stored (pull on model - sent_k).
+enum StreamOp { OP_FMA = 0, OP_IDENT = 1, OP_SUB = 2 };
 enum StreamMode { MODE_PLAIN = 0, MODE_COLLECT = 1, MODE_HIST = 2 };
-enum SelectOp { SEL_WORKER = 0, SEL_PULL = 1 };
+// What happens to a sent entry: SEL_WORKER state <- m * val;  SEL_PULL state <- +0;
+// SEL_PULL_V state <- state + val (the values themselves are model - state).
+enum SelectOp { SEL_WORKER = 0, SEL_PULL = 1, SEL_PULL_V = 2 };
 
 struct StreamArgs {
     const float *grad;            // OP_FMA only
@@ -121,7 +125,8 @@ struct StreamArgs {
 };
 
 struct SelectArgs {
-    float *state;                 // worker state or difference row
+    float *state;                 // worker state, difference row, or sent_k row
+    const float *model;           // SEL_PULL_V only: values are model - state
     const TensorDesc *tdesc;
     const PlanEntry *plan;
     uint32_t *tau;                // hints of this stream, updated
@@ -144,6 +149,7 @@ struct SelectArgs {
 
 struct SegArgs {
     float *state;
+    const float *model;           // SEL_PULL_V only
     const TensorDesc *tdesc;
     const PlanEntry *plan;
     const SegDesc *segtab;
@@ -179,7 +185,7 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
                  const uint32_t *pending);
 // Repair round, first half: histogram pass, pick and collecting pass over the segments
 // of the tensors left SEG_PENDING (reads `state` only).
-void launch_seg_recollect(const StreamArgs &a, bool vec, const SegArgs &g, void *stream);
+void launch_seg_recollect(int op, const StreamArgs &a, bool vec, const SegArgs &g, void *stream);
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1);
 // The five kernels of the segmented selection, in order, on `stream`.
 void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1);

@@ -220,6 +220,10 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
             for (int r = 0; r < 4; ++r)
                 g[r] = __builtin_nontemporal_load((const f32x4 *)(A.grad + base + r * 256 + lane * 4));
         }
+        if (OP == OP_SUB) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) g[r] = *(const f32x4 *)(A.grad + base + r * 256 + lane * 4);
+        }
 #pragma unroll
         for (int r = 0; r < 4; ++r)
             s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
@@ -228,7 +232,8 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
         for (int r = 0; r < 4; ++r)
 #pragma unroll
             for (int j = 0; j < 4; ++j)
-                a[r][j] = (OP == OP_FMA) ? __builtin_fmaf(A.lr, g[r][j], s[r][j]) : s[r][j];
+                a[r][j] = (OP == OP_FMA) ? __builtin_fmaf(A.lr, g[r][j], s[r][j])
+                                         : ((OP == OP_SUB) ? (g[r][j] - s[r][j]) : s[r][j]);
         if (MODE != MODE_PLAIN) tile_tail<MODE>(A, tau, t, d, a, lhist, cur, stage, only);
         // The state goes out last: this wave never has to wait for the stores to be
         // acknowledged (the memory counter it would wait on also counts stores).
@@ -255,6 +260,8 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
                 if (OP == OP_FMA) {
                     v = __builtin_fmaf(A.lr, A.grad[e], A.state[e]);
                     A.state[e] = v;
+                } else if (OP == OP_SUB) {
+                    v = A.grad[e] - A.state[e];
                 } else {
                     v = A.state[e];
                 }
@@ -330,6 +337,9 @@ void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blo
         if (mode == MODE_PLAIN) launch_stream_t<OP_FMA, MODE_PLAIN>(vec, a, blocks, st, ev0, ev1);
         else if (mode == MODE_COLLECT) launch_stream_t<OP_FMA, MODE_COLLECT>(vec, a, blocks, st, ev0, ev1);
         else launch_stream_t<OP_FMA, MODE_HIST>(vec, a, blocks, st, ev0, ev1);
+    } else if (op == OP_SUB) {
+        if (mode == MODE_COLLECT) launch_stream_t<OP_SUB, MODE_COLLECT>(vec, a, blocks, st, ev0, ev1);
+        else if (mode == MODE_HIST) launch_stream_t<OP_SUB, MODE_HIST>(vec, a, blocks, st, ev0, ev1);
     } else {
         if (mode == MODE_COLLECT) launch_stream_t<OP_IDENT, MODE_COLLECT>(vec, a, blocks, st, ev0, ev1);
         else if (mode == MODE_HIST) launch_stream_t<OP_IDENT, MODE_HIST>(vec, a, blocks, st, ev0, ev1);
@@ -501,11 +511,34 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 // select
 // ---------------------------------------------------------------------------
 
+// The value the selection ranks at flat index ix, read from the buffers themselves
+// (dense sources, zero fill): the state / difference row, or model - sent_k.
+template <int OP>
+__device__ __forceinline__ float row_value(const float *state, const float *model, uint32_t ix)
+{
+    return (OP == SEL_PULL_V) ? (model[ix] - state[ix]) : state[ix];
+}
+
+// What a sent entry leaves behind: worker m * a (Eq. 12, state stored as m u); pull on a
+// difference row +0 (Eq. 6 as D_k -= G); pull on model - sent_k: sent_k += G (Eq. 6).
+template <int OP>
+__device__ __forceinline__ void fix_sent(float *state, uint32_t ix, float val, float m)
+{
+    if (OP == SEL_WORKER) store_scattered(&state[ix], m * val);
+    else if (OP == SEL_PULL) store_scattered(&state[ix], 0.0f);
+    else store_scattered(&state[ix], state[ix] + val);
+}
+
+template <int OP>
 struct SrcDense {          // the tensor itself: position p <-> element off + p
     static constexpr bool AGG = false;
     const float *base;
+    const float *model;
     uint32_t off;
-    __device__ __forceinline__ uint32_t bits(uint32_t p) const { return __float_as_uint(base[off + p]); }
+    __device__ __forceinline__ uint32_t bits(uint32_t p) const
+    {
+        return __float_as_uint(row_value<OP>(base, model, off + p));
+    }
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return off + p; }
 };
 
@@ -778,7 +811,7 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                     if (pos < k) {
                         A.out_idx[outoff + pos] = ix;
                         A.out_val[outoff + pos] = __uint_as_float(vb[i]);
-                        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * __uint_as_float(vb[i])) : 0.0f);
+                        fix_sent<OP>(A.state, ix, __uint_as_float(vb[i]), A.m);
                     }
                     ++pos;
                 }
@@ -807,7 +840,7 @@ __device__ __forceinline__ uint32_t hint_rank(const TensorDesc &td, const PlanEn
     *Eq = 0;
     // a pull, or a worker without momentum: sent entries vanish, so even with nothing new
     // before the next call k entries must remain above the hinted key (about 2k)
-    uint32_t R = (OP == SEL_PULL || m == 0.0f) ? pe.k2_pull : pe.k2;
+    uint32_t R = (OP != SEL_WORKER || m == 0.0f) ? pe.k2_pull : pe.k2;
     if (OP == SEL_WORKER && drift && E != 0) {
         if (c >= E) {
             *Eq = E;
@@ -864,17 +897,17 @@ __device__ __forceinline__ void zero_fill_emit(const SrcList src, const uint32_t
     const uint32_t X = z + P;
     for (uint32_t q = tid; q < X; q += SEL_THREADS) {
         const uint32_t ix = td.off + q;
-        const float v = A.state[ix];
+        const float v = row_value<OP>(A.state, A.model, ix);
         A.out_idx[pe.outoff + q] = ix;
         A.out_val[pe.outoff + q] = v;
-        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * v) : 0.0f);
+        fix_sent<OP>(A.state, ix, v, A.m);
     }
     for (uint32_t p = P + tid; p < c; p += SEL_THREADS) {
         const uint32_t ix = src.index(p);
         const float v = __uint_as_float(src.bits(p));
         A.out_idx[pe.outoff + z + p] = ix;
         A.out_val[pe.outoff + z + p] = v;
-        store_scattered(&A.state[ix], (OP == SEL_WORKER) ? (A.m * v) : 0.0f);
+        fix_sent<OP>(A.state, ix, v, A.m);
     }
 }
 
@@ -1079,12 +1112,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
         if (td.n <= 2 * SEL_LDS_LIST) {
             uint32_t *lv = (uint32_t *)llist;
             __syncthreads();
-            for (uint32_t p = tid; p < td.n; p += SEL_THREADS) lv[p] = __float_as_uint(A.state[td.off + p]);
+            for (uint32_t p = tid; p < td.n; p += SEL_THREADS)
+                lv[p] = __float_as_uint(row_value<OP>(A.state, A.model, td.off + p));
             __syncthreads();
             SrcDenseLds src{lv, td.off};
             select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
         } else {
-            SrcDense src{A.state, td.off};
+            SrcDense<OP> src{A.state, A.model, td.off};
             select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
         }
     } else if (c <= SEL_LDS_LIST) {
@@ -1547,7 +1581,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
                     if (pos < pe.k) {
                         A.out_idx[pe.outoff + pos] = v[i].x;
                         A.out_val[pe.outoff + pos] = __uint_as_float(v[i].y);
-                        store_scattered(&A.state[v[i].x], (OP == SEL_WORKER) ? (A.m * __uint_as_float(v[i].y)) : 0.0f);
+                        fix_sent<OP>(A.state, v[i].x, __uint_as_float(v[i].y), A.m);
                     }
                     ++pos;
                 }
@@ -1564,7 +1598,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
 // A border tile shared with a neighbouring tensor is rewritten whole; the neighbour's
 // candidates in it are no longer needed by then (its selection is complete, or it is
 // pending too and rewrites the same values).
-template <int MODE, bool VEC>
+template <int OP, int MODE, bool VEC>
 __global__ __launch_bounds__(STREAM_THREADS) void k_seg_restream(const StreamArgs A, const SegArgs G,
                                                                 const uint32_t *__restrict__ toff,
                                                                 const uint32_t *__restrict__ tau)
@@ -1581,20 +1615,27 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_seg_restream(const StreamArg
     const uint32_t wave = uniform(threadIdx.x >> 6);
     uint2 *stage = stage_all + (MODE == MODE_COLLECT ? wave * STAGE : 0u);
     for (uint32_t i = wave; i < sd.ntiles; i += WAVES_PER_BLOCK)
-        process_tile<OP_IDENT, MODE, VEC>(A, toff, tau, sd.tile0 + i, lhist, (int)sd.j, stage, (int)sd.j);
+        process_tile<OP, MODE, VEC>(A, toff, tau, sd.tile0 + i, lhist, (int)sd.j, stage, (int)sd.j);
     flush_hist<MODE>(lhist, A.ghist, (int)sd.j);
 }
 
-void launch_seg_recollect(const StreamArgs &a, bool vec, const SegArgs &g, void *stream)
+template <int OP>
+static void launch_seg_recollect_t(const StreamArgs &a, bool vec, const SegArgs &g, hipStream_t st)
 {
-    hipStream_t st = (hipStream_t)stream;
-    if (g.nseg_total == 0) return;
     const dim3 grid(g.nseg_total), block(STREAM_THREADS);
-    if (vec) hipLaunchKernelGGL((k_seg_restream<MODE_HIST, true>), grid, block, 0, st, a, g, a.toff, a.tau);
-    else hipLaunchKernelGGL((k_seg_restream<MODE_HIST, false>), grid, block, 0, st, a, g, a.toff, a.tau);
-    launch_pick(g.tdesc, g.plan, a.ghist, g.tau, g.tprev, g.stats, g.J, stream, g.segstate, g.pending);
-    if (vec) hipLaunchKernelGGL((k_seg_restream<MODE_COLLECT, true>), grid, block, 0, st, a, g, a.toff, a.tau);
-    else hipLaunchKernelGGL((k_seg_restream<MODE_COLLECT, false>), grid, block, 0, st, a, g, a.toff, a.tau);
+    if (vec) hipLaunchKernelGGL((k_seg_restream<OP, MODE_HIST, true>), grid, block, 0, st, a, g, a.toff, a.tau);
+    else hipLaunchKernelGGL((k_seg_restream<OP, MODE_HIST, false>), grid, block, 0, st, a, g, a.toff, a.tau);
+    launch_pick(g.tdesc, g.plan, a.ghist, g.tau, g.tprev, g.stats, g.J, st, g.segstate, g.pending);
+    if (vec) hipLaunchKernelGGL((k_seg_restream<OP, MODE_COLLECT, true>), grid, block, 0, st, a, g, a.toff, a.tau);
+    else hipLaunchKernelGGL((k_seg_restream<OP, MODE_COLLECT, false>), grid, block, 0, st, a, g, a.toff, a.tau);
+}
+
+// op: OP_IDENT (the values are in `state`) or OP_SUB (model - state)
+void launch_seg_recollect(int op, const StreamArgs &a, bool vec, const SegArgs &g, void *stream)
+{
+    if (g.nseg_total == 0) return;
+    if (op == OP_SUB) launch_seg_recollect_t<OP_SUB>(a, vec, g, (hipStream_t)stream);
+    else launch_seg_recollect_t<OP_IDENT>(a, vec, g, (hipStream_t)stream);
 }
 
 void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1)
@@ -1604,14 +1645,16 @@ void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *e
     launch_k(k_seg_join, dim3(a.nseg_total), dim3(SEG_THREADS), st, ev0, nullptr, a);
     if (op == SEL_WORKER)
         launch_k(k_seg_window<SEL_WORKER>, dim3(a.J), dim3(SEG_THREADS), st, nullptr, nullptr, a);
-    else
+    else   // both kinds of pull share the hint policy
         launch_k(k_seg_window<SEL_PULL>, dim3(a.J), dim3(SEG_THREADS), st, nullptr, nullptr, a);
     launch_k(k_seg_prefix, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, nullptr, a);
     launch_k(k_seg_rank, dim3(a.J), dim3(RANK_THREADS), st, nullptr, nullptr, a);
     if (op == SEL_WORKER)
         launch_k(k_seg_emit<SEL_WORKER>, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, ev1, a);
-    else
+    else if (op == SEL_PULL)
         launch_k(k_seg_emit<SEL_PULL>, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, ev1, a);
+    else
+        launch_k(k_seg_emit<SEL_PULL_V>, dim3(a.nseg_total), dim3(SEG_THREADS), st, nullptr, ev1, a);
 }
 
 void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1)
@@ -1620,8 +1663,10 @@ void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *
     if (op == SEL_WORKER)
         launch_k(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads,
                  a.slots);
-    else
+    else if (op == SEL_PULL)
         launch_k(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads, a.slots);
+    else
+        launch_k(k_select<SEL_PULL_V>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads, a.slots);
 }
 
 // ---------------------------------------------------------------------------

@@ -26,6 +26,7 @@ EXPORTS = [
     "dgs_workspace_bytes", "dgs_create", "dgs_destroy", "dgs_nnz", "dgs_worker_step",
     "dgs_server_attach", "dgs_server_push", "dgs_server_pull", "dgs_server_pull_all",
     "dgs_apply_sparse", "dgs_set_option", "dgs_get_stats", "dgs_profile_read", "dgs_strerror",
+    "dgs_server_attach_sent", "dgs_server_push_model", "dgs_server_pull_sent",
 ]
 
 
@@ -68,6 +69,9 @@ def lib():
         L.dgs_server_pull.argtypes = [_vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
         L.dgs_server_pull_all.argtypes = [_vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64, _u64p]
         L.dgs_apply_sparse.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_uint64, ctypes.c_float]
+        L.dgs_server_attach_sent.argtypes = [_vp, _vp]
+        L.dgs_server_push_model.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_uint64]
+        L.dgs_server_pull_sent.argtypes = [_vp, _vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
         L.dgs_set_option.argtypes = [_vp, ctypes.c_int, ctypes.c_int64]
         L.dgs_get_stats.argtypes = [_vp, ctypes.POINTER(_Stats)]
         L.dgs_profile_read.argtypes = [_vp, ctypes.c_int, _u64p, ctypes.POINTER(ctypes.c_double)]
@@ -199,6 +203,22 @@ class Context:
         self._check_capacity(density, idx_out, val_out)
         _check(lib().dgs_server_pull(self._h, worker_id, density, _ptr(idx_out), _ptr(val_out),
                                      ctypes.byref(K)), "dgs_server_pull")
+        return int(K.value)
+
+    # -- the server state as Algorithm 2 prints it: global model + what each worker was sent
+    def server_attach_sent(self, sent) -> None:
+        _check(lib().dgs_server_attach_sent(self._h, _ptr(sent)), "dgs_server_attach_sent")
+        self.sent = sent
+
+    def server_push_model(self, model, idx, val, nnz: int) -> None:
+        _check(lib().dgs_server_push_model(self._h, _ptr(model), _ptr(idx), _ptr(val), nnz),
+               "dgs_server_push_model")
+
+    def server_pull_sent(self, model, worker_id: int, density: float, idx_out, val_out) -> int:
+        K = ctypes.c_uint64(0)
+        self._check_capacity(density, idx_out, val_out)
+        _check(lib().dgs_server_pull_sent(self._h, _ptr(model), worker_id, density, _ptr(idx_out),
+                                          _ptr(val_out), ctypes.byref(K)), "dgs_server_pull_sent")
         return int(K.value)
 
     def server_pull_all(self, worker_id: int, idx_out, val_out, capacity: int) -> int:

@@ -55,6 +55,10 @@ def exact_fma_f32(lr, g, s):
     return round_fraction_to_f32(Fraction(float(lr)) * Fraction(float(g)) + Fraction(float(s)))
 
 
+def bits(a: np.ndarray) -> np.ndarray:
+    return np.ascontiguousarray(a).view(np.uint32)
+
+
 def ceil_rho_n(density: float, n: int) -> int:
     """ceil(density * n) with the product rounded to double, by exact
     arithmetic."""
@@ -411,6 +415,56 @@ def test_server_against_literal_algorithm_2_and_identities(oracle):
         oracle.apply_sparse(theta_k[w], gi, gv, 1.0)
         assert not diff[w].any()
         assert np.array_equal(theta_k[w], model)
+
+
+def test_printed_server_form_against_literal_algorithm_2(oracle):
+    """The oracle's model / sent_k form (Algorithm 2 as printed) against the dense numpy
+    statement above, on Gaussian data (same fp32 operations, so bit equality), and
+    against the difference-row form on integer data, where both are exact."""
+    rng = np.random.default_rng(14)
+    sizes = [700, 5, 1300]
+    off = synth.offsets_from_sizes(sizes)
+    n = int(off[-1])
+    W = 3
+    rho_up, rho_down = 0.03, 0.02
+    kj = [ceil_rho_n(rho_up, s) for s in sizes]
+    order = synth.event_schedule(W, 30, 15)
+    # Gaussian values, theta_0 = 0: M and v_k of the printed algorithm are model and sent_k
+    model = np.zeros(n, np.float32)
+    sent = np.zeros((W, n), np.float32)
+    M_lit = np.zeros(n, np.float32)
+    v_lit = [np.zeros(n, np.float32) for _ in range(W)]
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = synth.sparse_payload(off, kj, None, rng)
+        oracle.server_push_model(model, idx, val)
+        M_lit, v_lit[k], wi, wv = alg2_literal_v(M_lit, v_lit[k], idx, val, off, rho_down, ceil_rho_n)
+        gi, gv = oracle.server_pull_sent(model, sent, k, off, rho_down)
+        assert np.array_equal(gi, wi), e
+        assert np.array_equal(bits(gv), bits(wv)), e
+        assert np.array_equal(bits(model), bits(M_lit))
+        assert np.array_equal(bits(sent[k]), bits(v_lit[k]))
+    # integer data, theta_0 != 0: identical messages from both server forms
+    theta0 = rng.integers(-5, 6, size=n).astype(np.float32)
+    model_d, model_s = theta0.copy(), theta0.copy()
+    diff = np.zeros((W, n), np.float32)
+    sent = np.tile(theta0, (W, 1))
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = synth.sparse_payload(off, kj, None, rng)
+        val = np.round(val * 4).astype(np.float32)
+        oracle.server_push(model_d, diff, idx, val)
+        oracle.server_push_model(model_s, idx, val)
+        di, dv = oracle.server_pull(diff, k, off, rho_down)
+        si, sv = oracle.server_pull_sent(model_s, sent, k, off, rho_down)
+        assert np.array_equal(di, si) and np.array_equal(dv, sv), e
+        assert np.array_equal(model_d, model_s)
+        for w in range(W):
+            assert np.array_equal(diff[w], model_s - sent[w])
+    # density 1: the worker is brought fully up to date (sent_k == model)
+    for w in range(W):
+        oracle.server_pull_sent(model_s, sent, w, off, 1.0)
+        assert np.array_equal(sent[w], model_s)
 
 
 def test_double_pull_returns_next_k(oracle):
