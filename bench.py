@@ -9,7 +9,9 @@ Gaussian values, a pool of gradient sets cycled), resident in HBM before the
 timed region starts.
 
 Other workloads, for the design notes (not the default bench line):
+  c1  one flat tensor of 2^20 parameters, density 0.01 (latency-bound)
   c3  server stress: 32 workers' difference rows, step = push + pull of a seeded worker
+  c4  transformer-shaped 108M parameters, heavy-tailed gradients, row-sparse embedding
   c5  1e9 parameters in 64 tensors, `--density` 1e-4 or 1e-2, step as in c2
 
 Prints ONE JSON line: params/s over the timed steps, the roofline of the
@@ -36,7 +38,7 @@ LR, MOMENTUM = 1.0, 0.9
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE, scaled by the same counters on a copy kernel of known size); the
 # summaries are under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c2": 307.98e6, "c3": None, "c5": None}
+MEASURED_TRAFFIC_BYTES = {"c1": None, "c2": 307.98e6, "c3": None, "c4": None, "c5": None}
 
 
 def make_workload(name, density):
@@ -59,6 +61,27 @@ def make_workload(name, density):
         return dict(off=off, payloads=payloads, order=order, W=32, density=rho,
                     desc="server stress: 25,557,032-param model, 32 workers' difference rows, "
                          "step = server_push of a pooled payload + server_pull of a seeded worker")
+    if name == "c1":
+        off = synth.layout_flat(1 << 20)
+        rng = np.random.default_rng(0)
+        grads = [synth.gaussian(1 << 20, rng) for _ in range(8)]
+        return dict(off=off, grads=grads, W=1, density=density or 0.01,
+                    desc="one flat tensor of 1,048,576 fp32 params, N(0,1), 1 worker: worker_step + "
+                         "server_push + server_pull per step (latency-bound)")
+    if name == "c4":
+        off = synth.layout_transformer()
+        J = len(off) - 1
+        scales = synth.tensor_scales(J, 4)
+        rng = np.random.default_rng(4)
+        grads = []
+        for _ in range(4):
+            g = synth.student_t_grads(off, scales, rng)
+            synth.zero_rows(g, int(off[J - 1]), 30522, 768, 0.05, rng)
+            grads.append(g)
+        return dict(off=off, grads=grads, W=1, density=density or 1e-3,
+                    desc="transformer-shaped 108,375,552 fp32 params in 49 tensors, Student-t(3) gradients, "
+                         "embedding gradient 95 % zero rows, 1 worker: worker_step + server_push + "
+                         "server_pull per step")
     if name == "c5":
         off = synth.layout_equal(1_000_000_000, 64)
         scales = synth.tensor_scales(64, 5)
@@ -113,10 +136,13 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c2", choices=["c2", "c3", "c5"])
+    ap.add_argument("--workload", default="c2", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--density", type=float, default=None)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--force-exact", action="store_true", help="time the non-predicted two-pass path")
+    ap.add_argument("--server-form", default="diff", choices=["diff", "sent"],
+                    help="c3 only: per-worker difference rows (default) or the printed form, "
+                         "global model + what each worker has been sent")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run 20 elementwise copies of one 25,557,032-float tensor and exit "
                          "(known traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -166,13 +192,24 @@ def main():
                for i, v in wl["payloads"]]
         order = [int(x) for x in wl["order"]]
 
-        def step(t):
-            i, v, nn = pay[t % len(pay)]
-            w = order[t % len(order)]
-            ctx.server_push(model, w, i, v, nn)
-            ctx.server_pull(w, rho, pidx, pval)
-        dominant, dom_kind, dom_bytes = "k_stream<ident,collect> (dgs_server_pull streaming pass)", dgs.PROF_PULL_STREAM, 4.0 * n
-        step_bytes = (8.0 * K + 8.0 * (W + 1) * K) + (4.0 * n + 12.0 * K)
+        if args.server_form == "sent":
+            ctx.server_attach_sent(diff)          # W rows, all equal to the (zero) initial model
+
+            def step(t):
+                i, v, nn = pay[t % len(pay)]
+                w = order[t % len(order)]
+                ctx.server_push_model(model, i, v, nn)
+                ctx.server_pull_sent(model, w, rho, pidx, pval)
+            dominant, dom_kind, dom_bytes = "k_stream<sub,collect> (dgs_server_pull_sent streaming pass)", dgs.PROF_PULL_STREAM, 8.0 * n
+            step_bytes = (8.0 * K + 8.0 * K) + (8.0 * n + 16.0 * K)
+        else:
+            def step(t):
+                i, v, nn = pay[t % len(pay)]
+                w = order[t % len(order)]
+                ctx.server_push(model, w, i, v, nn)
+                ctx.server_pull(w, rho, pidx, pval)
+            dominant, dom_kind, dom_bytes = "k_stream<ident,collect> (dgs_server_pull streaming pass)", dgs.PROF_PULL_STREAM, 4.0 * n
+            step_bytes = (8.0 * K + 8.0 * (W + 1) * K) + (4.0 * n + 12.0 * K)
     else:
         g_dev = [torch.from_numpy(g).to(dev) for g in wl["grads"]]
         state = torch.zeros(n, dtype=torch.float32, device=dev)
@@ -236,7 +273,8 @@ def main():
         "dtype": "f32", "data": "synthetic",
         "config": {"workload": f"{name}: {wl['desc']}, density {rho:g}",
                    "n": n, "tensors": J, "density": rho, "K": K, "workers": W,
-                   "momentum": MOMENTUM, "path": "exact" if args.force_exact else "predicted"},
+                   "momentum": MOMENTUM, "path": "exact" if args.force_exact else "predicted",
+                   "server_form": args.server_form},
         "roofline": roofline,
         "kernel_us": kernel_us,
         "step_algorithmic_GBs": step_bytes / (dt / steps) / 1e9,

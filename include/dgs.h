@@ -47,9 +47,14 @@ enum {
     DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
     DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */
     DGS_OPT_STREAM_QUADS = 5,/* 4096-element groups per workgroup of the streaming kernel */
-    DGS_OPT_SEGMENTED = 6    /* selection of large tensors by the multi-workgroup kernels:
+    DGS_OPT_SEGMENTED = 6,   /* selection of large tensors by the multi-workgroup kernels:
                                 0 automatic (by tensor size and density), 1 every tensor of at
                                 least 65536 elements, 2 never */
+    DGS_OPT_REPAIR_ROUND = 7 /* 1 (default): behind the multi-workgroup selection, enqueue the kernels
+                                that collect again, with a fresh threshold, the tensors whose
+                                predicted threshold failed (they return at once when there is none,
+                                about 20 us per call); 0: such tensors go straight to the slow
+                                single-workgroup selection from the state buffer */
 };
 
 /* Kernel classes reported by dgs_profile_read(). */

@@ -140,6 +140,7 @@ struct dgs_ctx {
     bool force_exact = false, profile = false, validate = false;
     int margin_pct = 50;
     int seg_mode = SEG_MODE_AUTO;
+    bool repair_round = true;
     uint32_t stream_quads = 0;         // 0 = automatic
     // host counters
     uint64_t calls_worker = 0, calls_pull = 0, calls_push = 0, exact_calls = 0;
@@ -388,17 +389,20 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sg.round = 0;
         sg.pending = c->flag + 8;
         se.pending = sg.pending;
+        sg.repair = c->repair_round ? 1u : 0u;
         ProfSlot ps(c, prof_seg);
-        launch_segmented(op_select, sg, c->stream, ps.ev0, nullptr);
+        launch_segmented(op_select, sg, c->stream, ps.ev0, c->repair_round ? nullptr : ps.ev1);
         // repair round for the tensors whose prediction failed: collect again from `state`
         // with a threshold taken from a fresh histogram, then the same chain once more
         // (all of these kernels return at once when nothing is pending)
-        StreamArgs sr = sa;
-        if (op_again == OP_IDENT) sr.grad = nullptr;
-        launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
-        sg.round = 1;
-        sg.exact_mode = 1u;
-        launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
+        if (c->repair_round) {
+            StreamArgs sr = sa;
+            if (op_again == OP_IDENT) sr.grad = nullptr;
+            launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
+            sg.round = 1;
+            sg.exact_mode = 1u;
+            launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
+        }
         ps.launched();
     }
     {
@@ -718,6 +722,7 @@ int dgs_set_option(dgs_ctx *c, int option, int64_t value)
         if (value < 0 || value > 2) return DGS_EINVAL;
         c->seg_mode = (int)value;
         return DGS_OK;
+    case DGS_OPT_REPAIR_ROUND: c->repair_round = value != 0; return DGS_OK;
     case DGS_OPT_STREAM_QUADS:
         if (value < 0 || value > (1 << 20)) return DGS_EINVAL;
         c->stream_quads = (uint32_t)value;

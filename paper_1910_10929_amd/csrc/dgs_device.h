@@ -173,6 +173,7 @@ struct SegArgs {
     float m;
     uint32_t write_hint, exact_mode, nseg_total, J;
     uint32_t round;               // 0: first attempt, 1: repair of the tensors left SEG_PENDING
+    uint32_t repair;              // a repair round follows round 0 (else failures go straight to k_select)
     uint32_t *pending;            // number of tensors left SEG_PENDING by round 0 (reset by k_select)
 };
 

@@ -1301,10 +1301,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
         st->T = 0;
         // a failed first attempt is collected again by the repair round; a failed repair
         // (e.g. one value filling a whole histogram bucket) is left to k_select
-        const uint32_t bad = (A.round == 0) ? SEG_PENDING : SEG_FALLBACK;
+        const bool again = (A.round == 0) && A.repair;
+        const uint32_t bad = again ? SEG_PENDING : SEG_FALLBACK;
         st->status = ok ? (SEG_ACTIVE + A.round) : (zf ? SEG_ZEROFILL : bad);
         if (!ok && !zf) {
-            if (A.round == 0) {
+            if (again) {
                 atomicAdd(A.pending, 1u);
             } else {
                 atomicAdd(&A.stats->fallback_tensors, 1ull);
@@ -1481,7 +1482,7 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
                 st->T = T;
                 st->r2 = rT;
                 A.tprev[j] = T;
-                if (A.round == 0) {
+                if (A.round == 0 && A.repair) {
                     st->status = SEG_COUNT;
                     atomicAdd(A.pending, 1u);
                 } else {
