@@ -131,6 +131,58 @@ def cpu_baseline(wl, name, budget_s=20.0):
             "sample": f"first {steps} {what} of the same workload, {dt:.1f} s on one host core"}
 
 
+def overlapped(torch, dgs, off, W, rho, K, g_dev, steps, warmup, n, step_bytes):
+    """Worker and server as two contexts on two streams of default priority: the worker's
+    step t+1 runs while the server handles push / pull t (the asynchrony of the method; with
+    one worker the gradient of step t+1 is taken as given).  Messages are double-buffered and
+    ordered with events."""
+    dev = "cuda:0"
+    sa, sb = torch.cuda.Stream(device=dev), torch.cuda.Stream(device=dev)
+    wctx = dgs.Context(off, W=0, device=dev, stream=sa)
+    sctx = dgs.Context(off, W=W, device=dev, stream=sb)
+    model = torch.zeros(n, dtype=torch.float32, device=dev)
+    diff = torch.zeros((W, n), dtype=torch.float32, device=dev)
+    sctx.server_attach(diff)
+    state = torch.zeros(n, dtype=torch.float32, device=dev)
+    msg = [(torch.zeros(K, dtype=torch.int32, device=dev), torch.zeros(K, dtype=torch.float32, device=dev))
+           for _ in range(2)]
+    pidx = torch.zeros(K, dtype=torch.int32, device=dev)
+    pval = torch.zeros(K, dtype=torch.float32, device=dev)
+    produced = [torch.cuda.Event() for _ in range(2)]
+    consumed = [torch.cuda.Event() for _ in range(2)]
+    torch.cuda.synchronize()
+
+    def step(t):
+        b = t % 2
+        if t >= 2:
+            sa.wait_event(consumed[b])                     # the server has read message t-2
+        wctx.worker_step(g_dev[t % len(g_dev)], state, LR, MOMENTUM, rho, msg[b][0], msg[b][1])
+        produced[b].record(sa)
+        sb.wait_event(produced[b])
+        sctx.server_push(model, 0, msg[b][0], msg[b][1], K)
+        consumed[b].record(sb)
+        sctx.server_pull(0, rho, pidx, pval)
+
+    t = 0
+    for _ in range(warmup):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step(t)
+        t += 1
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    st = (wctx.stats(), sctx.stats())
+    wctx.close()
+    sctx.close()
+    return {"ms_per_step": dt / steps * 1e3, "params_per_s": n * steps / dt,
+            "step_algorithmic_GBs": step_bytes / (dt / steps) / 1e9,
+            "internal_errors": st[0].internal_errors + st[1].internal_errors,
+            "fallback_tensors": st[0].fallback_tensors + st[1].fallback_tensors}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -143,6 +195,9 @@ def main():
     ap.add_argument("--server-form", default="diff", choices=["diff", "sent"],
                     help="c3 only: per-worker difference rows (default) or the printed form, "
                          "global model + what each worker has been sent")
+    ap.add_argument("--overlap", action="store_true",
+                    help="c2/c4/c5: also time worker and server on two streams (worker step t+1 "
+                         "overlaps push/pull t); reported as an extra field, never as `value`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run 20 elementwise copies of one 25,557,032-float tensor and exit "
                          "(known traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -282,6 +337,8 @@ def main():
                   "segmented_tensors": st.segmented_tensors, "repaired_tensors": st.repaired_tensors,
                   "internal_errors": st.internal_errors},
     }
+    if args.overlap and name != "c3":
+        out["overlapped_two_streams"] = overlapped(torch, dgs, off, W, rho, K, g_dev, steps, warmup, n, step_bytes)
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(wl, name)
     ctx.close()
     print(json.dumps(out))
