@@ -38,7 +38,7 @@ LR, MOMENTUM = 1.0, 0.9
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc runs (FETCH_SIZE,
 # WRITE_SIZE, scaled by the same counters on a copy kernel of known size); the
 # summaries are under profiles/.  None = not measured for that workload.
-MEASURED_TRAFFIC_BYTES = {"c1": None, "c2": 307.98e6, "c3": None, "c4": None, "c5": None}
+MEASURED_TRAFFIC_BYTES = {"c1": None, "c2": 308.61e6, "c3": None, "c4": None, "c5": None}
 
 
 def make_workload(name, density):
