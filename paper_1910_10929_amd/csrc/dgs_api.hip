@@ -194,9 +194,13 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
         // segmented selection: always for very large tensors, and whenever the candidate
         // list would not fit the single workgroup's LDS list
         bool seg = false;
-        if (c->nseg[j] != 0 && density <= DENSE_DENSITY && c->seg_mode != SEG_MODE_NEVER)
-            seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
-                  (k2 > k2p ? k2 : k2p) > SEL_LDS_LIST;
+        if (c->nseg[j] != 0 && c->seg_mode != SEG_MODE_NEVER) {
+            if (density > DENSE_DENSITY)
+                seg = true;   // dense request: the chain reads the tensor itself, one workgroup would crawl
+            else
+                seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
+                      (k2 > k2p ? k2 : k2p) > SEL_LDS_LIST;
+        }
         out[j].seg = seg ? 1u : 0u;
         out[j].pad0 = out[j].pad1 = out[j].pad2 = 0;
         active += seg ? 1u : 0u;
@@ -304,7 +308,18 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     sa.nquads = c->nquads;
     sa.lr = lr;
 
-    if (dense_req) {
+    const bool have_seg = c->plan_slot[slot].nseg_active != 0;
+    if (dense_req && have_seg) {
+        // dense request with large tensors: the accumulate pass also histograms the keys, and
+        // k_pick turns that into a lower bound of each k-th key; the segmented chain then reads
+        // the tensors themselves
+        ProfSlot ps(c, prof_stream);
+        const uint32_t blocks = stream_blocks(c, MODE_HIST, &sa.quads_per_block);
+        launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
+        ps.launched();
+        launch_pick(c->tdesc, plan, c->ghist, tau, c->tprev + (size_t)hint_set * c->J, c->stats, c->J, c->stream,
+                    nullptr, nullptr);
+    } else if (dense_req) {
         if (op_stream == OP_FMA) {
             ProfSlot ps(c, prof_stream);
             const uint32_t blocks = stream_blocks(c, MODE_PLAIN, &sa.quads_per_block);
@@ -357,7 +372,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.force_dense = dense_req ? 1u : 0u;
     se.write_hint = dense_req ? 0u : 1u;
     se.segstate = c->segstate;
-    if (c->plan_slot[slot].nseg_active != 0) {
+    if (have_seg) {
         SegArgs sg{};
         sg.state = state;
         sg.model = se.model;
@@ -382,7 +397,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sg.out_val = val_out;
         sg.stats = c->stats;
         sg.m = m;
-        sg.write_hint = 1u;
+        sg.write_hint = dense_req ? 0u : 1u;
+        sg.dense = dense_req ? 1u : 0u;
         sg.exact_mode = exact ? 1u : 0u;
         sg.nseg_total = c->nseg_total;
         sg.J = c->J;
@@ -396,9 +412,11 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         // with a threshold taken from a fresh histogram, then the same chain once more
         // (all of these kernels return at once when nothing is pending)
         if (c->repair_round) {
-            StreamArgs sr = sa;
-            if (op_again == OP_IDENT) sr.grad = nullptr;
-            launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
+            if (!dense_req) {   // a dense request has no candidate lists to collect again
+                StreamArgs sr = sa;
+                if (op_again == OP_IDENT) sr.grad = nullptr;
+                launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
+            }
             sg.round = 1;
             sg.exact_mode = 1u;
             launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
@@ -411,6 +429,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         ps.launched();
     }
     if (!dense_req) c->hint_density[hint_set] = density;
+    else if (have_seg) c->hint_density[hint_set] = 0.0;   // k_pick has overwritten this stream's hints
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;
 }

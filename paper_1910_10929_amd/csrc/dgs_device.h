@@ -53,9 +53,10 @@ constexpr uint32_t SEG_MAX_PER_TENSOR = 8192;      // per-segment counters kept 
 // SEG_ACTIVE + r: being resolved by round r of the chain (0 = first attempt, 1 = repair);
 // SEG_PENDING: the first attempt failed, the repair round collects again with a threshold
 // taken from a fresh histogram; SEG_COUNT: the k-th key is known but too many entries share
-// its prefix, the repair round counts the segments against it; SEG_FALLBACK / SEG_ZEROFILL:
-// left to k_select.
-enum SegStatus { SEG_IDLE = 0, SEG_FALLBACK = 2, SEG_ZEROFILL = 3, SEG_PENDING = 4, SEG_COUNT = 5, SEG_ACTIVE = 8 };
+// its prefix, the repair round counts the segments against it; SEG_ALL: k_j = n_j, every element
+// is sent; SEG_FALLBACK / SEG_ZEROFILL: left to k_select.
+enum SegStatus { SEG_IDLE = 0, SEG_FALLBACK = 2, SEG_ZEROFILL = 3, SEG_PENDING = 4, SEG_COUNT = 5, SEG_ALL = 6,
+                 SEG_ACTIVE = 8 };
 enum SegMode { SEG_MODE_AUTO = 0, SEG_MODE_ALWAYS = 1, SEG_MODE_NEVER = 2 };
 
 struct TensorDesc {
@@ -174,6 +175,8 @@ struct SegArgs {
     uint32_t write_hint, exact_mode, nseg_total, J;
     uint32_t round;               // 0: first attempt, 1: repair of the tensors left SEG_PENDING
     uint32_t repair;              // a repair round follows round 0 (else failures go straight to k_select)
+    uint32_t dense;               // dense request: no candidate lists, the chain reads the tensor itself
+                                  // (every element with key >= tau, tau from this call's histogram)
     uint32_t *pending;            // number of tensors left SEG_PENDING by round 0 (reset by k_select)
 };
 

@@ -1176,6 +1176,44 @@ __device__ __forceinline__ uint32_t seg_window_base(uint32_t tau_cur, uint32_t t
     return max(b_tau, b_mid);
 }
 
+// The entries one segment contributes: its compacted candidate list, or (dense
+// requests) the tensor's own elements inside the segment, in index order.
+struct SegSource {
+    const uint2 *list;
+    const float *state;
+    const float *model;
+    uint32_t first;   // dense: first element
+    uint32_t count;
+    bool dense;
+    __device__ __forceinline__ uint2 get(uint32_t e) const
+    {
+        if (!dense) return list[e];
+        const uint32_t ix = first + e;
+        const float v = model ? (model[ix] - state[ix]) : state[ix];
+        return make_uint2(ix, __float_as_uint(v));
+    }
+};
+
+__device__ __forceinline__ SegSource seg_source(const SegArgs &A, const TensorDesc &td, const SegDesc &sd,
+                                                uint32_t seg, bool dense)
+{
+    SegSource S;
+    S.list = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    S.state = A.state;
+    S.model = A.model;
+    S.dense = dense;
+    if (dense) {
+        const uint64_t lo = max((uint64_t)td.off, (uint64_t)sd.tile0 * TILE);
+        const uint64_t hi = min((uint64_t)td.off + td.n, ((uint64_t)sd.tile0 + sd.ntiles) * TILE);
+        S.first = (uint32_t)lo;
+        S.count = (uint32_t)(hi - lo);
+    } else {
+        S.first = 0;
+        S.count = A.segcnt[seg];
+    }
+    return S;
+}
+
 __global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
 {
     __shared__ uint32_t h[SEG_WBINS];
@@ -1189,6 +1227,31 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_join(const SegArgs A)
     const TensorDesc td = A.tdesc[sd.j];
     const uint32_t tid = threadIdx.x;
     for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) h[b] = 0;
+    if (A.dense) {
+        // dense request: count the segment's own elements at or above this call's threshold
+        const SegSource S = seg_source(A, td, sd, blockIdx.x, true);
+        const uint32_t tau_d = A.tau[sd.j];
+        const uint32_t base_d = seg_window_base(tau_d, A.tprev[sd.j]);
+        uint32_t mine = 0;
+        __syncthreads();
+        for (uint32_t e = tid; e < S.count; e += SEG_THREADS) {
+            const uint32_t key = S.get(e).y & 0x7FFFFFFFu;
+            if (key >= tau_d) {
+                const uint32_t hi12 = key >> SEG_LOWBITS;
+                const uint32_t w = (hi12 > base_d) ? (hi12 - base_d) : 0u;
+                atomicAdd(&h[min(w, SEG_WBINS - 1u)], 1u);
+                ++mine;
+            }
+        }
+        const uint32_t tot = block_sum(mine, wsum, SEG_THREADS / 64);
+        uint32_t *ghd = A.whist + (size_t)sd.j * HBINS;
+        for (uint32_t b = tid; b < SEG_WBINS; b += SEG_THREADS) {
+            const uint32_t v = h[b];
+            if (v) atomicAdd(&ghd[b], v);
+        }
+        if (tid == 0) A.segcnt[blockIdx.x] = tot;
+        return;
+    }
     const uint32_t tlo = td.off / TILE;
     const bool head_shared = (td.off % TILE) != 0;
 
@@ -1291,9 +1354,11 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
     if (tid == 0) {
         SegState *st = &A.segstate[j];
         const int bk = res[0], bR = res[2];
-        const bool ok = (st->ovf == 0) && (c >= pe.k) && bk >= bin_min && bk < (int)SEG_WBINS - 1;
+        const bool all = (pe.k == td.n);   // everything is sent: no threshold to find
+        const bool ok = all || ((st->ovf == 0) && (c >= pe.k) && bk >= bin_min && bk < (int)SEG_WBINS - 1);
         // fewer candidates than k with every nonzero collected: k_select completes with zeros
-        const bool zf = (st->ovf == 0) && (c < pe.k) && (tau_cur <= 1u);
+        // (from the candidate lists, which a dense request does not have)
+        const bool zf = !A.dense && !all && (st->ovf == 0) && (c < pe.k) && (tau_cur <= 1u);
         st->ovf = 0;
         st->pfxcount = 0;
         st->pfx = win_base + (uint32_t)max(bk, 0);
@@ -1301,9 +1366,9 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_window(const SegArgs A)
         st->T = 0;
         // a failed first attempt is collected again by the repair round; a failed repair
         // (e.g. one value filling a whole histogram bucket) is left to k_select
-        const bool again = (A.round == 0) && A.repair;
+        const bool again = (A.round == 0) && A.repair && !A.dense;   // the second collection needs candidate lists
         const uint32_t bad = again ? SEG_PENDING : SEG_FALLBACK;
-        st->status = ok ? (SEG_ACTIVE + A.round) : (zf ? SEG_ZEROFILL : bad);
+        st->status = all ? (uint32_t)SEG_ALL : (ok ? (SEG_ACTIVE + A.round) : (zf ? SEG_ZEROFILL : bad));
         if (!ok && !zf) {
             if (again) {
                 atomicAdd(A.pending, 1u);
@@ -1357,8 +1422,8 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
     if (!A.plan[sd.j].seg) return;
     SegState *st = &A.segstate[sd.j];
     const uint32_t status = st->status;
-    const uint32_t cs = A.segcnt[blockIdx.x];
-    const uint2 *src = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    const SegSource src = seg_source(A, A.tdesc[sd.j], sd, blockIdx.x, A.dense != 0);
+    const uint32_t cs = src.count;
     const uint32_t tid = threadIdx.x;
     if (A.round != 0 && status == SEG_COUNT) {
         // the k-th key T is known (the prefix list had overflowed): count this segment's
@@ -1366,7 +1431,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
         const uint32_t T = st->T;
         uint32_t g = 0, q = 0;
         for (uint32_t e = tid; e < cs; e += SEG_THREADS) {
-            const uint32_t key = src[e].y & 0x7FFFFFFFu;
+            const uint32_t key = src.get(e).y & 0x7FFFFFFFu;
             g += (key > T) ? 1u : 0u;
             q += (key == T) ? 1u : 0u;
         }
@@ -1390,7 +1455,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_prefix(const SegArgs A)
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const uint32_t e = eb + u * SEG_THREADS + tid;
-            ent[u] = (e < cs) ? src[e] : make_uint2(0, 0);
+            ent[u] = (e < cs) ? src.get(e) : make_uint2(0, 0);
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
@@ -1464,7 +1529,7 @@ __global__ __launch_bounds__(RANK_THREADS) void k_seg_rank(const SegArgs A)
         }
         find_ranks<SEG_LBINS, RANK_THREADS / 64>(h, r2, 0u, 0u, rowsum, res);
         const int b3 = res[0];
-        if (b3 < 0 || m < r2) {
+        if (b3 < 0) {   // the rank exceeds what the prefix kernel counted: cannot happen
             if (tid == 0) {
                 st->status = SEG_FALLBACK;
                 atomicAdd(&A.stats->fallback_tensors, 1ull);
@@ -1537,13 +1602,27 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
     const PlanEntry pe = A.plan[sd.j];
     if (!pe.seg) return;
     const SegState *st = &A.segstate[sd.j];
-    if (st->status != SEG_ACTIVE + A.round) return;
-    const uint32_t T = st->T;
-    const uint32_t seg = A.tdesc[sd.j].seg_first + sd.sidx;
-    const uint2 so = A.segOut[seg];
-    const uint32_t cs = A.segcnt[seg];
-    const uint2 *src = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    const uint32_t status = st->status;
+    const TensorDesc td = A.tdesc[sd.j];
     const uint32_t tid = threadIdx.x;
+    if (A.round == 0 && status == SEG_ALL) {
+        // k_j = n_j: every element of the segment is sent, at its own position
+        const SegSource all = seg_source(A, td, sd, blockIdx.x, true);
+        for (uint32_t e = tid; e < all.count; e += SEG_THREADS) {
+            const uint2 ent = all.get(e);
+            const uint32_t pos = ent.x - td.off;
+            A.out_idx[pe.outoff + pos] = ent.x;
+            A.out_val[pe.outoff + pos] = __uint_as_float(ent.y);
+            fix_sent<OP>(A.state, ent.x, __uint_as_float(ent.y), A.m);
+        }
+        return;
+    }
+    if (status != SEG_ACTIVE + A.round) return;
+    const uint32_t T = st->T;
+    const uint32_t seg = td.seg_first + sd.sidx;
+    const uint2 so = A.segOut[seg];
+    const SegSource src = seg_source(A, td, sd, seg, A.dense != 0);
+    const uint32_t cs = src.count;
     constexpr uint32_t ITEMS = 4;
     uint32_t run_sel = so.x, run_eq = 0;
     const uint32_t rT = so.y;
@@ -1552,7 +1631,7 @@ __global__ __launch_bounds__(SEG_THREADS) void k_seg_emit(const SegArgs A)
         uint2 v[ITEMS];
         uint32_t g = 0, q = 0;
 #pragma unroll
-        for (uint32_t i = 0; i < ITEMS; ++i) v[i] = (p0 + i < cs) ? src[p0 + i] : make_uint2(0, 0);
+        for (uint32_t i = 0; i < ITEMS; ++i) v[i] = (p0 + i < cs) ? src.get(p0 + i) : make_uint2(0, 0);
 #pragma unroll
         for (uint32_t i = 0; i < ITEMS; ++i) {
             const uint32_t key = v[i].y & 0x7FFFFFFFu;

@@ -149,3 +149,50 @@ def test_automatic_mode_mixes_both_selections(oracle):
         st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), rho)
         assert st.fallback_tensors == 0
         assert st.segmented_tensors == (3 if rho == 1e-3 else 6)
+
+
+@pytest.mark.parametrize("rho", [0.05, 0.5, 1.0])
+def test_dense_requests_on_large_tensors(oracle, rho):
+    """Densities above 1/32 on tensors of at least 65536 elements: no candidate lists, the
+    multi-workgroup chain reads the tensors themselves (density 1: everything is sent).  A
+    sparse step in between must not be disturbed by the dense ones."""
+    off = synth.offsets_from_sizes(SEG_SIZES)
+    scales = synth.tensor_scales(len(SEG_SIZES), 52)
+    rng = np.random.default_rng(53)
+    n = int(off[-1])
+    ctx = dgs.Context(off, W=1)
+    w = Worker(ctx, density_max=1.0)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=1.0)
+    s_ref = np.zeros(n, np.float32)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((1, n), np.float32)
+    for t, r in enumerate((rho, 0.002, rho, rho)):
+        g = synth.gaussian_grads(off, scales, rng)
+        if t == 2:
+            g[:150_000] = 0.0                      # fewer nonzeros than k in the first tensors
+        wi, wv = oracle.worker_step(g, s_ref, off, np.float32(0.5), np.float32(0.9), r)
+        gi, gv = w.step(g, 0.5, 0.9, r)
+        assert_pairs_match(gi, gv, wi, wv, f"step {t} density {r}")
+        assert_state_match(w.state_host(), s_ref, f"state {t}")
+        oracle.server_push(model_ref, diff_ref, wi, wv)
+        ctx.server_push(srv.model, 0, w.idx, w.val, gi.size)
+        pi_ref, pv_ref = oracle.server_pull(diff_ref, 0, off, r)
+        pi, pv = srv.pull(0, r)
+        assert_pairs_match(pi, pv, pi_ref, pv_ref, f"pull {t} density {r}")
+    assert_state_match(srv.diff.cpu().numpy()[0], diff_ref[0], "diff")
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    assert st.segmented_tensors >= 7 * 4      # the seven large tensors, most calls
+    ctx.close()
+
+
+@pytest.mark.parametrize("name", ["all_equal", "few_levels", "tie_class_across_segments"])
+def test_dense_requests_with_tie_classes(oracle, name):
+    n_big = 600_000
+    g_big = _patterns(n_big)[name]
+    off = synth.offsets_from_sizes([n_big, 100, 9000])
+    rng = np.random.default_rng(54)
+    tail = synth.gaussian(9100, rng)
+    g1 = np.concatenate([g_big, tail])
+    g2 = np.concatenate([g_big[::-1].copy(), -tail])
+    run_worker_parity(oracle, off, [g1, g2, g1], 1.0, np.float32(0.5), 0.1)
