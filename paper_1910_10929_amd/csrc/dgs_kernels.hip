@@ -565,8 +565,9 @@ struct SelShared {
     uint32_t kmin;
 };
 
-// Count into an LDS histogram.  With AGG, lanes of a wavefront that hit the same
-// bin are merged into one atomic (all 64 lanes must call this together).
+// Count into an LDS histogram.  With AGG (all 64 lanes must call this together), the
+// lanes that hit the same bin as the first valid lane are merged into one atomic --
+// candidate keys mostly share their top bits -- and the others add on their own.
 template <bool AGG>
 __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
 {
@@ -574,21 +575,24 @@ __device__ __forceinline__ void hist_add(uint32_t *h, uint32_t bin, bool valid)
         if (valid) atomicAdd(&h[bin], 1u);
         return;
     }
-    uint64_t todo = ballot64(valid);
-    while (todo != 0) {
-        const int leader = __ffsll((unsigned long long)todo) - 1;
-        const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
-        const uint64_t same = ballot64(valid && bin == b0);
-        if ((int)lane_id() == leader) atomicAdd(&h[b0], (uint32_t)__popcll(same));
-        todo &= ~same;
-    }
+    const uint64_t todo = ballot64(valid);
+    if (todo == 0) return;
+    const int leader = __ffsll((unsigned long long)todo) - 1;
+    const uint32_t b0 = (uint32_t)__builtin_amdgcn_readlane((int)bin, leader);
+    const uint64_t same = ballot64(valid && bin == b0);
+    if ((int)lane_id() == leader) atomicAdd(&h[b0], (uint32_t)__popcll(same));
+    else if (valid && bin != b0) atomicAdd(&h[bin], 1u);
 }
 
-// Exact selection over `cN` ordered entries of `src`; emits the k winners in
-// order and applies the state fix-up.  If R != 0 and R <= cN, also finds the
-// 21-bit key prefix of the entry of rank R: *tau_next = its lower edge (>= 1)
-// and *expect = how many entries lie at or above that edge; otherwise both 0.
-// win_base: (collection threshold >> 11) for candidate lists, 0xFFFFFFFF otherwise.
+// Window histogram of candidate keys: bucket (key >> 11) - win_base, everything at or
+// below the base in bucket 0, everything beyond the window in bucket 2047.
+__device__ __forceinline__ void window_count(uint32_t *h, uint32_t win_base, uint32_t key)
+{
+    const uint32_t hi = key >> 11;
+    const uint32_t w = (hi > win_base) ? (hi - win_base) : 0u;
+    atomicAdd(&h[min(w, 2047u)], 1u);
+}
+
 // Next threshold when fewer candidates (c) than the hinted rank R were collected, all at
 // or above `kmin`: the lowest q of them span `width` keys; the same density is assumed
 // below kmin (it is higher in fact, so this errs towards more candidates), with half as
@@ -605,9 +609,18 @@ __device__ __forceinline__ uint32_t hint_extrapolated(uint32_t kmin, uint32_t c,
     return max(tn, 1u);
 }
 
+// Exact selection over `cN` ordered entries of `src`; emits the k winners in
+// order and applies the state fix-up.  If R != 0 and R <= cN, also finds the
+// 21-bit key prefix of the entry of rank R: *tau_next = its lower edge (>= 1)
+// and *expect = how many entries lie at or above that edge; otherwise both 0.
+// Candidate lists come with a window: win_base = first bucket (key >> 11), 0xFFFFFFFF for
+// other sources; win_min = 1 if entries may lie below the base (bucket 0 is then mixed and
+// cannot hold a result), else 0; win_ready: S.h already holds the window histogram of the
+// entries (window_count); kmin = smallest key of the list.
 template <int OP, int ITEMS, class Src>
 __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, const uint32_t k,
                                             const uint32_t R, const uint32_t Eq, const uint32_t win_base,
+                                            const uint32_t win_min, const bool win_ready, const uint32_t kmin,
                                             SelShared &S, const SelectArgs &A, const uint32_t outoff,
                                             uint32_t *tau_next, uint32_t *expect, uint32_t *q_e,
                                             uint32_t *t_out)
@@ -624,51 +637,59 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
     bool have_prefix = false;
 
     // ---- candidate lists: every key is >= the collection threshold, and the k-th key
-    //      normally lies within a factor ~1.4 of it.  One pass over a window of 2047
-    //      buckets of key >> 11 above the threshold (bucket 2047 = everything beyond)
-    //      resolves 20 key bits at once.
+    //      normally lies within a factor ~1.4 of it, or close to the previous call's.  One
+    //      pass over a window of 2047 buckets of key >> 11 (bucket 2047 = everything
+    //      beyond) resolves 20 key bits at once.  A window that was placed by those hints
+    //      and missed the k-th key is tried once more from the smallest key of the list.
     if (Src::AGG && win_base != 0xFFFFFFFFu) {
-        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
-        __syncthreads();
-        for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
-            uint32_t kk[4];
+        uint32_t base = win_base, bmin = win_min;
+        bool counted = win_ready;
+        for (int attempt = 0; attempt < 2; ++attempt) {
+            if (!counted) {   // otherwise the caller has counted the entries while it built the list
+                for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;
+                __syncthreads();
+                for (uint32_t pb = 0; pb < cN; pb += 4 * SEL_THREADS) {
+                    uint32_t kk[4];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const uint32_t p = pb + i * SEL_THREADS + tid;
-                kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
-            }
+                    for (int i = 0; i < 4; ++i) {
+                        const uint32_t p = pb + i * SEL_THREADS + tid;
+                        kk[i] = (p < cN) ? (src.bits(p) & 0x7FFFFFFFu) : 0u;
+                    }
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                if (pb + i * SEL_THREADS + tid < cN) {
-                    const uint32_t hi = kk[i] >> 11;
-                    const uint32_t w = (hi > win_base) ? (hi - win_base) : 0u;
-                    atomicAdd(&S.h[min(w, 2047u)], 1u);
+                    for (int i = 0; i < 4; ++i)
+                        if (pb + i * SEL_THREADS + tid < cN) window_count(S.h, base, kk[i]);
                 }
             }
-        }
-        // third rank: the drift quantile if R is among the candidates; otherwise the entry
-        // below which the lowest quarter of the candidates lies (for the extrapolated hint)
-        const uint32_t qlow = max(cN / 4u, min(cN, 16u));
-        const uint32_t third = measurable ? ((Eq <= cN) ? Eq : 0u) : ((R != 0) ? (cN - qlow + 1u) : 0u);
-        find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, third, S.rowsum, S.res);
-        const int bk = S.res[0], bR = S.res[2], bE = S.res[4];
-        const uint32_t rk = (uint32_t)S.res[1], rR = (uint32_t)S.res[3];
-        if (bk >= 0 && bk < 2047 && bR >= 0 && bR < 2047) {
-            have_prefix = true;
-            pfx = win_base + (uint32_t)bk;
-            r2 = rk;
-            lowbits = 11;
-            if (measurable) {
-                const uint32_t edge = (win_base + (uint32_t)bR) << 11;
-                *tau_next = edge ? edge : 1u;
-                *expect = R - rR + S.h[bR];
-                if (bE >= 0 && bE < 2047) *q_e = (win_base + (uint32_t)bE) << 11;
-            } else if (R != 0 && bE >= 0 && bE < 2047) {
-                *tau_next = hint_extrapolated(max(win_base << 11, 1u), cN, R, qlow, ((uint32_t)bE + 1u) << 11);
-                *expect = R;
+            // third rank: the drift quantile if R is among the candidates; otherwise the entry
+            // below which the lowest quarter of the candidates lies (for the extrapolated hint)
+            const uint32_t qlow = max(cN / 4u, min(cN, 16u));
+            const uint32_t third = measurable ? ((Eq <= cN) ? Eq : 0u) : ((R != 0) ? (cN - qlow + 1u) : 0u);
+            find_ranks<2048, SEL_WAVES>(S.h, k, measurable ? R : k, third, S.rowsum, S.res);
+            const int bk = S.res[0], bR = S.res[2], bE = S.res[4];
+            const uint32_t rk = (uint32_t)S.res[1], rR = (uint32_t)S.res[3];
+            const int lo = (int)bmin;
+            if (bk >= lo && bk < 2047 && bR >= lo && bR < 2047) {
+                have_prefix = true;
+                pfx = base + (uint32_t)bk;
+                r2 = rk;
+                lowbits = 11;
+                if (measurable) {
+                    const uint32_t edge = (base + (uint32_t)bR) << 11;
+                    *tau_next = edge ? edge : 1u;
+                    *expect = R - rR + S.h[bR];
+                    if (bE >= lo && bE < 2047) *q_e = (base + (uint32_t)bE) << 11;
+                } else if (R != 0 && bE >= lo && bE < 2047) {
+                    const uint32_t top = (base + (uint32_t)bE + 1u) << 11;   // the lowest quarter ends below it
+                    *tau_next = hint_extrapolated(max(kmin, 1u), cN, R, qlow, top - min(kmin, top - 1u));
+                    *expect = R;
+                }
             }
+            __syncthreads();
+            if (have_prefix || base == (kmin >> 11)) break;
+            base = kmin >> 11;
+            bmin = 0;
+            counted = false;
         }
-        __syncthreads();
     }
 
     if (!have_prefix) {
@@ -932,24 +953,32 @@ __device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
 // Ordered-list entry: LDS while it fits, global scratch beyond.
 __device__ __forceinline__ void put_entry(uint2 *llist, uint2 *glist, uint32_t pos, uint2 e)
 {
-    if (pos < SEL_LDS_LIST) llist[pos] = e;
-    else glist[pos] = e;
+    if (pos < SEL_LDS_LIST) {
+        llist[pos] = e;
+    } else {
+        glist[pos] = e;
+        // keeps the two stores apart: merged into one store through a generic pointer they
+        // would take the slow flat path into LDS
+        asm volatile("" ::: "memory");
+    }
 }
 
-constexpr uint32_t SEL_BATCH = 3;                               // chunks of SEL_THREADS tiles per batch
-constexpr uint32_t SEL_BATCH_TILES = SEL_BATCH * SEL_THREADS;   // 3072
-constexpr uint32_t SEL_QUADS = SEL_THREADS / 4;                 // groups of 4 lanes, one tile each
-constexpr uint32_t SEL_COPY_ITERS = SEL_BATCH_TILES / SEL_QUADS;
+constexpr uint32_t SEL_ROWS = 12;                                  // rows of 16 tiles per wavefront and batch
+constexpr uint32_t SEL_WAVE_TILES = SEL_ROWS * 16;                 // 192
+constexpr uint32_t SEL_BATCH_TILES = SEL_WAVES * SEL_WAVE_TILES;   // 3072
 
 // One workgroup per tensor.  Big tensors: join the per-tile candidate slots into
 // one ordered list (LDS; lists that outgrow it continue in global scratch), then
-// select.  Small tensors, dense requests and failed predictions: select straight
-// from the state buffer.
+// select on the list; if the list is short or a tile overflowed, select densely
+// from the state buffer.  Small tensors always select densely.
 //
-// Joining: the first 64-byte line of every tile's slots (8 candidates) is fetched
-// by 4 cooperating lanes before the counts are known; the counts are fetched one
-// tile per thread (coalesced), scanned into list positions, and the lanes then
-// drop their two entries into place.  Tiles with more than 8 candidates, and a
+// The join: a batch of tiles is dealt out to the wavefronts in equal runs of whole
+// rows (16 consecutive tiles).  A wavefront fetches the counts of its run, one tile
+// per lane, and the first line of every tile (its first 8 candidates), 4 lanes per
+// tile and a row per load, before the counts are known.  Counts are handed to the
+// tiles' lanes by lane permutation and scanned row by row in registers; one exchange
+// of the wavefronts' totals through LDS gives every tile its list position, and the
+// lanes drop their two entries into place.  Tiles with more than 8 candidates, and a
 // first tile shared with the previous tensor, take a per-tile loop.
 template <int OP>
 __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
@@ -959,9 +988,6 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
 {
     __shared__ SelShared S;
     __shared__ uint2 llist[SEL_LDS_LIST];
-    __shared__ uint32_t tpos[SEL_BATCH_TILES];   // per tile of the batch: position in the list
-    __shared__ uint16_t tcnt[SEL_BATCH_TILES];   // per tile of the batch: this tensor's candidates
-    __shared__ uint32_t start0;                  // first slot of the tensor in a first tile shared with its predecessor
     const uint32_t j = blockIdx.x;
     const uint32_t tid = threadIdx.x;
     const TensorDesc td = A.tdesc[j];
@@ -981,92 +1007,134 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     uint32_t c = 0;
     uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
+    const uint32_t hint2_cur = (td.big && A.write_hint) ? A.hint2[j] : 0u;
+    // every candidate key is >= the collection threshold: the window histogram starts there,
+    // and the join counts the entries into it as it places them
+    // (or 1024 buckets below the k-th key of the previous call, if that lies higher)
+    const uint32_t tprev_cur = td.big ? A.tprev[j] : 0u;
+    const uint32_t win_join = max(tau_cur >> 11, max(tprev_cur >> 11, 1024u) - 1024u);
     uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
     if (tid == 0) S.kmin = 0xFFFFFFFFu;
 
     if (!dense) {
+        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;   // complete before the join's barrier
         const uint32_t ntl = thi - tlo + 1;
-        const uint32_t ql = tid >> 2, sub = tid & 3u;
+        const uint32_t lane = lane_id(), wave = tid >> 6;
+        const uint32_t qw = lane >> 2, sub = lane & 3u;
         uint32_t ovf = 0;
-        for (uint32_t cb = 0; cb < ntl; cb += SEL_BATCH_TILES) {
-            // first line of every tile of the batch, 4 lanes per tile
-            uint4 pf[SEL_COPY_ITERS];
+        auto join_batch = [&](const uint32_t cb) __attribute__((always_inline)) {
+            const uint32_t nb = min(ntl - cb, SEL_BATCH_TILES);
+            const uint32_t rows = (nb + 16 * SEL_WAVES - 1) / (16 * SEL_WAVES);   // per wavefront, 1..SEL_ROWS
+            const uint32_t w0 = cb + wave * rows * 16;                            // first tile of this wavefront's run
+            // counts of the run, one tile per lane and load
+            uint32_t w[SEL_ROWS / 4];
 #pragma unroll
-            for (uint32_t it = 0; it < SEL_COPY_ITERS; ++it) {
-                const uint32_t tl = cb + it * SEL_QUADS + ql;
+            for (uint32_t u = 0; u < SEL_ROWS / 4; ++u) {
+                const uint32_t sl = u * 64 + lane;
+                w[u] = (sl < rows * 16 && w0 + sl < ntl) ? tile_cnt[tlo + w0 + sl] : 0u;
+            }
+            // first line of every tile of the run
+            uint4 pf[SEL_ROWS];
+#pragma unroll
+            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
+                const uint32_t tl = w0 + it * 16 + qw;
                 pf[it] = make_uint4(0, 0, 0, 0);
-                if (tl < ntl) pf[it] = ((const uint4 *)(heads + (size_t)(tlo + tl) * HEAD))[sub];
+                if (it < rows && tl < ntl) pf[it] = ((const uint4 *)(heads + (size_t)(tlo + tl) * HEAD))[sub];
             }
-            // counts, one tile per thread and chunk
-            uint32_t w[SEL_BATCH];
+            // a first tile shared with the previous tensor: that tensor's candidates come first
+            uint32_t start0 = 0;
+            if (head_shared && w0 == 0) {
+                const uint32_t ww = (uint32_t)__builtin_amdgcn_readfirstlane((int)w[0]);
+                if (ww != CNT_OVERFLOW) {
+                    start0 = ww & 0xFFFFu;
+                    if (lane == 0) w[0] = ww >> 16;
+                }
+            }
 #pragma unroll
-            for (uint32_t u = 0; u < SEL_BATCH; ++u) {
-                const uint32_t tl = cb + u * SEL_THREADS + tid;
-                w[u] = (tl < ntl) ? tile_cnt[tlo + tl] : 0u;
+            for (uint32_t u = 0; u < SEL_ROWS / 4; ++u) {
+                if (w[u] == CNT_OVERFLOW) { ovf = 1; w[u] = 0; }
+                else if (!(head_shared && w0 == 0 && u == 0 && lane == 0)) w[u] &= 0xFFFFu;
             }
+            // positions inside the run: the counts go to the tiles' lanes, rows are scanned in turn
+            // (per tile: count in the low half, position in the high half -- a run holds at
+            // most 192 * CAPT entries)
+            uint32_t cp[SEL_ROWS];
+            uint32_t run = 0;
 #pragma unroll
-            for (uint32_t u = 0; u < SEL_BATCH; ++u) {
-                if (cb + u * SEL_THREADS >= ntl) break;      // uniform
-                const uint32_t tl = cb + u * SEL_THREADS + tid;
-                uint32_t ww = w[u];
-                if (ww == CNT_OVERFLOW) { ovf = 1; ww = 0; }
-                const bool hs = head_shared && (tl == 0);
-                const uint32_t cnt = hs ? (ww >> 16) : (ww & 0xFFFFu);
-                const uint32_t start = hs ? (ww & 0xFFFFu) : 0u;
-                uint32_t ctot;
-                const uint32_t pos = c + block_excl_scan<SEL_WAVES>(cnt, S.wsum, ctot);
-                tpos[u * SEL_THREADS + tid] = pos;
-                tcnt[u * SEL_THREADS + tid] = (uint16_t)cnt;
-                if (hs) start0 = start;
-                c += ctot;
+            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
+                cp[it] = 0;
+                if (it < rows) {                                                  // uniform
+                    const uint32_t n_t = (uint32_t)__builtin_amdgcn_ds_bpermute(
+                        (int)((((it & 3u) * 16u) + qw) * 4u), (int)w[it >> 2]);
+                    const uint32_t incl = wave_incl_scan(sub == 0 ? n_t : 0u);    // over the row's tiles
+                    cp[it] = n_t | ((run + incl - n_t) << 16);
+                    run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
+                }
             }
+            if (lane == 0) S.wsum[wave] = run;
             __syncthreads();
+            uint32_t before = 0, tot = 0;
+#pragma unroll
+            for (uint32_t x = 0; x < SEL_WAVES; ++x) {
+                const uint32_t v = S.wsum[x];
+                if (x < wave) before += v;
+                tot += v;
+            }
+            const uint32_t base = c + before;
+            c += tot;
             // entries into place
 #pragma unroll
-            for (uint32_t it = 0; it < SEL_COPY_ITERS; ++it) {
-                const uint32_t li = it * SEL_QUADS + ql;
-                const uint32_t tl = cb + li;
-                if (tl >= ntl) continue;
-                const uint32_t cnt = tcnt[li];
-                const uint32_t start = (head_shared && tl == 0) ? start0 : 0u;
-                const uint32_t pos = tpos[li];
-                if (cnt == 0) continue;
+            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
+                const uint32_t tl = w0 + it * 16 + qw;
+                const uint32_t n_t = cp[it] & 0xFFFFu;
+                if (n_t == 0) continue;
+                const uint32_t start = (tl == 0) ? start0 : 0u;
+                const uint32_t pos = base + (cp[it] >> 16);
                 uint32_t i0 = 0;
                 if (start == 0) {
-                    if (2 * sub < cnt) {
+                    if (2 * sub < n_t) {
                         put_entry(llist, glist, pos + 2 * sub, make_uint2(pf[it].x, pf[it].y));
                         kmin = min(kmin, pf[it].y & 0x7FFFFFFFu);
+                        window_count(S.h, win_join, pf[it].y & 0x7FFFFFFFu);
                     }
-                    if (2 * sub + 1 < cnt) {
+                    if (2 * sub + 1 < n_t) {
                         put_entry(llist, glist, pos + 2 * sub + 1, make_uint2(pf[it].z, pf[it].w));
                         kmin = min(kmin, pf[it].w & 0x7FFFFFFFu);
+                        window_count(S.h, win_join, pf[it].w & 0x7FFFFFFFu);
                     }
                     i0 = HEAD;
                 }
-                if (i0 < cnt) {
+                if (i0 < n_t) {
                     // the rest of a crowded tile: the four lanes interleave, each with four
                     // independent loads at a time (entry q of the tile: heads for q < HEAD,
                     // slots beyond)
                     const uint2 *hd = heads + (size_t)(tlo + tl) * HEAD;
                     const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT;
-                    for (uint32_t i = i0 + sub; i < cnt; i += 16) {
+                    for (uint32_t i = i0 + sub; i < n_t; i += 16) {
                         uint2 e[4];
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) {
                             const uint32_t q = start + i + 4 * v;
-                            e[v] = (i + 4 * v < cnt) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
+                            e[v] = (i + 4 * v < n_t) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
                         }
 #pragma unroll
                         for (uint32_t v = 0; v < 4; ++v) {
-                            if (i + 4 * v < cnt) {
+                            if (i + 4 * v < n_t) {
                                 put_entry(llist, glist, pos + i + 4 * v, e[v]);
                                 kmin = min(kmin, e[v].y & 0x7FFFFFFFu);
+                                window_count(S.h, win_join, e[v].y & 0x7FFFFFFFu);
                             }
                         }
                     }
                 }
             }
-            __syncthreads();   // tpos / tcnt are reused by the next batch
+        };
+        // the first batch (up to 3072 tiles: all there is, as a rule) stands outside the loop, so
+        // that what the loop keeps in registers across its rounds does not weigh on it
+        join_batch(0);
+        for (uint32_t cb = SEL_BATCH_TILES; cb < ntl; cb += SEL_BATCH_TILES) {
+            __syncthreads();   // wsum is reused
+            join_batch(cb);
         }
         kmin = wave_min_to_last(kmin);
         if (lane_id() == 63) atomicMin(&S.kmin, kmin);
@@ -1103,11 +1171,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     // ---- rank whose key becomes the next predicted threshold
     uint32_t R = 0, Eq = 0;
     if (td.big && A.write_hint)
-        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, A.hint2[j], A.m, &Eq);
+        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, hint2_cur, A.m, &Eq);
 
     uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
-    // every candidate key is >= kmin (>= the collection threshold): the window starts there
-    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (kmin >> 11);
+    // the join's histogram stands if no candidate lies below the threshold (none can)
+    const bool win_ready = (kmin != 0xFFFFFFFFu) && (kmin >> 11) >= (tau_cur >> 11);
+    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (win_ready ? win_join : (kmin >> 11));
+    const uint32_t win_min = (win_ready && win_join > (kmin >> 11)) ? 1u : 0u;   // entries below the window
     if (dense) {
         if (td.n <= 2 * SEL_LDS_LIST) {
             uint32_t *lv = (uint32_t *)llist;
@@ -1116,17 +1186,21 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                 lv[p] = __float_as_uint(row_value<OP>(A.state, A.model, td.off + p));
             __syncthreads();
             SrcDenseLds src{lv, td.off};
-            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
+            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, S, A, pe.outoff,
+                               &tau_next, &expect, &q_e, &t_k);
         } else {
             SrcDense<OP> src{A.state, A.model, td.off};
-            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
+            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, S, A, pe.outoff,
+                               &tau_next, &expect, &q_e, &t_k);
         }
     } else if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
+        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, S, A, pe.outoff,
+                           &tau_next, &expect, &q_e, &t_k);
     } else {
         SrcList src{glist};
-        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, S, A, pe.outoff, &tau_next, &expect, &q_e, &t_k);
+        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, S, A, pe.outoff,
+                           &tau_next, &expect, &q_e, &t_k);
     }
 
     if (td.big && A.write_hint && tid == 0) {
