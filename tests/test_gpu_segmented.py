@@ -151,6 +151,24 @@ def test_automatic_mode_mixes_both_selections(oracle):
         assert st.segmented_tensors == (3 if rho == 1e-3 else 6)
 
 
+@pytest.mark.parametrize("seg_mode", [None, dgs.SEG_NEVER], ids=["auto", "never"])
+def test_single_workgroup_join_over_several_batches(oracle, seg_mode):
+    """Tensors of more than 3072 tiles that stay on the single-workgroup path (below the
+    size where the multi-workgroup chain takes over by itself, or above it with that chain
+    switched off) are joined in several batches; the second tensor starts inside a tile of
+    the first.  A crowded stretch (every element a candidate in a few tiles) spills into the
+    per-tile slots on the way."""
+    sizes = [3_400_017, 3_900_000, 5000] if seg_mode is None else [3_400_017, 7_000_001, 5000]
+    off = synth.offsets_from_sizes(sizes)
+    scales = synth.tensor_scales(len(sizes), 55)
+    rng = np.random.default_rng(56)
+    grads = [synth.gaussian_grads(off, scales, rng) for _ in range(4)]
+    for g in grads[2:]:
+        g[3_400_000:3_400_600] *= np.float32(50.0)      # crowded tiles across the tensor border
+    st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), 1e-3, seg_mode=seg_mode)
+    assert st.segmented_tensors == 0 and st.internal_errors == 0
+
+
 @pytest.mark.parametrize("rho", [0.05, 0.5, 1.0])
 def test_dense_requests_on_large_tensors(oracle, rho):
     """Densities above 1/32 on tensors of at least 65536 elements: no candidate lists, the
