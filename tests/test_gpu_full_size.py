@@ -111,6 +111,48 @@ def test_c4_transformer_shapes_heavy_tails(oracle):
     ctx.close()
 
 
+def test_c4_server_eight_workers(oracle):
+    """Config 4, server side: 8 difference rows over the 108,375,552-parameter layout; the
+    pushed messages are what a worker sends for the heavy-tailed, row-sparse gradients (taken
+    from the oracle), in an interleaving where two workers pull twice.  The embedding goes
+    through the multi-workgroup selection, the other tensors through the single-workgroup one."""
+    import torch
+    off = synth.layout_transformer()
+    n = int(off[-1])
+    J = len(off) - 1
+    W = 8
+    scales = synth.tensor_scales(J, 4)
+    rng = np.random.default_rng(44)
+    g = synth.student_t_grads(off, scales, rng)
+    synth.zero_rows(g, int(off[J - 1]), 30522, 768, 0.05, rng)
+    s_ref = np.zeros(n, np.float32)
+    msgs = []
+    for gg in (g, (g[::-1] * np.float32(0.5)).copy()):
+        wi, wv = oracle.worker_step(gg, s_ref, off, np.float32(0.1), np.float32(0.9), 1e-3)
+        msgs.append((wi.copy(), wv.copy()))
+    del g, s_ref
+    ctx = dgs.Context(off, W=W)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=1e-3)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((W, n), np.float32)
+    for e, k in enumerate((0, 5, 0, 7, 5)):
+        idx, val = msgs[e % 2]
+        oracle.server_push(model_ref, diff_ref, idx, val)
+        srv.push(k, idx, val)
+        wi, wv = oracle.server_pull(diff_ref, k, off, 1e-3)
+        gi, gv = srv.pull(k, 1e-3)
+        assert gi.size == 108_401
+        assert_pairs_match(gi, gv, wi, wv, f"event {e} pull({k})")
+    assert_state_match(srv.model.cpu().numpy(), model_ref, "model")
+    for w_ in (0, 5, 3):
+        assert_state_match(srv.diff[w_].cpu().numpy(), diff_ref[w_], f"diff row {w_}")
+    st = ctx.stats()
+    assert st.internal_errors == 0 and st.segmented_tensors >= 5
+    ctx.close()
+    del srv
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("rho,K", [(1e-4, 100_032), (1e-2, 10_000_000)])
 def test_c5_one_billion_parameters(oracle, rho, K):
     """Config 5: 1e9 parameters in 64 equal tensors.  The oracle follows three
