@@ -10,7 +10,10 @@
  * Distributed Training"):
  *   - worker update with sparsification-aware momentum: Algorithm 3, Eq. 11, Eq. 12;
  *     with momentum 0 it is the residual scheme of Algorithm 1;
- *   - server: Algorithm 2 with secondary compression, Eq. 1, Eq. 3, Eq. 6.
+ *   - server: Algorithm 2 with secondary compression, Eq. 1, Eq. 3, Eq. 6;
+ *   - encode() / decode(): the paper asks for coordinate format only; the byte layout of
+ *     dgs_oracle_encode is this library's own (PARITY UNPINNED with respect to the paper,
+ *     pinned to its own statement), see there.
  *
  * Readings fixed where the paper is silent (all listed in the design notes):
  *   - "thr <- R% of |x|" is the k-th largest magnitude of tensor j with
@@ -341,6 +344,111 @@ int dgs_oracle_apply_sparse(float *dst, uint64_t n, const uint32_t *idx, const f
     for (e = 0; e < nnz; ++e) {
         if (idx[e] >= n) return ORACLE_EINVAL;
         dst[idx[e]] = fmaf(sign, val[e], dst[idx[e]]);
+    }
+    return ORACLE_OK;
+}
+
+/*
+ * Wire form of one message: encode() / decode() of Algorithms 1-3.  The paper only says
+ * that encode() packs the nonzero entries into coordinate format; the (idx, val) pairs
+ * above already are that.  The byte layout below is this library's own -- PARITY UNPINNED
+ * with respect to the paper: the pins fix it to the statement given here (a byte string
+ * worked out by hand, a big-integer construction, the round trip), not to anything printed
+ * in the paper.
+ *
+ * A message for (layout, density) holds exactly k_j = ceil(density * n_j) entries of every
+ * tensor j, ascending, tensor after tensor (K = sum k_j); both ends know the layout and the
+ * density, so there is no header:
+ *   bytes [0, 4K)   the K values, fp32 little-endian, in message order (bit-exact);
+ *   then for j = 0 .. J-1 the index block of tensor j: its k_j local indices idx - off_j,
+ *   b_j bits each with b_j = number of bits of n_j - 1 (at least 1); entry e holds bits
+ *   [e b_j, (e + 1) b_j) of the block, least significant bit first; bit i of the block is
+ *   bit i mod 8 of its byte i / 8; the block is padded with zero bits to a multiple of 4
+ *   bytes.
+ */
+static uint32_t index_bits(uint64_t nj)
+{
+    uint32_t b = 0;
+    uint64_t top = nj - 1;
+    while (top) { ++b; top >>= 1; }
+    return b ? b : 1;
+}
+
+int dgs_oracle_wire_bytes(const uint64_t *offsets, uint32_t J, double density, uint64_t *bytes_out)
+{
+    uint32_t j;
+    uint64_t bytes = 0;
+    if (!(density > 0.0) || density > 1.0) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        bytes += 4 * kj;                                       /* values */
+        bytes += 4 * ((kj * index_bits(nj) + 31) / 32);        /* index block */
+    }
+    *bytes_out = bytes;
+    return ORACLE_OK;
+}
+
+int dgs_oracle_encode(const uint64_t *offsets, uint32_t J, double density, const uint32_t *idx,
+                      const float *val, uint8_t *wire)
+{
+    uint32_t j, t;
+    uint64_t K = 0, e, o = 0, base, total;
+    if (dgs_oracle_wire_bytes(offsets, J, density, &total) != ORACLE_OK) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) K += dgs_oracle_k(density, offsets[j + 1] - offsets[j]);
+    memset(wire, 0, total);
+    for (e = 0; e < K; ++e) {                                   /* values, byte by byte */
+        uint32_t bits;
+        memcpy(&bits, &val[e], sizeof bits);
+        for (t = 0; t < 4; ++t) wire[4 * e + t] = (uint8_t)(bits >> (8 * t));
+    }
+    base = 4 * K;                                               /* first byte of the current index block */
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        uint32_t b = index_bits(nj);
+        for (e = 0; e < kj; ++e, ++o) {
+            uint64_t local;
+            if (idx[o] < offsets[j] || idx[o] >= offsets[j + 1]) return ORACLE_EINVAL;
+            if (e > 0 && idx[o] <= idx[o - 1]) return ORACLE_EINVAL;
+            local = idx[o] - offsets[j];
+            for (t = 0; t < b; ++t) {                           /* bit by bit */
+                uint64_t pos = e * b + t;
+                if ((local >> t) & 1u) wire[base + pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+        }
+        base += 4 * ((kj * b + 31) / 32);
+    }
+    return ORACLE_OK;
+}
+
+int dgs_oracle_decode(const uint64_t *offsets, uint32_t J, double density, const uint8_t *wire,
+                      uint32_t *idx, float *val)
+{
+    uint32_t j, t;
+    uint64_t K = 0, e, o = 0, base;
+    if (!(density > 0.0) || density > 1.0) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) K += dgs_oracle_k(density, offsets[j + 1] - offsets[j]);
+    for (e = 0; e < K; ++e) {
+        uint32_t bits = 0;
+        for (t = 0; t < 4; ++t) bits |= (uint32_t)wire[4 * e + t] << (8 * t);
+        memcpy(&val[e], &bits, sizeof bits);
+    }
+    base = 4 * K;
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        uint32_t b = index_bits(nj);
+        for (e = 0; e < kj; ++e, ++o) {
+            uint64_t local = 0;
+            for (t = 0; t < b; ++t) {
+                uint64_t pos = e * b + t;
+                if ((wire[base + pos / 8] >> (pos % 8)) & 1u) local |= (uint64_t)1 << t;
+            }
+            if (local >= nj) return ORACLE_EINVAL;
+            idx[o] = (uint32_t)(offsets[j] + local);
+        }
+        base += 4 * ((kj * b + 31) / 32);
     }
     return ORACLE_OK;
 }

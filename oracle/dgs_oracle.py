@@ -58,6 +58,10 @@ def lib():
                                                    ctypes.c_uint64]
         L.dgs_oracle_server_pull_sent.argtypes = [_c_f32p, _c_f32p, _c_u64p, ctypes.c_uint32,
                                                   ctypes.c_double, _c_u32p, _c_f32p, _c_u64p]
+        _c_u8p = ctypes.POINTER(ctypes.c_uint8)
+        L.dgs_oracle_wire_bytes.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u64p]
+        L.dgs_oracle_encode.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u32p, _c_f32p, _c_u8p]
+        L.dgs_oracle_decode.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u8p, _c_u32p, _c_f32p]
         _lib = L
     return _lib
 
@@ -181,3 +185,31 @@ def server_pull_all(diff: np.ndarray, k: int, capacity: int | None = None):
 def apply_sparse(dst: np.ndarray, idx: np.ndarray, val: np.ndarray, sign: float = 1.0) -> None:
     _check(lib().dgs_oracle_apply_sparse(_f32(dst), dst.size, _u32(idx), _f32(val), idx.size, sign),
            "apply_sparse")
+
+
+def wire_bytes(offsets: np.ndarray, density: float) -> int:
+    out = ctypes.c_uint64(0)
+    _check(lib().dgs_oracle_wire_bytes(_u64(offsets), len(offsets) - 1, float(density), ctypes.byref(out)),
+           "wire_bytes")
+    return int(out.value)
+
+
+def encode(offsets: np.ndarray, density: float, idx: np.ndarray, val: np.ndarray) -> np.ndarray:
+    """The message's wire form (uint8 array)."""
+    _, K = nnz(offsets, density)
+    assert idx.size == K and val.size == K
+    wire = np.zeros(wire_bytes(offsets, density), dtype=np.uint8)
+    _check(lib().dgs_oracle_encode(_u64(offsets), len(offsets) - 1, float(density), _u32(idx), _f32(val),
+                                   wire.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "encode")
+    return wire
+
+
+def decode(offsets: np.ndarray, density: float, wire: np.ndarray):
+    _, K = nnz(offsets, density)
+    assert wire.dtype == np.uint8 and wire.flags.c_contiguous and wire.size == wire_bytes(offsets, density)
+    idx = np.zeros(K, dtype=np.uint32)
+    val = np.zeros(K, dtype=np.float32)
+    _check(lib().dgs_oracle_decode(_u64(offsets), len(offsets) - 1, float(density),
+                                   wire.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _u32(idx), _f32(val)),
+           "decode")
+    return idx, val

@@ -536,6 +536,76 @@ def test_hand_example(oracle):
         assert diff.tolist() == ev["diff"]
 
 
+def wire_by_big_integers(off, kj, idx, val) -> bytes:
+    """The wire form built with Python integers: one big integer per index block."""
+    out = np.ascontiguousarray(val).astype("<f4").tobytes()
+    o = 0
+    for j in range(len(off) - 1):
+        nj = int(off[j + 1] - off[j])
+        b = max(1, (nj - 1).bit_length())
+        block = 0
+        for e in range(int(kj[j])):
+            block |= (int(idx[o]) - int(off[j])) << (e * b)
+            o += 1
+        out += block.to_bytes(4 * ((int(kj[j]) * b + 31) // 32), "little")
+    return out
+
+
+def test_wire_form_hand_example(oracle):
+    with open(os.path.join(HERE, "golden", "x2_wire_example.json")) as f:
+        ex = json.load(f)
+    off = synth.offsets_from_sizes(ex["sizes"])
+    kj, K = oracle.nnz(off, ex["density"])
+    assert list(kj) == ex["k"] and K == len(ex["idx"])
+    idx = np.array(ex["idx"], np.uint32)
+    val = np.array([int(h, 16) for h in ex["val_bits_hex"]], np.uint32).view(np.float32)
+    want = bytes.fromhex(ex["wire_hex"].replace(" ", ""))
+    assert oracle.wire_bytes(off, ex["density"]) == len(want) == 48
+    assert oracle.encode(off, ex["density"], idx, val).tobytes() == want
+    di, dv = oracle.decode(off, ex["density"], np.frombuffer(want, np.uint8).copy())
+    assert np.array_equal(di, idx) and np.array_equal(bits(dv), bits(val))
+    ex2 = ex["second"]
+    off2 = synth.offsets_from_sizes(ex2["sizes"])
+    val2 = np.array([int(h, 16) for h in ex2["val_bits_hex"]], np.uint32).view(np.float32)
+    want2 = bytes.fromhex(ex2["wire_hex"].replace(" ", ""))
+    assert oracle.encode(off2, ex2["density"], np.array(ex2["idx"], np.uint32), val2).tobytes() == want2
+
+
+def test_wire_form_against_big_integer_construction(oracle):
+    rng = np.random.default_rng(77)
+    for trial in range(12):
+        J = int(rng.integers(1, 9))
+        rho = float(rng.choice([1e-3, 0.01, 0.3, 1.0]))
+        pool = [1, 2, 3, 31, 32, 33, 255, 256, 257, 1000, 4096, 65_536, 65_537, 100_003, 1 << 20]
+        pool = [x for x in pool if x * rho <= 4096]          # keeps the big integers small
+        sizes = [int(x) for x in rng.choice(pool, J)]
+        off = synth.offsets_from_sizes(sizes)
+        kj, K = oracle.nnz(off, rho)
+        idx = np.concatenate([np.sort(rng.choice(sizes[j], int(kj[j]), replace=False)) + int(off[j])
+                              for j in range(J)]).astype(np.uint32)
+        val = rng.integers(0, 1 << 32, K, dtype=np.uint64).astype(np.uint32).view(np.float32)   # any bit pattern
+        want = wire_by_big_integers(off, kj, idx, val)
+        assert oracle.wire_bytes(off, rho) == len(want)
+        wire = oracle.encode(off, rho, idx, val)
+        assert wire.tobytes() == want, f"trial {trial}: sizes {sizes} density {rho}"
+        di, dv = oracle.decode(off, rho, wire)
+        assert np.array_equal(di, idx) and np.array_equal(bits(dv), bits(val))
+
+
+def test_wire_form_rejects_entries_outside_their_tensor(oracle):
+    off = synth.offsets_from_sizes([10, 10])
+    val = np.ones(2, np.float32)
+    with pytest.raises(Exception):
+        oracle.encode(off, 0.1, np.array([3, 7], np.uint32), val)        # second entry not in tensor 1
+    off1 = synth.offsets_from_sizes([100])
+    with pytest.raises(Exception):
+        oracle.encode(off1, 0.02, np.array([5, 5], np.uint32), val)      # not ascending
+    wire = oracle.encode(off1, 0.02, np.array([5, 99], np.uint32), val)
+    wire[8] = 0xFF                                                       # local index 127 >= n
+    with pytest.raises(Exception):
+        oracle.decode(off1, 0.02, wire)
+
+
 def test_oracle_sources_are_independent_of_the_product():
     """The oracle and the HIP path share no code and do not import each other."""
     root = os.path.dirname(HERE)
