@@ -308,6 +308,20 @@ def main():
         kernel_us[kname] = round(ms / cnt * 1e3, 2) if cnt else None
         if kind == dom_kind and cnt:
             dom_us = ms / cnt * 1e3
+    # wire form of the last pulled message (outside the timed step: the paper's encode() is the
+    # coordinate format the step already produces; this is the byte layout for a network)
+    wire = torch.zeros(ctx.wire_bytes(rho), dtype=torch.uint8, device=dev)
+    didx, dval = torch.zeros_like(pidx), torch.zeros_like(pval)
+    for _ in range(20):
+        ctx.encode(rho, pidx, pval, wire)
+        ctx.decode(rho, wire, didx, dval)
+    torch.cuda.synchronize()
+    wire_info = {"bytes": int(wire.numel()), "pair_bytes": 8 * K,
+                 "round_trip_ok": bool(torch.equal(didx, pidx) and torch.equal(dval.view(torch.int32),
+                                                                              pval.view(torch.int32)))}
+    for kname, kind in (("encode_us", dgs.PROF_ENCODE), ("decode_us", dgs.PROF_DECODE)):
+        cnt, ms = ctx.profile_read(kind)
+        wire_info[kname] = round(ms / cnt * 1e3, 2) if cnt else None
     ctx.set_option(dgs.OPT_PROFILE, 0)
     st = ctx.stats()
 
@@ -332,6 +346,7 @@ def main():
                    "server_form": args.server_form},
         "roofline": roofline,
         "kernel_us": kernel_us,
+        "wire_form": wire_info,
         "step_algorithmic_GBs": step_bytes / (dt / steps) / 1e9,
         "stats": {"exact_calls": st.exact_calls, "fallback_tensors": st.fallback_tensors,
                   "segmented_tensors": st.segmented_tensors, "repaired_tensors": st.repaired_tensors,

@@ -67,7 +67,9 @@ enum {
     DGS_PROF_EXACT_EXTRA = 5,   /* second (collecting) pass of the non-predicted path */
     DGS_PROF_WORKER_SEGMENTED = 6, /* multi-workgroup selection kernels, first begin to last end */
     DGS_PROF_PULL_SEGMENTED = 7,
-    DGS_PROF_KINDS = 8
+    DGS_PROF_ENCODE = 8,        /* dgs_encode */
+    DGS_PROF_DECODE = 9,        /* dgs_decode */
+    DGS_PROF_KINDS = 10
 };
 
 typedef struct dgs_stats {
@@ -222,6 +224,32 @@ int dgs_server_pull_all(dgs_ctx *ctx, uint32_t worker_id, uint32_t *idx_out, flo
  */
 int dgs_apply_sparse(dgs_ctx *ctx, float *dst, const uint32_t *idx, const float *val,
                      uint64_t nnz, float sign);
+
+/*
+ * Wire form of a message: the encode() / decode() of Algorithms 1-3, which the paper
+ * describes only as packing the nonzero entries into coordinate format.  The (idx, val)
+ * pairs of the calls above are that format in memory; these two calls turn a message into
+ * the bytes to put on a network and back, without loss.  The layout is this library's own:
+ *   bytes [0, 4K)  the K = dgs_nnz(density) values, fp32 little-endian, in message order;
+ *   then, tensor after tensor, the k_j local indices idx - off_j of tensor j, b_j bits each
+ *   (b_j = number of bits of n_j - 1, at least 1), entry e in bits [e b_j, (e + 1) b_j) of
+ *   the tensor's block, least significant bit first, bit i of a block in bit i mod 8 of its
+ *   byte i / 8, each block padded with zero bits to a multiple of 4 bytes.
+ * Both ends derive k_j, b_j and every offset from the layout and the density: no header.
+ * A message is what dgs_worker_step, dgs_server_pull or dgs_server_pull_sent returned for
+ * `density`: exactly k_j ascending entries per tensor (not dgs_server_pull_all's).
+ *   dgs_wire_bytes  size of the wire form in bytes (host result; a multiple of 4).
+ *   dgs_encode      idx, val: device, K entries; wire: device, 4-byte aligned,
+ *                   dgs_wire_bytes(density) bytes, written completely.
+ *   dgs_decode      the reverse; idx_out, val_out: device, K entries.
+ * Asynchronous on the context's stream.  With DGS_OPT_VALIDATE both calls check on the device
+ * that every entry lies inside its tensor (this synchronises) and return DGS_EINVAL if not;
+ * without it such an index is cut to b_j bits (encode) or passed on as decoded (decode,
+ * to be caught by dgs_server_push's own range check).
+ */
+int dgs_wire_bytes(dgs_ctx *ctx, double density, uint64_t *bytes_out /*host*/);
+int dgs_encode(dgs_ctx *ctx, double density, const uint32_t *idx, const float *val, void *wire);
+int dgs_decode(dgs_ctx *ctx, double density, const void *wire, uint32_t *idx_out, float *val_out);
 
 int dgs_set_option(dgs_ctx *ctx, int option, int64_t value);
 

@@ -88,6 +88,7 @@ struct PlanSlot {
     int seg_mode = 0;
     uint32_t nseg_active = 0;          // tensors planned as segmented
     uint64_t K = 0;
+    uint64_t wire_words = 0;           // 32-bit words of the wire form's index area
     uint64_t last_use = 0;
 };
 
@@ -174,9 +175,9 @@ struct ProfSlot {
 
 // k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
 void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out,
-               uint32_t *nseg_active)
+               uint32_t *nseg_active, uint64_t *wire_words_out)
 {
-    uint64_t K = 0;
+    uint64_t K = 0, words = 0;
     uint32_t active = 0;
     for (uint32_t j = 0; j < c->J; ++j) {
         const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
@@ -202,12 +203,20 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
                       (k2 > k2p ? k2 : k2p) > SEL_LDS_LIST;
         }
         out[j].seg = seg ? 1u : 0u;
-        out[j].pad0 = out[j].pad1 = out[j].pad2 = 0;
+        // wire form: local indices of b bits each, the tensor's block padded to whole words
+        uint32_t b = 0;
+        for (uint64_t top = nj - 1; top; top >>= 1) ++b;
+        if (b == 0) b = 1;
+        out[j].wire_off = (uint32_t)words;      // fits: words <= K, checked by the caller
+        out[j].wire_bits = b;
+        out[j].pad2 = 0;
+        words += (k * b + 31) / 32;
         active += seg ? 1u : 0u;
         K += k;
     }
     *nseg_active = active;
     *K_out = K;
+    *wire_words_out = words;
 }
 
 // Returns the cache slot holding the plan for `density`, uploading it if new.
@@ -234,9 +243,9 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
         if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
     }
     PlanEntry *stage = c->plan_stage + (size_t)victim * c->J;
-    uint64_t K = 0;
+    uint64_t K = 0, wire_words = 0;
     uint32_t active = 0;
-    fill_plan(c, density, c->margin_pct, stage, &K, &active);
+    fill_plan(c, density, c->margin_pct, stage, &K, &active, &wire_words);
     if (K >= (1ull << 32)) return DGS_EINVAL;
     if (hipMemcpyAsync(c->plans + (size_t)victim * c->J, stage, (size_t)c->J * sizeof(PlanEntry),
                        hipMemcpyHostToDevice, c->stream) != hipSuccess)
@@ -248,6 +257,7 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
     p.seg_mode = c->seg_mode;
     p.nseg_active = active;
     p.K = K;
+    p.wire_words = wire_words;
     p.last_use = c->tick;
     *slot_out = victim;
     *K_out = K;
@@ -723,6 +733,78 @@ int dgs_apply_sparse(dgs_ctx *c, float *dst, const uint32_t *idx, const float *v
     if (nnz && (!idx || !val)) return DGS_EINVAL;
     launch_apply(dst, idx, val, (uint32_t)nnz, sign, c->stream);
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+int dgs_wire_bytes(dgs_ctx *c, double density, uint64_t *bytes_out)
+{
+    if (!c || !bytes_out || !(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    uint32_t slot;
+    uint64_t K;
+    const int rc = get_plan(c, density, &slot, &K);
+    if (rc != DGS_OK) return rc;
+    *bytes_out = 4ull * (K + c->plan_slot[slot].wire_words);
+    return DGS_OK;
+}
+
+namespace {
+
+// Reads the device flag the validating kernels set (synchronises).
+int read_flag(dgs_ctx *c, uint32_t *out)
+{
+    if (hipMemcpyAsync(out, c->flag, sizeof(uint32_t), hipMemcpyDeviceToHost, c->stream) != hipSuccess)
+        return DGS_EHIP;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    return DGS_OK;
+}
+
+}  // namespace
+
+int dgs_encode(dgs_ctx *c, double density, const uint32_t *idx, const float *val, void *wire)
+{
+    if (!c || !idx || !val || !wire || !(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!aligned4(idx) || !aligned4(val) || !aligned4(wire)) return DGS_EINVAL;
+    uint32_t slot;
+    uint64_t K;
+    const int rc = get_plan(c, density, &slot, &K);
+    if (rc != DGS_OK) return rc;
+    const uint64_t words = c->plan_slot[slot].wire_words;
+    if (K + words >= (1ull << 32)) return DGS_EINVAL;
+    if (c->validate) launch_fill_u32(c->flag, 0u, 1, c->stream);
+    ProfSlot ps(c, DGS_PROF_ENCODE);
+    launch_wire_pack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, (uint32_t)words, idx, val,
+                     (uint32_t *)wire, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
+    ps.launched();
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    if (c->validate) {
+        uint32_t bad = 0;
+        const int rf = read_flag(c, &bad);
+        if (rf != DGS_OK) return rf;
+        if (bad) return DGS_EINVAL;
+    }
+    return DGS_OK;
+}
+
+int dgs_decode(dgs_ctx *c, double density, const void *wire, uint32_t *idx_out, float *val_out)
+{
+    if (!c || !idx_out || !val_out || !wire || !(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!aligned4(idx_out) || !aligned4(val_out) || !aligned4(wire)) return DGS_EINVAL;
+    uint32_t slot;
+    uint64_t K;
+    const int rc = get_plan(c, density, &slot, &K);
+    if (rc != DGS_OK) return rc;
+    if (c->validate) launch_fill_u32(c->flag, 0u, 1, c->stream);
+    ProfSlot ps(c, DGS_PROF_DECODE);
+    launch_wire_unpack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, (const uint32_t *)wire,
+                       idx_out, val_out, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
+    ps.launched();
+    if (hipGetLastError() != hipSuccess) return DGS_EHIP;
+    if (c->validate) {
+        uint32_t bad = 0;
+        const int rf = read_flag(c, &bad);
+        if (rf != DGS_OK) return rf;
+        if (bad) return DGS_EINVAL;
+    }
     return DGS_OK;
 }
 

@@ -75,7 +75,9 @@ struct PlanEntry {
     uint32_t outoff;  // sum of k over earlier tensors
     uint32_t k2_pull; // same for a pull, whose sent entries vanish: about 2k (<= n_j)
     uint32_t seg;     // 1: segmented selection at this density
-    uint32_t pad0, pad1, pad2;
+    uint32_t wire_off;   // wire form: first 32-bit word of the tensor's index block (after the values)
+    uint32_t wire_bits;  // wire form: bits per local index = bit length of n_j - 1 (>= 1)
+    uint32_t pad2;
 };
 
 struct SegDesc {
@@ -196,6 +198,12 @@ void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *e
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
                  const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1);
 void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t *flag, void *stream);
+void launch_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K, uint32_t words,
+                      const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag, void *stream,
+                      void *ev0, void *ev1);
+void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K,
+                        const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag, void *stream,
+                        void *ev0, void *ev1);
 void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream);
 void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream);

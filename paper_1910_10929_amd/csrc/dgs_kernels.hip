@@ -1894,6 +1894,100 @@ void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nn
                        val, nnz, sign);
 }
 
+// ---------------------------------------------------------------------------
+// wire form of a message: fp32 values, then per tensor its local indices bit-packed
+// ---------------------------------------------------------------------------
+
+// Last tensor whose `field` (ascending over the tensors) is <= x.
+template <uint32_t PlanEntry::*FIELD>
+__device__ __forceinline__ uint32_t plan_search(const PlanEntry *plan, uint32_t J, uint32_t x)
+{
+    uint32_t lo = 0, hi = J;                 // invariant: plan[lo].FIELD <= x, answer in [lo, hi)
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (plan[mid].*FIELD <= x) lo = mid; else hi = mid;
+    }
+    return lo;                               // offsets increase strictly: every tensor has k_j >= 1
+}
+
+// One thread per value (copied) and per 32-bit word of the index area: the word gathers the
+// pieces of the entries that overlap it (entry e of tensor j covers bits [e b_j, (e + 1) b_j)
+// of the tensor's block).  Out-of-tensor indices are masked to b_j bits and, with `flag`, reported.
+__global__ __launch_bounds__(256) void k_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J,
+                                                   uint32_t K, uint32_t words, const uint32_t *idx,
+                                                   const float *val, uint32_t *wire, uint32_t *flag)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t < K) {
+        wire[t] = __float_as_uint(val[t]);
+        return;
+    }
+    if (t >= (uint64_t)K + words) return;
+    const uint32_t w = (uint32_t)(t - K);
+    const uint32_t j = plan_search<&PlanEntry::wire_off>(plan, J, w);
+    const PlanEntry pe = plan[j];
+    const TensorDesc td = tdesc[j];
+    const uint32_t b = pe.wire_bits;
+    const uint64_t bit0 = (uint64_t)(w - pe.wire_off) * 32u;           // first bit of this word in the block
+    const uint64_t e0 = bit0 / b;
+    if (e0 >= pe.k) { wire[t] = 0; return; }                           // cannot happen: blocks end with their last entry
+    const uint64_t e1 = min((uint64_t)pe.k - 1u, (bit0 + 31u) / b);
+    const uint32_t mask = (b >= 32u) ? 0xFFFFFFFFu : ((1u << b) - 1u);
+    uint32_t word = 0;
+    bool bad = false;
+    for (uint64_t e = e0; e <= e1; ++e) {
+        const uint32_t local = idx[pe.outoff + e] - td.off;
+        bad |= local >= td.n;
+        const uint64_t pos = e * b;
+        const uint32_t piece = local & mask;
+        word |= (pos >= bit0) ? (piece << (uint32_t)(pos - bit0)) : (piece >> (uint32_t)(bit0 - pos));
+    }
+    wire[t] = word;
+    if (bad && flag) atomicOr(flag, 1u);
+}
+
+// One thread per entry: value copied, local index cut out of one or two words of its block.
+__global__ __launch_bounds__(256) void k_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J,
+                                                     uint32_t K, const uint32_t *wire, uint32_t *idx,
+                                                     float *val, uint32_t *flag)
+{
+    const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
+    if (t >= K) return;
+    val[t] = __uint_as_float(wire[t]);
+    const uint32_t j = plan_search<&PlanEntry::outoff>(plan, J, (uint32_t)t);
+    const PlanEntry pe = plan[j];
+    const TensorDesc td = tdesc[j];
+    const uint32_t b = pe.wire_bits;
+    const uint64_t pos = (uint64_t)((uint32_t)t - pe.outoff) * b;
+    const uint32_t *block = wire + K + pe.wire_off;
+    const uint32_t w = (uint32_t)(pos >> 5), sh = (uint32_t)(pos & 31u);
+    uint64_t x = block[w];
+    if (sh + b > 32u) x |= (uint64_t)block[w + 1] << 32;              // an entry that crosses ends inside the block
+    const uint32_t mask = (b >= 32u) ? 0xFFFFFFFFu : ((1u << b) - 1u);
+    const uint32_t local = (uint32_t)(x >> sh) & mask;
+    idx[t] = td.off + local;
+    if (local >= td.n && flag) atomicOr(flag, 1u);
+}
+
+void launch_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K, uint32_t words,
+                      const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag, void *stream,
+                      void *ev0, void *ev1)
+{
+    const uint64_t threads = (uint64_t)K + words;
+    if (threads == 0) return;
+    launch_k(k_wire_pack, dim3((uint32_t)((threads + 255) / 256)), dim3(256), (hipStream_t)stream, ev0, ev1,
+             tdesc, plan, J, K, words, idx, val, wire, flag);
+}
+
+void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K,
+                        const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag, void *stream,
+                        void *ev0, void *ev1)
+{
+    if (K == 0) return;
+    launch_k(k_wire_unpack, dim3((K + 255) / 256), dim3(256), (hipStream_t)stream, ev0, ev1, tdesc, plan, J, K,
+             wire, idx, val, flag);
+}
+
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *p, uint32_t v, size_t count)
 {
     size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;

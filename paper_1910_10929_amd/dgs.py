@@ -20,13 +20,14 @@ DGS_EINVAL, DGS_ENOMEM, DGS_ENOTSUP, DGS_ECAPACITY, DGS_EHIP = -1, -2, -3, -4, -
 OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS, OPT_SEGMENTED, OPT_REPAIR_ROUND = 1, 2, 3, 4, 5, 6, 7
 SEG_AUTO, SEG_ALWAYS, SEG_NEVER = 0, 1, 2
 (PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA,
- PROF_WORKER_SEGMENTED, PROF_PULL_SEGMENTED) = range(8)
+ PROF_WORKER_SEGMENTED, PROF_PULL_SEGMENTED, PROF_ENCODE, PROF_DECODE) = range(10)
 
 EXPORTS = [
     "dgs_workspace_bytes", "dgs_create", "dgs_destroy", "dgs_nnz", "dgs_worker_step",
     "dgs_server_attach", "dgs_server_push", "dgs_server_pull", "dgs_server_pull_all",
     "dgs_apply_sparse", "dgs_set_option", "dgs_get_stats", "dgs_profile_read", "dgs_strerror",
     "dgs_server_attach_sent", "dgs_server_push_model", "dgs_server_pull_sent",
+    "dgs_wire_bytes", "dgs_encode", "dgs_decode",
 ]
 
 
@@ -69,6 +70,9 @@ def lib():
         L.dgs_server_pull.argtypes = [_vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
         L.dgs_server_pull_all.argtypes = [_vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64, _u64p]
         L.dgs_apply_sparse.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_uint64, ctypes.c_float]
+        L.dgs_wire_bytes.argtypes = [_vp, ctypes.c_double, _u64p]
+        L.dgs_encode.argtypes = [_vp, ctypes.c_double, _vp, _vp, _vp]
+        L.dgs_decode.argtypes = [_vp, ctypes.c_double, _vp, _vp, _vp]
         L.dgs_server_attach_sent.argtypes = [_vp, _vp]
         L.dgs_server_push_model.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_uint64]
         L.dgs_server_pull_sent.argtypes = [_vp, _vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
@@ -233,3 +237,24 @@ class Context:
     def apply_sparse(self, dst, idx, val, nnz: int, sign: float = 1.0) -> None:
         _check(lib().dgs_apply_sparse(self._h, _ptr(dst), _ptr(idx), _ptr(val), nnz, sign),
                "dgs_apply_sparse")
+
+    # -- wire form of a message ---------------------------------------------------
+
+    def wire_bytes(self, density: float) -> int:
+        out = ctypes.c_uint64(0)
+        _check(lib().dgs_wire_bytes(self._h, float(density), ctypes.byref(out)), "dgs_wire_bytes")
+        return int(out.value)
+
+    def encode(self, density: float, idx, val, wire) -> None:
+        """idx, val: the message of `density` (K entries); wire: uint8 device tensor of wire_bytes(density)."""
+        K = self.nnz(density)
+        if idx.numel() < K or val.numel() < K or wire.numel() * wire.element_size() < self.wire_bytes(density):
+            raise DgsError(DGS_ECAPACITY, "dgs_encode: buffers shorter than the message")
+        _check(lib().dgs_encode(self._h, float(density), _ptr(idx), _ptr(val), _ptr(wire)), "dgs_encode")
+
+    def decode(self, density: float, wire, idx_out, val_out) -> None:
+        K = self.nnz(density)
+        if (idx_out.numel() < K or val_out.numel() < K
+                or wire.numel() * wire.element_size() < self.wire_bytes(density)):
+            raise DgsError(DGS_ECAPACITY, "dgs_decode: buffers shorter than the message")
+        _check(lib().dgs_decode(self._h, float(density), _ptr(wire), _ptr(idx_out), _ptr(val_out)), "dgs_decode")
