@@ -336,6 +336,33 @@ int dgs_oracle_server_pull_all(float *diff_k, uint64_t n, uint32_t *idx, float *
     return ORACLE_OK;
 }
 
+/*
+ * The same on the state Algorithm 2 prints (global model and sent_k = theta_0 + v_k):
+ * G = M - v_k (Eq. 3, one fp32 subtraction per element), every entry with a nonzero
+ * magnitude key is sent, then v_k <- v_k + G on those (Eq. 6).  In fp32 v_k + (M - v_k)
+ * need not reproduce M bit for bit; the printed update is what is computed.
+ */
+int dgs_oracle_server_pull_all_sent(const float *model, float *sent_k, uint64_t n, uint32_t *idx,
+                                    float *val, uint64_t capacity, uint64_t *nnz)
+{
+    uint64_t i, o = 0;
+    for (i = 0; i < n; ++i)
+        if (mag_key(model[i] - sent_k[i]) != 0) ++o;
+    if (o > capacity) { *nnz = o; return ORACLE_EINVAL; }
+    o = 0;
+    for (i = 0; i < n; ++i) {
+        float g = model[i] - sent_k[i];
+        if (mag_key(g) != 0) {
+            idx[o] = (uint32_t)i;
+            val[o] = g;
+            ++o;
+            sent_k[i] = sent_k[i] + g;
+        }
+    }
+    *nnz = o;
+    return ORACLE_OK;
+}
+
 /* Worker applies a decoded message: theta[idx] += sign * val (Eq. 5 with sign = +1). */
 int dgs_oracle_apply_sparse(float *dst, uint64_t n, const uint32_t *idx, const float *val,
                             uint64_t nnz, float sign)

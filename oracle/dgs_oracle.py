@@ -58,6 +58,8 @@ def lib():
                                                    ctypes.c_uint64]
         L.dgs_oracle_server_pull_sent.argtypes = [_c_f32p, _c_f32p, _c_u64p, ctypes.c_uint32,
                                                   ctypes.c_double, _c_u32p, _c_f32p, _c_u64p]
+        L.dgs_oracle_server_pull_all_sent.argtypes = [_c_f32p, _c_f32p, ctypes.c_uint64, _c_u32p, _c_f32p,
+                                                      ctypes.c_uint64, _c_u64p]
         _c_u8p = ctypes.POINTER(ctypes.c_uint8)
         L.dgs_oracle_wire_bytes.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u64p]
         L.dgs_oracle_encode.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u32p, _c_f32p, _c_u8p]
@@ -179,6 +181,18 @@ def server_pull_all(diff: np.ndarray, k: int, capacity: int | None = None):
     out = ctypes.c_uint64(0)
     _check(lib().dgs_oracle_server_pull_all(_f32(row), n, _u32(idx), _f32(val), cap,
                                             ctypes.byref(out)), "server_pull_all")
+    return idx[:out.value].copy(), val[:out.value].copy()
+
+
+def server_pull_all_sent(model: np.ndarray, sent: np.ndarray, k: int, capacity: int | None = None):
+    row = sent[k]
+    n = row.size
+    cap = n if capacity is None else capacity
+    idx = np.zeros(cap, dtype=np.uint32)
+    val = np.zeros(cap, dtype=np.float32)
+    out = ctypes.c_uint64(0)
+    _check(lib().dgs_oracle_server_pull_all_sent(_f32(model), _f32(row), n, _u32(idx), _f32(val), cap,
+                                                 ctypes.byref(out)), "server_pull_all_sent")
     return idx[:out.value].copy(), val[:out.value].copy()
 
 

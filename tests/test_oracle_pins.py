@@ -467,6 +467,47 @@ def test_printed_server_form_against_literal_algorithm_2(oracle):
         assert np.array_equal(sent[w], model_s)
 
 
+def test_printed_server_form_without_secondary_compression(oracle):
+    """Algorithm 2 with the compression switch off on the printed state: G = M - v_k whole
+    (Eq. 3), v_k += G (Eq. 6).  Against the dense numpy statement on Gaussian data (bits),
+    against the difference-row form on integer data (both exact), and v_k == M afterwards."""
+    rng = np.random.default_rng(16)
+    n, W = 3000, 3
+    off = synth.layout_flat(n)
+    order = synth.event_schedule(W, 20, 17)
+    model = rng.standard_normal(n).astype(np.float32)
+    sent = np.tile(model, (W, 1))
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = synth.sparse_payload(off, [40], None, rng)
+        oracle.server_push_model(model, idx, val)
+        G = model - sent[k]                                    # dense, fp32
+        nz = np.nonzero(key_of(G))[0]
+        want_sent = sent[k].copy()
+        want_sent[nz] = want_sent[nz] + G[nz]
+        gi, gv = oracle.server_pull_all_sent(model, sent, k)
+        assert np.array_equal(gi, nz.astype(np.uint32)), e
+        assert np.array_equal(bits(gv), bits(G[nz])), e
+        assert np.array_equal(bits(sent[k]), bits(want_sent)), e
+    theta0 = rng.integers(-5, 6, size=n).astype(np.float32)
+    model_d, model_s = theta0.copy(), theta0.copy()
+    diff = np.zeros((W, n), np.float32)
+    sent = np.tile(theta0, (W, 1))
+    for e, k in enumerate(order):
+        k = int(k)
+        idx, val = synth.sparse_payload(off, [40], None, rng)
+        val = np.round(val * 4).astype(np.float32)
+        oracle.server_push(model_d, diff, idx, val)
+        oracle.server_push_model(model_s, idx, val)
+        di, dv = oracle.server_pull_all(diff, k)
+        si, sv = oracle.server_pull_all_sent(model_s, sent, k)
+        assert np.array_equal(di, si) and np.array_equal(dv, sv), e
+        assert np.array_equal(sent[k], model_s)
+    with pytest.raises(Exception):                              # capacity
+        oracle.server_push_model(model_s, np.array([1, 2, 3], np.uint32), np.ones(3, np.float32))
+        oracle.server_pull_all_sent(model_s, sent, 0, capacity=2)
+
+
 def test_double_pull_returns_next_k(oracle):
     rng = np.random.default_rng(13)
     off = synth.offsets_from_sizes([1000, 500])
