@@ -216,6 +216,10 @@ int dgs_server_pull_sent(dgs_ctx *ctx, const float *model, uint32_t worker_id, d
  */
 int dgs_server_pull_all(dgs_ctx *ctx, uint32_t worker_id, uint32_t *idx_out, float *val_out,
                         uint64_t capacity, uint64_t *nnz_out /*host*/);
+/* The same on the printed state (after dgs_server_attach_sent): G = every nonzero of
+ * model - sent_k (Eq. 3), then sent_k += G on those (Eq. 6). */
+int dgs_server_pull_all_sent(dgs_ctx *ctx, const float *model, uint32_t worker_id, uint32_t *idx_out,
+                             float *val_out, uint64_t capacity, uint64_t *nnz_out /*host*/);
 
 /*
  * Worker applies a decoded message (Algorithm 1/3, "theta <- SGD(theta,

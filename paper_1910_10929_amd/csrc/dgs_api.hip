@@ -705,25 +705,44 @@ int dgs_server_pull_sent(dgs_ctx *c, const float *model, uint32_t worker_id, dou
                          val_out, nnz_out, DGS_PROF_PULL_STREAM, DGS_PROF_PULL_SELECT, DGS_PROF_PULL_SEGMENTED);
 }
 
-int dgs_server_pull_all(dgs_ctx *c, uint32_t worker_id, uint32_t *idx_out, float *val_out,
-                        uint64_t capacity, uint64_t *nnz_out)
+namespace {
+
+// Every nonzero of `row` (model == nullptr) or of model - row; waits for the count.
+int pull_all(dgs_ctx *c, float *row, const float *model, uint32_t *idx_out, float *val_out, uint64_t capacity,
+             uint64_t *nnz_out)
 {
-    if (!c || !c->diff || !nnz_out) return DGS_EINVAL;
-    if (worker_id >= c->W) return DGS_EINVAL;
-    if (capacity && (!idx_out || !val_out)) return DGS_EINVAL;
-    float *row = c->diff + (size_t)worker_id * c->n;
     uint32_t *total = c->flag + 4;
-    launch_pull_all_count(row, c->n, c->ntiles, c->tile_cnt, c->stream);
+    launch_pull_all_count(row, model, c->n, c->ntiles, c->tile_cnt, c->stream);
     launch_pull_all_scan(c->tile_cnt, c->ntiles, total, c->stream);
     uint32_t cnt = 0;
     if (hipMemcpyAsync(&cnt, total, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
     if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
     *nnz_out = cnt;
     if (cnt > capacity) return DGS_ECAPACITY;
-    if (cnt) launch_pull_all_emit(row, c->n, c->ntiles, c->tile_cnt, idx_out, val_out, c->stream);
+    if (cnt) launch_pull_all_emit(row, model, c->n, c->ntiles, c->tile_cnt, idx_out, val_out, c->stream);
     ++c->calls_pull;
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;
+}
+
+}  // namespace
+
+int dgs_server_pull_all(dgs_ctx *c, uint32_t worker_id, uint32_t *idx_out, float *val_out,
+                        uint64_t capacity, uint64_t *nnz_out)
+{
+    if (!c || !c->diff || !nnz_out) return DGS_EINVAL;
+    if (worker_id >= c->W) return DGS_EINVAL;
+    if (capacity && (!idx_out || !val_out)) return DGS_EINVAL;
+    return pull_all(c, c->diff + (size_t)worker_id * c->n, nullptr, idx_out, val_out, capacity, nnz_out);
+}
+
+int dgs_server_pull_all_sent(dgs_ctx *c, const float *model, uint32_t worker_id, uint32_t *idx_out,
+                             float *val_out, uint64_t capacity, uint64_t *nnz_out)
+{
+    if (!c || !c->sent || !model || !nnz_out) return DGS_EINVAL;
+    if (worker_id >= c->W || !aligned4(model)) return DGS_EINVAL;
+    if (capacity && (!idx_out || !val_out)) return DGS_EINVAL;
+    return pull_all(c, c->sent + (size_t)worker_id * c->n, model, idx_out, val_out, capacity, nnz_out);
 }
 
 int dgs_apply_sparse(dgs_ctx *c, float *dst, const uint32_t *idx, const float *val, uint64_t nnz, float sign)

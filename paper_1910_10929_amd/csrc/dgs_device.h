@@ -207,9 +207,10 @@ void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t
 void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream);
 void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream);
-void launch_pull_all_count(const float *row, uint32_t n, uint32_t ntiles, uint32_t *tile_cnt, void *stream);
+void launch_pull_all_count(const float *row, const float *model, uint32_t n, uint32_t ntiles,
+                           uint32_t *tile_cnt, void *stream);
 void launch_pull_all_scan(uint32_t *tile_cnt, uint32_t ntiles, uint32_t *total, void *stream);
-void launch_pull_all_emit(float *row, uint32_t n, uint32_t ntiles, const uint32_t *tile_pos,
-                          uint32_t *out_idx, float *out_val, void *stream);
+void launch_pull_all_emit(float *row, const float *model, uint32_t n, uint32_t ntiles,
+                          const uint32_t *tile_pos, uint32_t *out_idx, float *out_val, void *stream);
 
 }  // namespace dgs

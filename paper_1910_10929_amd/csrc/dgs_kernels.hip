@@ -2004,11 +2004,12 @@ void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream)
 }
 
 // ---------------------------------------------------------------------------
-// pull without secondary compression: every nonzero of one difference row
+// pull without secondary compression: every nonzero of one difference row, or of
+// model - sent_k when a model is given (the server state as Algorithm 2 prints it)
 // ---------------------------------------------------------------------------
 
-__device__ __forceinline__ void load_tile_guarded(const float *row, uint32_t base, uint32_t n,
-                                                  float (&a)[4][4])
+__device__ __forceinline__ void load_tile_guarded(const float *row, const float *model, uint32_t base,
+                                                  uint32_t n, float (&a)[4][4])
 {
     const uint32_t lane = lane_id();
 #pragma unroll
@@ -2016,17 +2017,18 @@ __device__ __forceinline__ void load_tile_guarded(const float *row, uint32_t bas
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const uint32_t e = base + r * 256 + lane * 4 + j;
-            a[r][j] = (e < n) ? row[e] : 0.0f;
+            a[r][j] = (e < n) ? (model ? model[e] - row[e] : row[e]) : 0.0f;
         }
 }
 
-__global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_count(const float *row, uint32_t n,
-                                                                   uint32_t ntiles, uint32_t *tile_cnt)
+__global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_count(const float *row, const float *model,
+                                                                   uint32_t n, uint32_t ntiles,
+                                                                   uint32_t *tile_cnt)
 {
     const uint32_t t = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
     if (t >= ntiles) return;
     float a[4][4];
-    load_tile_guarded(row, t * TILE, n, a);
+    load_tile_guarded(row, model, t * TILE, n, a);
     uint32_t cnt = 0;
 #pragma unroll
     for (int r = 0; r < 4; ++r)
@@ -2054,8 +2056,9 @@ __global__ __launch_bounds__(1024) void k_pull_all_scan(uint32_t *tile_cnt, uint
     if (threadIdx.x == 0) *total = tot;
 }
 
-__global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, uint32_t n, uint32_t ntiles,
-                                                                  const uint32_t *tile_pos,
+// What is sent leaves the row as +0 (D_k -= G), or is added to it (sent_k += G, Eq. 6).
+__global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, const float *model, uint32_t n,
+                                                                  uint32_t ntiles, const uint32_t *tile_pos,
                                                                   uint32_t *out_idx, float *out_val)
 {
     const uint32_t t = blockIdx.x * WAVES_PER_BLOCK + (threadIdx.x >> 6);
@@ -2063,7 +2066,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, ui
     const uint32_t lane = lane_id();
     const uint32_t base = t * TILE;
     float a[4][4];
-    load_tile_guarded(row, base, n, a);
+    load_tile_guarded(row, model, base, n, a);
     uint32_t run = tile_pos[t];
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
@@ -2082,7 +2085,7 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, ui
                     const uint32_t e = base + r * 256 + lane * 4 + j;
                     out_idx[p] = e;
                     out_val[p] = a[r][j];
-                    store_scattered(&row[e], 0.0f);
+                    store_scattered(&row[e], model ? row[e] + a[r][j] : 0.0f);
                     ++p;
                 }
             }
@@ -2091,10 +2094,11 @@ __global__ __launch_bounds__(STREAM_THREADS) void k_pull_all_emit(float *row, ui
     }
 }
 
-void launch_pull_all_count(const float *row, uint32_t n, uint32_t ntiles, uint32_t *tile_cnt, void *stream)
+void launch_pull_all_count(const float *row, const float *model, uint32_t n, uint32_t ntiles,
+                           uint32_t *tile_cnt, void *stream)
 {
     hipLaunchKernelGGL(k_pull_all_count, dim3((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK),
-                       dim3(STREAM_THREADS), 0, (hipStream_t)stream, row, n, ntiles, tile_cnt);
+                       dim3(STREAM_THREADS), 0, (hipStream_t)stream, row, model, n, ntiles, tile_cnt);
 }
 
 void launch_pull_all_scan(uint32_t *tile_cnt, uint32_t ntiles, uint32_t *total, void *stream)
@@ -2102,11 +2106,11 @@ void launch_pull_all_scan(uint32_t *tile_cnt, uint32_t ntiles, uint32_t *total, 
     hipLaunchKernelGGL(k_pull_all_scan, dim3(1), dim3(1024), 0, (hipStream_t)stream, tile_cnt, ntiles, total);
 }
 
-void launch_pull_all_emit(float *row, uint32_t n, uint32_t ntiles, const uint32_t *tile_pos,
-                          uint32_t *out_idx, float *out_val, void *stream)
+void launch_pull_all_emit(float *row, const float *model, uint32_t n, uint32_t ntiles,
+                          const uint32_t *tile_pos, uint32_t *out_idx, float *out_val, void *stream)
 {
     hipLaunchKernelGGL(k_pull_all_emit, dim3((ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK),
-                       dim3(STREAM_THREADS), 0, (hipStream_t)stream, row, n, ntiles, tile_pos, out_idx,
+                       dim3(STREAM_THREADS), 0, (hipStream_t)stream, row, model, n, ntiles, tile_pos, out_idx,
                        out_val);
 }
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "dgs_server_attach", "dgs_server_push", "dgs_server_pull", "dgs_server_pull_all",
     "dgs_apply_sparse", "dgs_set_option", "dgs_get_stats", "dgs_profile_read", "dgs_strerror",
     "dgs_server_attach_sent", "dgs_server_push_model", "dgs_server_pull_sent",
-    "dgs_wire_bytes", "dgs_encode", "dgs_decode",
+    "dgs_wire_bytes", "dgs_encode", "dgs_decode", "dgs_server_pull_all_sent",
 ]
 
 
@@ -69,6 +69,7 @@ def lib():
         L.dgs_server_push.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64]
         L.dgs_server_pull.argtypes = [_vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
         L.dgs_server_pull_all.argtypes = [_vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64, _u64p]
+        L.dgs_server_pull_all_sent.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64, _u64p]
         L.dgs_apply_sparse.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_uint64, ctypes.c_float]
         L.dgs_wire_bytes.argtypes = [_vp, ctypes.c_double, _u64p]
         L.dgs_encode.argtypes = [_vp, ctypes.c_double, _vp, _vp, _vp]
@@ -232,6 +233,15 @@ class Context:
         if rc == DGS_ECAPACITY:
             raise DgsError(rc, f"dgs_server_pull_all needs capacity {K.value}")
         _check(rc, "dgs_server_pull_all")
+        return int(K.value)
+
+    def server_pull_all_sent(self, model, worker_id: int, idx_out, val_out, capacity: int) -> int:
+        K = ctypes.c_uint64(0)
+        rc = lib().dgs_server_pull_all_sent(self._h, _ptr(model), worker_id, _ptr(idx_out), _ptr(val_out),
+                                            capacity, ctypes.byref(K))
+        if rc == DGS_ECAPACITY:
+            raise DgsError(rc, f"dgs_server_pull_all_sent needs capacity {K.value}")
+        _check(rc, "dgs_server_pull_all_sent")
         return int(K.value)
 
     def apply_sparse(self, dst, idx, val, nnz: int, sign: float = 1.0) -> None:

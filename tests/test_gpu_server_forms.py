@@ -90,6 +90,48 @@ def test_printed_form_full_size_resnet50_shapes(oracle):
     assert st.exact_calls <= 8
 
 
+def test_printed_form_without_secondary_compression(oracle):
+    """dgs_server_pull_all_sent: every nonzero of model - sent_k, sent_k += G; a ragged layout
+    whose last tile is partial, pulls that find nothing, and the capacity error."""
+    import torch
+    off = synth.offsets_from_sizes([70_001, 64, 9408, 5])
+    n = int(off[-1])
+    W = 3
+    rng = np.random.default_rng(70)
+    scales = synth.tensor_scales(len(off) - 1, 71)
+    kj, _ = oracle.nnz(off, 0.004)
+    model0 = synth.gaussian(n, rng)
+    ctx = dgs.Context(off, W=W)
+    srv = SentServer(ctx, model0)
+    cap = 4 * int(sum(kj)) + 8
+    oi = torch.zeros(cap, dtype=torch.int32, device=ctx.device)
+    ov = torch.zeros(cap, dtype=torch.float32, device=ctx.device)
+    model_ref = model0.copy()
+    sent_ref = np.tile(model0, (W, 1))
+    for e, k in enumerate((0, 1, 0, 0, 2, 1, 1)):
+        if e != 3:                                   # event 3: a pull with nothing new
+            idx, val = synth.sparse_payload(off, kj, scales, rng)
+            oracle.server_push_model(model_ref, idx, val)
+            srv.push(idx, val)
+        wi, wv = oracle.server_pull_all_sent(model_ref, sent_ref, k)
+        K = ctx.server_pull_all_sent(srv.model, k, oi, ov, cap)
+        torch.cuda.synchronize()
+        assert K == wi.size, f"event {e}"
+        assert np.array_equal(to_host_u32(oi[:K]), wi), f"event {e}"
+        assert np.array_equal(ov[:K].cpu().numpy().view(np.uint32), wv.view(np.uint32)), f"event {e}"
+    assert_state_match(srv.sent.cpu().numpy().ravel(), sent_ref.ravel(), "sent")
+    idx, val = synth.sparse_payload(off, kj, scales, rng)
+    srv.push(idx, val)
+    before = srv.sent.clone()
+    with pytest.raises(dgs.DgsError) as err:
+        ctx.server_pull_all_sent(srv.model, 2, oi, ov, 10)
+    assert err.value.code == dgs.DGS_ECAPACITY
+    torch.cuda.synchronize()
+    assert torch.equal(before, srv.sent)             # nothing was modified
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
+
+
 def test_printed_form_argument_errors():
     import torch
     off = synth.offsets_from_sizes([5000, 20])
