@@ -1,0 +1,150 @@
+// Wavefront and workgroup helpers shared by the gfx950 (CDNA4, wave64) kernels of libdgs:
+// lane primitives, DPP scans, workgroup scans, rank search in an LDS histogram, and the
+// kernel launch wrapper that can stamp a dispatch into HIP events.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
+#include "dgs_device.h"
+
+namespace dgs {
+
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ uint32_t lane_id() { return threadIdx.x & 63u; }
+
+__device__ __forceinline__ uint32_t mbcnt64(uint64_t mask)
+{
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(mask >> 32),
+                                     __builtin_amdgcn_mbcnt_lo((uint32_t)mask, 0u));
+}
+
+__device__ __forceinline__ uint64_t ballot64(bool p) { return __builtin_amdgcn_ballot_w64(p); }
+
+__device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgcn_readfirstlane(v); }
+
+// Isolated 4-byte store into a large buffer that a later streaming pass will sweep
+// (state fix-ups, pull zero-writes, the push scatter).  Non-temporal: plain stores
+// leave partially written lines behind in the cache hierarchy, and 1e5 of them were
+// measured to slow the NEXT streaming pass over a 4 GB buffer by 130 us (6 %);
+// non-temporal ones by 15 us.
+__device__ __forceinline__ void store_scattered(float *p, float v) { __builtin_nontemporal_store(v, p); }
+
+// Plain launch, or a launch whose begin and / or end is stamped into an event.
+template <class K, class... Args>
+static void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t st, void *ev0, void *ev1, Args... args)
+{
+    if (ev0 || ev1)
+        hipExtLaunchKernelGGL(kernel, grid, block, 0, st, (hipEvent_t)ev0, (hipEvent_t)ev1, 0, args...);
+    else
+        hipLaunchKernelGGL(kernel, grid, block, 0, st, args...);
+}
+
+// ---------------------------------------------------------------------------
+// workgroup helpers for pick / select
+// ---------------------------------------------------------------------------
+
+// Inclusive prefix sum over the 64 lanes of a wavefront, in registers (DPP):
+// four shifts inside each row of 16 lanes, then two row broadcasts.
+__device__ __forceinline__ uint32_t wave_incl_scan(uint32_t v)
+{
+    int x = (int)v;
+    x += __builtin_amdgcn_update_dpp(0, x, 0x111, 0xf, 0xf, false);   // row_shr:1
+    x += __builtin_amdgcn_update_dpp(0, x, 0x112, 0xf, 0xf, false);   // row_shr:2
+    x += __builtin_amdgcn_update_dpp(0, x, 0x114, 0xf, 0xf, false);   // row_shr:4
+    x += __builtin_amdgcn_update_dpp(0, x, 0x118, 0xf, 0xf, false);   // row_shr:8
+    x += __builtin_amdgcn_update_dpp(0, x, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1, 3
+    x += __builtin_amdgcn_update_dpp(0, x, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2, 3
+    return (uint32_t)x;
+}
+
+__device__ __forceinline__ uint32_t wave_sum(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_readlane((int)wave_incl_scan(v), 63);
+}
+
+// Exclusive scan over the workgroup in thread order; `total` is the workgroup sum.
+// wsum: LDS scratch of NW words.  Contains two barriers.
+template <int NW>
+__device__ __forceinline__ uint32_t block_excl_scan(uint32_t v, uint32_t *wsum, uint32_t &total)
+{
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t incl = wave_incl_scan(v);
+    __syncthreads();
+    if (lane_id() == 63) wsum[wave] = incl;
+    __syncthreads();
+    uint32_t before = 0, tot = 0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) {
+        const uint32_t x = wsum[w];
+        if ((uint32_t)w < wave) before += x;
+        tot += x;
+    }
+    total = tot;
+    return before + incl - v;
+}
+
+// Workgroup sum.  wsum: LDS scratch of nw words.  Contains two barriers.
+__device__ __forceinline__ uint32_t block_sum(uint32_t v, uint32_t *wsum, int nw)
+{
+    const uint32_t s = wave_sum(v);
+    __syncthreads();
+    if (lane_id() == 0) wsum[threadIdx.x >> 6] = s;
+    __syncthreads();
+    uint32_t tot = 0;
+    for (int w = 0; w < nw; ++w) tot += wsum[w];
+    return tot;
+}
+
+// In an LDS histogram h[NB] (NB a multiple of 64, at most 4096), find for each of
+// three ranks R[0..2] (counted from the top bin, >= 1) the bin holding it and the
+// rank inside that bin:  res[2 i] = bin, res[2 i + 1] = rank in the bin; bin -1 if the
+// rank exceeds the histogram total (or is 0).  Every wavefront sums rows of 64 bins,
+// then up to three wavefronts each scan the row sums and the row their rank lands in.
+// Barriers: one on entry (h complete), one in the middle, one on exit.
+template <int NB, int NW>
+__device__ __forceinline__ void find_ranks(const uint32_t *h, uint32_t R0, uint32_t R1, uint32_t R2,
+                                           uint32_t *rowsum, int *res)
+{
+    constexpr int ROWS = NB / 64;
+    constexpr int SEARCHERS = NW < 3 ? NW : 3;
+    static_assert(ROWS * 64 == NB && ROWS <= 64, "histogram shape");
+    const uint32_t lane = lane_id();
+    const uint32_t wave = threadIdx.x >> 6;
+    __syncthreads();
+    for (int r = (int)wave; r < ROWS; r += NW) {
+        const uint32_t s = wave_sum(h[r * 64 + lane]);
+        if (lane == 0) rowsum[r] = s;
+    }
+    __syncthreads();
+    if (wave < (uint32_t)SEARCHERS) {
+        // lane l looks at row ROWS-1-l: the top row first
+        const uint32_t rs = (lane < (uint32_t)ROWS) ? rowsum[ROWS - 1 - lane] : 0u;
+        const uint32_t rincl = wave_incl_scan(rs);
+        for (int which = (int)wave; which < 3; which += SEARCHERS) {
+            const uint32_t R = which == 0 ? R0 : (which == 1 ? R1 : R2);
+            int bin = -1;
+            uint32_t rin = 0;
+            const uint64_t hit = ballot64(lane < (uint32_t)ROWS && rincl >= R);
+            if (hit != 0 && R != 0) {
+                const int rl = __ffsll((unsigned long long)hit) - 1;          // first row reaching R
+                const uint32_t above = (uint32_t)__builtin_amdgcn_readlane((int)(rincl - rs), rl);
+                const int row = ROWS - 1 - rl;
+                const uint32_t Rr = R - above;                                 // rank inside the row
+                const uint32_t v = h[row * 64 + (63 - lane)];                  // top bin first
+                const uint32_t vincl = wave_incl_scan(v);
+                const uint64_t hit2 = ballot64(vincl >= Rr);
+                const int bl = __ffsll((unsigned long long)hit2) - 1;
+                const uint32_t above2 = (uint32_t)__builtin_amdgcn_readlane((int)(vincl - v), bl);
+                bin = row * 64 + 63 - bl;
+                rin = Rr - above2;
+            }
+            if (lane == 0) {
+                res[2 * which] = bin;
+                res[2 * which + 1] = (int)rin;
+            }
+        }
+    }
+    __syncthreads();
+}
+
+}  // namespace dgs
