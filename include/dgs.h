@@ -140,6 +140,15 @@ int dgs_nnz(const dgs_ctx *ctx, double density, uint64_t *K_out /*host*/);
  * schemes) is not part of this method: DGS_ENOTSUP.
  *
  * Buffers must be 4-byte aligned; 16-byte alignment gives the fast path.
+ *
+ * Graph capture.  Once a call at `density` has been made eagerly on this context (the
+ * launch plan of a density is uploaded on its first use, and the first call of a stream
+ * takes the two-pass path), dgs_worker_step, dgs_server_push / dgs_server_push_model
+ * (without DGS_OPT_VALIDATE) and dgs_server_pull / dgs_server_pull_sent enqueue kernels only
+ * -- no memset or copy nodes, no host wait -- and may be captured into a HIP graph on the
+ * context's stream.  The choice between the predicted and the two-pass path is taken on
+ * the host when the call is made, i.e. at capture time; everything a failed prediction
+ * needs afterwards runs on the device, so replays stay exact.
  */
 int dgs_worker_step(dgs_ctx *ctx, const float *grad, float *momentum, float *residual,
                     float lr, float m, double density,
