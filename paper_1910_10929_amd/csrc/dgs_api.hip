@@ -174,49 +174,56 @@ struct ProfSlot {
 };
 
 // k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
+// Which tensors take the segmented chain: its launches cost about 55 us whatever it is given,
+// and one workgroup copes with a candidate list of up to one and a half times its LDS list (the
+// rest lives in global scratch) in less than that.  So a tensor goes segmented by itself only if it is very
+// large or its list would exceed that; once the chain runs anyway, every capable tensor whose
+// list outgrows LDS joins it.
 void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out,
                uint32_t *nseg_active, uint64_t *wire_words_out)
 {
-    uint64_t K = 0, words = 0;
-    uint32_t active = 0;
-    for (uint32_t j = 0; j < c->J; ++j) {
-        const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
-        uint64_t k = (uint64_t)std::ceil(density * (double)nj);
-        if (k < 1) k = 1;
-        if (k > nj) k = nj;
-        uint64_t k2 = k + (k * (uint64_t)margin_pct) / 100 + 4ull * isqrt_u32((uint32_t)k) + 16;
-        if (k2 > nj) k2 = nj;
-        out[j].k = (uint32_t)k;
-        out[j].k2 = (uint32_t)k2;
-        out[j].outoff = (uint32_t)K;
-        uint64_t k2p = 2 * k + 4ull * isqrt_u32((uint32_t)k) + 16;
-        if (k2p > nj) k2p = nj;
-        out[j].k2_pull = (uint32_t)k2p;
-        // segmented selection: always for very large tensors, and whenever the candidate
-        // list would not fit the single workgroup's LDS list
-        bool seg = false;
-        if (c->nseg[j] != 0 && c->seg_mode != SEG_MODE_NEVER) {
-            if (density > DENSE_DENSITY)
-                seg = true;   // dense request: the chain reads the tensor itself, one workgroup would crawl
-            else
-                seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
-                      (k2 > k2p ? k2 : k2p) > SEL_LDS_LIST;
+    auto plan_with = [&](uint64_t list_limit) -> uint32_t {
+        uint64_t K = 0, words = 0;
+        uint32_t active = 0;
+        for (uint32_t j = 0; j < c->J; ++j) {
+            const uint64_t nj = c->offsets[j + 1] - c->offsets[j];
+            uint64_t k = (uint64_t)std::ceil(density * (double)nj);
+            if (k < 1) k = 1;
+            if (k > nj) k = nj;
+            uint64_t k2 = k + (k * (uint64_t)margin_pct) / 100 + 4ull * isqrt_u32((uint32_t)k) + 16;
+            if (k2 > nj) k2 = nj;
+            out[j].k = (uint32_t)k;
+            out[j].k2 = (uint32_t)k2;
+            out[j].outoff = (uint32_t)K;
+            uint64_t k2p = 2 * k + 4ull * isqrt_u32((uint32_t)k) + 16;
+            if (k2p > nj) k2p = nj;
+            out[j].k2_pull = (uint32_t)k2p;
+            bool seg = false;
+            if (c->nseg[j] != 0 && c->seg_mode != SEG_MODE_NEVER) {
+                if (density > DENSE_DENSITY)
+                    seg = true;   // dense request: the chain reads the tensor itself, one workgroup would crawl
+                else
+                    seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
+                          (k2 > k2p ? k2 : k2p) > list_limit;
+            }
+            out[j].seg = seg ? 1u : 0u;
+            // wire form: local indices of b bits each, the tensor's block padded to whole words
+            uint32_t b = 0;
+            for (uint64_t top = nj - 1; top; top >>= 1) ++b;
+            if (b == 0) b = 1;
+            out[j].wire_off = (uint32_t)words;      // fits: words <= K, checked by the caller
+            out[j].wire_bits = b;
+            out[j].pad2 = 0;
+            words += (k * b + 31) / 32;
+            active += seg ? 1u : 0u;
+            K += k;
         }
-        out[j].seg = seg ? 1u : 0u;
-        // wire form: local indices of b bits each, the tensor's block padded to whole words
-        uint32_t b = 0;
-        for (uint64_t top = nj - 1; top; top >>= 1) ++b;
-        if (b == 0) b = 1;
-        out[j].wire_off = (uint32_t)words;      // fits: words <= K, checked by the caller
-        out[j].wire_bits = b;
-        out[j].pad2 = 0;
-        words += (k * b + 31) / 32;
-        active += seg ? 1u : 0u;
-        K += k;
-    }
-    *nseg_active = active;
-    *K_out = K;
-    *wire_words_out = words;
+        *nseg_active = active;
+        *K_out = K;
+        *wire_words_out = words;
+        return active;
+    };
+    if (plan_with(SEL_LDS_LIST + SEL_LDS_LIST / 2) != 0) plan_with(SEL_LDS_LIST);
 }
 
 // Returns the cache slot holding the plan for `density`, uploading it if new.
