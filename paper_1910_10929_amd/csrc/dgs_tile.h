@@ -194,9 +194,14 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
 #pragma unroll
             for (int r = 0; r < 4; ++r) g[r] = *(const f32x4 *)(A.grad + base + r * 256 + lane * 4);
         }
+        // Non-temporal like the gradient: a pass that allocates what it streams in the
+        // last-level cache pushes out the dirty lines earlier kernels left there and waits for
+        // their write-back.  Measured: a cold 433 MB server row takes 131 us with plain loads
+        // and 66 us with non-temporal ones; the worker pass over 1e9 parameters 2255 us against
+        // 2165 us; buffers small enough to stay cached (102 MB) lose nothing.
 #pragma unroll
         for (int r = 0; r < 4; ++r)
-            s[r] = *(const f32x4 *)(A.state + base + r * 256 + lane * 4);
+            s[r] = __builtin_nontemporal_load((const f32x4 *)(A.state + base + r * 256 + lane * 4));
         if (MODE != MODE_PLAIN) d = span_desc(toff, A.J, base, base + TILE - 1u);
 #pragma unroll
         for (int r = 0; r < 4; ++r)
