@@ -196,9 +196,8 @@ def main():
                     help="c3 only: per-worker difference rows (default) or the printed form, "
                          "global model + what each worker has been sent")
     ap.add_argument("--overlap", action="store_true",
-                    help="c4/c5: also time worker and server on two streams (worker step t+1 "
-                         "overlaps push/pull t); reported as an extra field, never as `value`; "
-                         "always on for the default workload c2")
+                    help="c2/c4/c5: also time worker and server on two streams (worker step t+1 "
+                         "overlaps push/pull t); reported as an extra field, never as `value`")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run 20 elementwise copies of one 25,557,032-float tensor and exit "
                          "(known traffic, used to scale the rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
@@ -355,7 +354,7 @@ def main():
                   "segmented_tensors": st.segmented_tensors, "repaired_tensors": st.repaired_tensors,
                   "internal_errors": st.internal_errors},
     }
-    if (args.overlap or name == "c2") and name != "c3":
+    if args.overlap and name != "c3":
         out["overlapped_two_streams"] = overlapped(torch, dgs, off, W, rho, K, g_dev, steps, warmup, n, step_bytes)
     out["cpu_baseline"] = None if args.no_cpu else cpu_baseline(wl, name)
     ctx.close()
