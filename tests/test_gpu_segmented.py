@@ -214,3 +214,32 @@ def test_dense_requests_with_tie_classes(oracle, name):
     g1 = np.concatenate([g_big, tail])
     g2 = np.concatenate([g_big[::-1].copy(), -tail])
     run_worker_parity(oracle, off, [g1, g2, g1], 1.0, np.float32(0.5), 0.1)
+
+
+@pytest.mark.parametrize("option,value", [(dgs.OPT_MARGIN_PCT, 0), (dgs.OPT_MARGIN_PCT, 300),
+                                          (dgs.OPT_STREAM_QUADS, 3), (dgs.OPT_REPAIR_ROUND, 0)])
+@pytest.mark.parametrize("seg_mode", [dgs.SEG_AUTO, dgs.SEG_ALWAYS], ids=["auto", "always"])
+def test_tuning_options_do_not_change_results(oracle, option, value, seg_mode):
+    """Candidate margin, streaming launch shape and the repair round only steer the code path.
+    The gradient scale jumps up and collapses on the way, so thresholds fail and (without the
+    repair round) the dense re-selection has to step in."""
+    off = synth.offsets_from_sizes([400_000, 64, 70_001, 9000])
+    n = int(off[-1])
+    rng = np.random.default_rng(57)
+    g = [synth.gaussian(n, rng) for _ in range(6)]
+    grads = [g[0], g[1], g[2] * np.float32(1e3), g[3] * np.float32(1e-6), g[4], g[5]]
+    ctx = dgs.Context(off, W=0)
+    ctx.set_option(option, value)
+    ctx.set_option(dgs.OPT_SEGMENTED, seg_mode)
+    w = Worker(ctx, density_max=0.002)
+    s_ref = np.zeros(n, np.float32)
+    for t, gg in enumerate(grads):
+        wi, wv = oracle.worker_step(gg, s_ref, off, 1.0, np.float32(0.5), 0.002)
+        gi, gv = w.step(gg, 1.0, 0.5, 0.002)
+        assert_pairs_match(gi, gv, wi, wv, f"step {t}")
+        assert_state_match(w.state_host(), s_ref, f"state {t}")
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    if option == dgs.OPT_REPAIR_ROUND:
+        assert st.repaired_tensors == 0
+    ctx.close()
