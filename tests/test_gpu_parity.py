@@ -344,3 +344,36 @@ def test_repeated_pulls_without_pushes(oracle, torch_mod):
     assert fallbacks[-1] == fallbacks[-3], "later empty pulls must not re-select densely"
     assert ctx.stats().internal_errors == 0
     ctx.close()
+
+
+def test_density_schedule_beyond_the_plan_cache(oracle, torch_mod):
+    """A warm-up style schedule over 12 densities, walked twice (more than the 8 launch plans the
+    context keeps, so plans are evicted and rebuilt), then a few steps at the last one (the
+    prediction takes over again); worker and pull both follow it."""
+    off = synth.offsets_from_sizes(RAGGED_SIZES)
+    n = int(off[-1])
+    scales = synth.tensor_scales(len(RAGGED_SIZES), 30)
+    rng = np.random.default_rng(31)
+    schedule = [0.25, 0.125, 0.0625, 0.04, 0.03, 0.02, 0.01, 0.007, 0.004, 0.002, 0.001, 0.0005]
+    ctx = dgs.Context(off, W=1)
+    w = Worker(ctx, density_max=0.25)
+    srv = Server(ctx, np.zeros(n, np.float32), density_max=0.25)
+    s_ref = np.zeros(n, np.float32)
+    model_ref = np.zeros(n, np.float32)
+    diff_ref = np.zeros((1, n), np.float32)
+    for t, rho in enumerate(schedule + schedule + [schedule[-1]] * 3):
+        g = synth.gaussian_grads(off, scales, rng)
+        wi, wv = oracle.worker_step(g, s_ref, off, np.float32(0.5), np.float32(0.9), rho)
+        gi, gv = w.step(g, 0.5, 0.9, rho)
+        assert_pairs_match(gi, gv, wi, wv, f"step {t} density {rho}")
+        oracle.server_push(model_ref, diff_ref, wi, wv)
+        ctx.server_push(srv.model, 0, w.idx, w.val, gi.size)
+        pi_ref, pv_ref = oracle.server_pull(diff_ref, 0, off, rho)
+        pi, pv = srv.pull(0, rho)
+        assert_pairs_match(pi, pv, pi_ref, pv_ref, f"pull {t} density {rho}")
+    assert_state_match(w.state_host(), s_ref, "worker state")
+    assert_state_match(srv.diff.cpu().numpy()[0], diff_ref[0], "difference row")
+    st = ctx.stats()
+    assert st.internal_errors == 0
+    assert st.exact_calls <= 2 * (2 * len(schedule) + 1)      # the last three steps are predicted
+    ctx.close()
