@@ -1,0 +1,82 @@
+"""Randomised GPU parity: seeded layouts (tensors from 1 to 4.6M elements), densities that change
+on the way, momentum / residual mode, tuning options picked at random (selection mode, candidate
+margin, launch shape, repair round), and gradients whose scale jumps, collapses, vanishes or
+carries a large tie class -- so predictions fail and every fallback runs.  Worker steps, pushes
+and a random number of pulls per step, each compared with the oracle (indices bit-exact, values
+1e-6 relative / 1e-7 absolute, state bits equal).  DGS_SOAK_SEEDS=a:b widens the seed range."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_1910_10929_amd import dgs, synth
+from harness import Server, Worker, assert_pairs_match, assert_state_match
+
+pytestmark = pytest.mark.gpu
+
+_lo, _hi = (int(x) for x in os.environ.get("DGS_SOAK_SEEDS", "0:12").split(":"))
+
+
+def random_layout(rng):
+    J = int(rng.integers(1, 10))
+    sizes = []
+    for _ in range(J):
+        kd = int(rng.integers(0, 6))
+        if kd == 0: sizes.append(int(rng.integers(1, 300)))
+        elif kd == 1: sizes.append(int(rng.integers(300, 9000)))
+        elif kd == 2: sizes.append(int(rng.integers(9000, 70_000)))
+        elif kd == 3: sizes.append(int(rng.integers(70_000, 400_000)))
+        elif kd == 4: sizes.append(int(rng.integers(400_000, 1_500_000)))
+        else: sizes.append(int(rng.integers(1_500_000, 4_600_000)) if rng.integers(0, 3) == 0 else int(rng.integers(1000, 20_000)))
+    return sizes
+
+def run(oracle, seed):
+    rng = np.random.default_rng(50_000 + seed)
+    sizes = random_layout(rng)
+    off = synth.offsets_from_sizes(sizes); n = int(off[-1]); J = len(sizes)
+    dens = [float(x) for x in rng.choice([3e-4, 1e-3, 3e-3, 0.01, 0.03, 0.05, 0.2], 2)]
+    rho_down = float(rng.choice([1e-3, 5e-3, 0.02]))
+    m = np.float32(rng.choice([0.0, 0.5, 0.9])); lr = np.float32(rng.choice([1.0, 0.1]))
+    scales = synth.tensor_scales(J, 60_000 + seed)
+    opts = {}
+    if rng.integers(0, 2): opts[dgs.OPT_SEGMENTED] = int(rng.choice([dgs.SEG_AUTO, dgs.SEG_ALWAYS, dgs.SEG_NEVER]))
+    if rng.integers(0, 3) == 0: opts[dgs.OPT_MARGIN_PCT] = int(rng.choice([0, 10, 200]))
+    if rng.integers(0, 4) == 0: opts[dgs.OPT_STREAM_QUADS] = int(rng.choice([2, 5]))
+    if rng.integers(0, 4) == 0: opts[dgs.OPT_REPAIR_ROUND] = 0
+    W = 2
+    ctx = dgs.Context(off, W=W)
+    for k, v in opts.items(): ctx.set_option(k, v)
+    dmax = max(dens + [rho_down])
+    w = Worker(ctx, density_max=dmax); srv = Server(ctx, np.zeros(n, np.float32), density_max=dmax)
+    s_ref = np.zeros(n, np.float32); model_ref = np.zeros(n, np.float32); diff_ref = np.zeros((W, n), np.float32)
+    steps = 9
+    for t in range(steps):
+        rho = dens[0] if t < 6 else dens[1]
+        g = synth.student_t_grads(off, scales, rng) if seed % 2 else synth.gaussian_grads(off, scales, rng)
+        ev = int(rng.integers(0, 8))
+        if ev == 0: g *= np.float32(1e3)
+        elif ev == 1: g *= np.float32(1e-4)
+        elif ev == 2: g[: n // 2] = 0.0
+        elif ev == 3: g[:] = np.float32(0.0)
+        elif ev == 4: g[rng.integers(0, n, size=max(n // 50, 1))] = np.float32(7.0)      # a tie class
+        wi, wv = oracle.worker_step(g, s_ref, off, lr, m, rho)
+        gi, gv = w.step(g, lr, m, rho, residual_mode=(m == 0.0 and seed % 3 == 0))
+        assert_pairs_match(gi, gv, wi, wv, f"seed {seed} step {t}")
+        assert_state_match(w.state_host(), s_ref, f"seed {seed} state {t}")
+        k = int(rng.integers(0, W))
+        oracle.server_push(model_ref, diff_ref, wi, wv)
+        ctx.server_push(srv.model, k, w.idx, w.val, gi.size)
+        for _ in range(int(rng.integers(0, 3))):
+            kk = int(rng.integers(0, W))
+            pi_ref, pv_ref = oracle.server_pull(diff_ref, kk, off, rho_down)
+            pi, pv = srv.pull(kk, rho_down)
+            assert_pairs_match(pi, pv, pi_ref, pv_ref, f"seed {seed} pull {t}")
+    assert_state_match(srv.diff.cpu().numpy().ravel(), diff_ref.ravel(), "diff")
+    st = ctx.stats()
+    assert st.internal_errors == 0, st
+    ctx.close()
+
+
+@pytest.mark.parametrize("seed", list(range(_lo, _hi)))
+def test_randomised_steps_with_failing_predictions(oracle, seed):
+    run(oracle, seed)
