@@ -9,6 +9,12 @@
  * stated per call).  Return value: 0 on success, a negative DGS_E* code
  * otherwise; nothing is thrown across the boundary.
  *
+ * Concurrency.  A context serialises its calls through its stream and keeps per-call
+ * scratch in its workspace: call it from one host thread at a time, and do not run two
+ * calls of one context at once on the GPU (they would race on the workspace).  Different
+ * contexts, each with its own workspace and stream, are independent -- e.g. a worker
+ * context and a server context whose steps overlap.
+ *
  * Notation: J tensors packed back to back in one flat fp32 buffer of n elements,
  * tensor j occupying [offsets[j], offsets[j+1]); n_j its size;
  * k_j = ceil(density * n_j) evaluated in IEEE double; K = sum_j k_j;
