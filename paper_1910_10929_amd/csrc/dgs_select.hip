@@ -101,9 +101,9 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
     const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
     const uint32_t hint2_cur = (td.big && A.write_hint) ? A.hint2[j] : 0u;
-    // every candidate key is >= the collection threshold: the window histogram starts there,
-    // and the join counts the entries into it as it places them
-    // (or 1024 buckets below the k-th key of the previous call, if that lies higher)
+    // The join counts the entries into the window histogram as it places them.  Every candidate
+    // key is >= the collection threshold, so the window starts there -- or, when that lies far
+    // below (a relaxed hint), 1024 buckets under the k-th key of the previous call.
     const uint32_t tprev_cur = td.big ? A.tprev[j] : 0u;
     const uint32_t win_join = max(tau_cur >> 11, max(tprev_cur >> 11, 1024u) - 1024u);
     uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
