@@ -57,6 +57,7 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 }
 
 constexpr uint32_t SEL_ROWS = 12;                                  // rows of 16 tiles per wavefront and batch
+constexpr uint32_t SEL_CNT_LOADS = (SEL_ROWS + 3) / 4;             // count loads per lane, 64 tiles each
 constexpr uint32_t SEL_WAVE_TILES = SEL_ROWS * 16;                 // 192
 constexpr uint32_t SEL_BATCH_TILES = SEL_WAVES * SEL_WAVE_TILES;   // 3072
 
@@ -120,9 +121,9 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
             const uint32_t rows = (nb + 16 * SEL_WAVES - 1) / (16 * SEL_WAVES);   // per wavefront, 1..SEL_ROWS
             const uint32_t w0 = cb + wave * rows * 16;                            // first tile of this wavefront's run
             // counts of the run, one tile per lane and load
-            uint32_t w[SEL_ROWS / 4];
+            uint32_t w[SEL_CNT_LOADS];
 #pragma unroll
-            for (uint32_t u = 0; u < SEL_ROWS / 4; ++u) {
+            for (uint32_t u = 0; u < SEL_CNT_LOADS; ++u) {
                 const uint32_t sl = u * 64 + lane;
                 w[u] = (sl < rows * 16 && w0 + sl < ntl) ? tile_cnt[tlo + w0 + sl] : 0u;
             }
@@ -144,7 +145,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
                 }
             }
 #pragma unroll
-            for (uint32_t u = 0; u < SEL_ROWS / 4; ++u) {
+            for (uint32_t u = 0; u < SEL_CNT_LOADS; ++u) {
                 if (w[u] == CNT_OVERFLOW) { ovf = 1; w[u] = 0; }
                 else if (!(head_shared && w0 == 0 && u == 0 && lane == 0)) w[u] &= 0xFFFFu;
             }
