@@ -316,24 +316,43 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
         uint32_t pos = run_sel + g_before + min(q_before, rem);
         uint32_t eq_seen = q_before;
         if (g | q) {
+            // which of this thread's entries are sent, and where they go
+            uint32_t ix[ITEMS], at[ITEMS];
 #pragma unroll
             for (int i = 0; i < ITEMS; ++i) {
                 const uint32_t p = p0 + i;
-                if (p >= cN) break;
                 const uint32_t key = vb[i] & 0x7FFFFFFFu;
-                bool sel = key > T;
-                if (key == T) {
+                bool sel = (p < cN) && key > T;
+                if (p < cN && key == T) {
                     sel = eq_seen < rem;
                     ++eq_seen;
                 }
+                at[i] = 0xFFFFFFFFu;
+                ix[i] = 0;
                 if (sel) {
-                    const uint32_t ix = src.index(p);
                     if (pos < k) {
-                        A.out_idx[outoff + pos] = ix;
-                        A.out_val[outoff + pos] = __uint_as_float(vb[i]);
-                        fix_sent<OP>(A.state, ix, __uint_as_float(vb[i]), A.m);
+                        at[i] = pos;
+                        ix[i] = src.index(p);
                     }
                     ++pos;
+                }
+            }
+            // sent_k += G reads the row: all of this thread's reads are issued before the first
+            // is needed (one memory round trip instead of one per entry)
+            float old[ITEMS];
+            if (OP == SEL_PULL_V) {
+#pragma unroll
+                for (int i = 0; i < ITEMS; ++i) old[i] = (at[i] != 0xFFFFFFFFu) ? A.state[ix[i]] : 0.0f;
+            }
+#pragma unroll
+            for (int i = 0; i < ITEMS; ++i) {
+                if (at[i] != 0xFFFFFFFFu) {
+                    const float v = __uint_as_float(vb[i]);
+                    A.out_idx[outoff + at[i]] = ix[i];
+                    A.out_val[outoff + at[i]] = v;
+                    if (OP == SEL_WORKER) store_scattered(&A.state[ix[i]], A.m * v);
+                    else if (OP == SEL_PULL) store_scattered(&A.state[ix[i]], 0.0f);
+                    else store_scattered(&A.state[ix[i]], old[i] + v);
                 }
             }
         }
