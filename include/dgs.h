@@ -239,7 +239,9 @@ int dgs_server_pull_all_sent(dgs_ctx *ctx, const float *model, uint32_t worker_i
 /*
  * Worker applies a decoded message (Algorithm 1/3, "theta <- SGD(theta,
  * decode(G))"; Eq. 5 with sign = +1):  dst[idx] = fmaf(sign, val, dst[idx]).
- * idx must be unique.
+ * dst: n floats.  idx must be unique; an index outside [0, n) is skipped.  With
+ * DGS_OPT_VALIDATE the message is checked on the device as for dgs_server_push (strictly
+ * ascending, in range; this synchronises) and DGS_EINVAL is returned before dst is touched.
  */
 int dgs_apply_sparse(dgs_ctx *ctx, float *dst, const uint32_t *idx, const float *val,
                      uint64_t nnz, float sign);
@@ -263,8 +265,8 @@ int dgs_apply_sparse(dgs_ctx *ctx, float *dst, const uint32_t *idx, const float 
  *   dgs_decode      the reverse; idx_out, val_out: device, K entries.
  * Asynchronous on the context's stream.  With DGS_OPT_VALIDATE both calls check on the device
  * that every entry lies inside its tensor (this synchronises) and return DGS_EINVAL if not;
- * without it such an index is cut to b_j bits (encode) or passed on as decoded (decode,
- * to be caught by dgs_server_push's own range check).
+ * without it such an index is cut to b_j bits (encode) or passed on as decoded (decode;
+ * dgs_server_push, dgs_server_push_model and dgs_apply_sparse skip indices outside [0, n)).
  */
 int dgs_wire_bytes(dgs_ctx *ctx, double density, uint64_t *bytes_out /*host*/);
 int dgs_encode(dgs_ctx *ctx, double density, const uint32_t *idx, const float *val, void *wire);

@@ -21,11 +21,19 @@ _c_u32p = ctypes.POINTER(ctypes.c_uint32)
 _c_u64p = ctypes.POINTER(ctypes.c_uint64)
 
 
+# DGS_ORACLE_SANITIZE=1 in the environment: the tests run against a build with the
+# undefined-behaviour sanitizer compiled in (any report aborts the process).
+_SANITIZE = os.environ.get("DGS_ORACLE_SANITIZE", "") == "1"
+if _SANITIZE:
+    _LIB = os.path.join(_HERE, "libdgs_oracle_ubsan.so")
+
+
 def build(force: bool = False) -> str:
     """Compile the oracle with gcc.  No fast-math, no contraction, no FTZ."""
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        extra = ["-g", "-fsanitize=undefined", "-fno-sanitize-recover=all"] if _SANITIZE else []
         cmd = ["gcc", "-std=c99", "-O2", "-fPIC", "-shared", "-ffp-contract=off",
-               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+               "-fno-fast-math", "-Wall", "-Wextra"] + extra + ["-o", _LIB, _SRC, "-lm"]
         subprocess.run(cmd, check=True)
     return _LIB
 

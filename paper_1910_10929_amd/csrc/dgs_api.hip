@@ -83,6 +83,7 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
 
 struct PlanSlot {
     bool valid = false;
+    bool captured = false;             // used while the stream was being captured: never evicted
     double density = 0.0;
     int margin = 0;
     int seg_mode = 0;
@@ -99,13 +100,25 @@ struct ProfClass {
 
 uint32_t isqrt_u32(uint32_t x) { return (uint32_t)std::floor(std::sqrt((double)x)); }
 
+// Host-side array of a context: owned (heap) for contexts made by dgs_create, borrowed from
+// the caller's stack for the entry point that must not allocate.
+template <class T>
+struct HostArr {
+    T *p = nullptr;
+    std::vector<T> own;
+    T &operator[](size_t i) const { return p[i]; }
+    template <class It> void assign(It first, It last) { own.assign(first, last); p = own.data(); }
+    void assign(size_t count, T v) { own.assign(count, v); p = own.data(); }
+    void borrow(T *q) { p = q; }
+};
+
 }  // namespace
 
 struct dgs_ctx {
     hipStream_t stream = nullptr;
     uint32_t J = 0, W = 0, n = 0, ntiles = 0, nquads = 0;
     int cus = 256;
-    std::vector<uint64_t> offsets;
+    HostArr<uint64_t> offsets;
     char *ws = nullptr;
     Layout L{};
     // device views
@@ -128,7 +141,7 @@ struct dgs_ctx {
     SegState *segstate = nullptr;
     uint4 *pfxlist = nullptr;
     uint32_t nseg_total = 0;
-    std::vector<uint32_t> nseg;        // per tensor: segments (0 = never segmented)
+    HostArr<uint32_t> nseg;            // per tensor: segments (0 = never segmented)
     float *diff = nullptr;
     float *sent = nullptr;             // W rows: what each worker has been sent (model - sent_k form)
     // plan cache
@@ -136,7 +149,8 @@ struct dgs_ctx {
     PlanEntry *plan_stage = nullptr;   // pinned host, NPLAN * J
     uint64_t tick = 0;
     // which density each hint set was produced for (0 = none yet)
-    std::vector<double> hint_density;  // W + 1 entries; entry 0 = worker
+    HostArr<double> hint_density;      // W + 1 entries; entry 0 = worker
+    bool no_alloc = false;             // tables go up as kernel arguments, nothing is allocated or copied
     // options
     bool force_exact = false, profile = false, validate = false;
     int margin_pct = 50;
@@ -226,25 +240,39 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
     if (plan_with(SEL_LDS_LIST + SEL_LDS_LIST / 2) != 0) plan_with(SEL_LDS_LIST);
 }
 
-// Returns the cache slot holding the plan for `density`, uploading it if new.
+int upload(dgs_ctx *c, void *dst, const void *src, size_t bytes);
+
+// Returns the cache slot holding the plan for `density`, uploading it if new.  A slot used
+// while the stream was being captured is never evicted afterwards (the captured graph holds
+// its device address), and a plan that would have to be uploaded during capture is refused.
 int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
 {
     ++c->tick;
+    bool capturing = false;
+    if (!c->no_alloc) {
+        hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+        if (hipStreamIsCapturing(c->stream, &cs) == hipSuccess) capturing = (cs != hipStreamCaptureStatusNone);
+        else (void)hipGetLastError();
+    }
     for (uint32_t s = 0; s < NPLAN; ++s) {
         PlanSlot &p = c->plan_slot[s];
         if (p.valid && p.density == density && p.margin == c->margin_pct && p.seg_mode == c->seg_mode) {
             p.last_use = c->tick;
+            if (capturing) p.captured = true;
             *slot_out = s;
             *K_out = p.K;
             return DGS_OK;
         }
     }
-    uint32_t victim = 0;
+    if (capturing) return DGS_ENOTSUP;   // first use of a density: call it once outside the capture
+    uint32_t victim = NPLAN;
     bool reuse = true;
     for (uint32_t s = 0; s < NPLAN; ++s) {
         if (!c->plan_slot[s].valid) { victim = s; reuse = false; break; }
-        if (c->plan_slot[s].last_use < c->plan_slot[victim].last_use) victim = s;
+        if (c->plan_slot[s].captured) continue;
+        if (victim == NPLAN || c->plan_slot[s].last_use < c->plan_slot[victim].last_use) victim = s;
     }
+    if (victim == NPLAN) return DGS_ENOTSUP;   // every slot belongs to a captured graph
     if (reuse) {
         // the staging area of this slot may still feed an earlier upload
         if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
@@ -254,11 +282,11 @@ int get_plan(dgs_ctx *c, double density, uint32_t *slot_out, uint64_t *K_out)
     uint32_t active = 0;
     fill_plan(c, density, c->margin_pct, stage, &K, &active, &wire_words);
     if (K >= (1ull << 32)) return DGS_EINVAL;
-    if (hipMemcpyAsync(c->plans + (size_t)victim * c->J, stage, (size_t)c->J * sizeof(PlanEntry),
-                       hipMemcpyHostToDevice, c->stream) != hipSuccess)
-        return DGS_EHIP;
+    const int rc = upload(c, c->plans + (size_t)victim * c->J, stage, (size_t)c->J * sizeof(PlanEntry));
+    if (rc != DGS_OK) return rc;
     PlanSlot &p = c->plan_slot[victim];
     p.valid = true;
+    p.captured = false;
     p.density = density;
     p.margin = c->margin_pct;
     p.seg_mode = c->seg_mode;
@@ -451,6 +479,107 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     return DGS_OK;
 }
 
+// Point the context's device views into its workspace.
+void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
+{
+    c->ws = (char *)workspace;
+    c->L = L;
+    c->toff = (uint32_t *)(c->ws + L.tile_desc);
+    c->tdesc = (TensorDesc *)(c->ws + L.tdesc);
+    c->plans = (PlanEntry *)(c->ws + L.plans);
+    c->tau = (uint32_t *)(c->ws + L.tau);
+    c->hint2 = (uint32_t *)(c->ws + L.hint2);
+    c->tprev = (uint32_t *)(c->ws + L.tprev);
+    c->ghist = (uint32_t *)(c->ws + L.ghist);
+    c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
+    c->heads = (uint2 *)(c->ws + L.heads);
+    c->slots = (uint2 *)(c->ws + L.slots);
+    c->ord = (uint2 *)(c->ws + L.ord);
+    c->stats = (DevStats *)(c->ws + L.stats);
+    c->flag = (uint32_t *)(c->ws + L.flag);
+    c->segtab = (SegDesc *)(c->ws + L.segtab);
+    c->segcnt = (uint32_t *)(c->ws + L.segcnt);
+    c->segG1 = (uint32_t *)(c->ws + L.segG1);
+    c->segQ = (uint32_t *)(c->ws + L.segQ);
+    c->segOut = (uint2 *)(c->ws + L.segOut);
+    c->segstate = (SegState *)(c->ws + L.segstate);
+    c->pfxlist = (uint4 *)(c->ws + L.pfxlist);
+}
+
+// Tensor, segment and initial-threshold tables of a layout, into host arrays of J,
+// (W + 1) J, J + 1 and (sum of tensor_segments) entries; fills c->nseg and c->nseg_total.
+void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, SegDesc *segs)
+{
+    const uint32_t J = c->J, W = c->W;
+    uint32_t pfx_slots = 0, nsegs = 0;
+    for (uint32_t j = 0; j < J; ++j) {
+        td[j].off = (uint32_t)c->offsets[j];
+        td[j].n = (uint32_t)(c->offsets[j + 1] - c->offsets[j]);
+        td[j].big = td[j].n > SMALL_N ? 1u : 0u;
+        td[j].pad0 = td[j].pad1 = 0;
+        const uint32_t ns = tensor_segments(c->offsets[j], c->offsets[j + 1] - c->offsets[j]);
+        td[j].seg_first = nsegs;
+        td[j].nseg = ns;
+        td[j].pfx_slot = ns ? pfx_slots++ : 0u;
+        c->nseg[j] = ns;
+        const uint32_t tlo = td[j].off / TILE, thi = (td[j].off + td[j].n - 1) / TILE;
+        for (uint32_t sidx = 0; sidx < ns; ++sidx) {
+            SegDesc d;
+            d.j = j;
+            d.tile0 = tlo + sidx * SEG_TILES;
+            d.ntiles = (thi + 1 - d.tile0 < SEG_TILES) ? (thi + 1 - d.tile0) : SEG_TILES;
+            d.sidx = sidx;
+            segs[nsegs++] = d;
+        }
+        for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
+    }
+    for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)c->offsets[j];
+    c->nseg_total = nsegs;
+}
+
+// Host -> device: a copy on the stream, or -- for the context that must not allocate or copy
+// -- kernels that carry the bytes as their arguments.
+int upload(dgs_ctx *c, void *dst, const void *src, size_t bytes)
+{
+    if (bytes == 0) return DGS_OK;
+    if (c->no_alloc) {
+        launch_put_words((uint32_t *)dst, (const uint32_t *)src, bytes / 4, c->stream);
+        return DGS_OK;
+    }
+    return hipMemcpyAsync(dst, src, bytes, hipMemcpyHostToDevice, c->stream) == hipSuccess ? DGS_OK : DGS_EHIP;
+}
+
+// Tables up, counters cleared: what a context's workspace holds before its first call.
+int upload_tables(dgs_ctx *c, const TensorDesc *td, const uint32_t *tau0, const uint32_t *toff, const SegDesc *segs)
+{
+    const uint32_t J = c->J, W = c->W;
+    int rc = upload(c, c->toff, toff, ((size_t)J + 1) * sizeof(uint32_t));
+    if (rc == DGS_OK) rc = upload(c, c->tdesc, td, (size_t)J * sizeof(TensorDesc));
+    if (rc == DGS_OK) rc = upload(c, c->tau, tau0, (size_t)(W + 1) * J * sizeof(uint32_t));
+    if (rc == DGS_OK) rc = upload(c, c->segtab, segs, (size_t)c->nseg_total * sizeof(SegDesc));
+    if (rc != DGS_OK) return rc;
+    launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
+    launch_fill_u32(c->tprev, 0u, (size_t)(W + 1) * J, c->stream);
+    launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
+    launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
+    launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);
+    launch_fill_u32(c->flag, 0u, 16, c->stream);
+    launch_fill_u32((uint32_t *)c->segstate, 0u, (size_t)J * sizeof(SegState) / 4, c->stream);
+    return hipGetLastError() == hipSuccess ? DGS_OK : DGS_EHIP;
+}
+
+// DGS_OPT_VALIDATE: indices strictly ascending and inside [0, n), checked on the device
+// before anything is modified (waits for the stream).
+int validate_message(dgs_ctx *c, const uint32_t *idx, uint64_t nnz)
+{
+    launch_fill_u32(c->flag, 0u, 1, c->stream);
+    launch_validate_idx(idx, (uint32_t)nnz, c->n, c->flag, c->stream);
+    uint32_t bad = 0;
+    if (hipMemcpyAsync(&bad, c->flag, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
+    if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
+    return bad ? DGS_EINVAL : DGS_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -480,28 +609,7 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->ntiles = (c->n + TILE - 1) / TILE;
     c->nquads = (c->ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
     c->offsets.assign(offsets, offsets + J + 1);
-    c->ws = (char *)workspace;
-    c->L = L;
-    c->toff = (uint32_t *)(c->ws + L.tile_desc);
-    c->tdesc = (TensorDesc *)(c->ws + L.tdesc);
-    c->plans = (PlanEntry *)(c->ws + L.plans);
-    c->tau = (uint32_t *)(c->ws + L.tau);
-    c->hint2 = (uint32_t *)(c->ws + L.hint2);
-    c->tprev = (uint32_t *)(c->ws + L.tprev);
-    c->ghist = (uint32_t *)(c->ws + L.ghist);
-    c->tile_cnt = (uint32_t *)(c->ws + L.tile_cnt);
-    c->heads = (uint2 *)(c->ws + L.heads);
-    c->slots = (uint2 *)(c->ws + L.slots);
-    c->ord = (uint2 *)(c->ws + L.ord);
-    c->stats = (DevStats *)(c->ws + L.stats);
-    c->flag = (uint32_t *)(c->ws + L.flag);
-    c->segtab = (SegDesc *)(c->ws + L.segtab);
-    c->segcnt = (uint32_t *)(c->ws + L.segcnt);
-    c->segG1 = (uint32_t *)(c->ws + L.segG1);
-    c->segQ = (uint32_t *)(c->ws + L.segQ);
-    c->segOut = (uint2 *)(c->ws + L.segOut);
-    c->segstate = (SegState *)(c->ws + L.segstate);
-    c->pfxlist = (uint4 *)(c->ws + L.pfxlist);
+    carve_workspace(c, workspace, L);
     c->hint_density.assign((size_t)W + 1, 0.0);
 
     int dev = 0;
@@ -517,52 +625,18 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     if (env) c->stream_quads = (uint32_t)std::strtoul(env, nullptr, 10);
 
     // host-side plan: tensor and tile descriptors
+    uint32_t nseg_total = 0;
+    for (uint32_t j = 0; j < J; ++j) nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
     std::vector<TensorDesc> td(J);
     std::vector<uint32_t> tau0((size_t)(W + 1) * J);
-    std::vector<SegDesc> segs;
-    c->nseg.assign(J, 0u);
-    uint32_t pfx_slots = 0;
-    for (uint32_t j = 0; j < J; ++j) {
-        td[j].off = (uint32_t)offsets[j];
-        td[j].n = (uint32_t)(offsets[j + 1] - offsets[j]);
-        td[j].big = td[j].n > SMALL_N ? 1u : 0u;
-        td[j].pad0 = td[j].pad1 = 0;
-        const uint32_t ns = tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
-        td[j].seg_first = (uint32_t)segs.size();
-        td[j].nseg = ns;
-        td[j].pfx_slot = ns ? pfx_slots++ : 0u;
-        c->nseg[j] = ns;
-        const uint32_t tlo = td[j].off / TILE, thi = (td[j].off + td[j].n - 1) / TILE;
-        for (uint32_t sidx = 0; sidx < ns; ++sidx) {
-            SegDesc d;
-            d.j = j;
-            d.tile0 = tlo + sidx * SEG_TILES;
-            d.ntiles = (thi + 1 - d.tile0 < SEG_TILES) ? (thi + 1 - d.tile0) : SEG_TILES;
-            d.sidx = sidx;
-            segs.push_back(d);
-        }
-        for (uint32_t w = 0; w <= W; ++w) tau0[(size_t)w * J + j] = td[j].big ? 1u : TAU_NEVER;
-    }
+    std::vector<SegDesc> segs(nseg_total + 1);
     std::vector<uint32_t> toff(J + 1);
-    for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)offsets[j];
+    c->nseg.assign(J, 0u);
+    fill_tables(c, td.data(), tau0.data(), toff.data(), segs.data());
 
     bool ok = true;
     ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
-    ok = ok && hipMemcpyAsync(c->toff, toff.data(), toff.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
-    ok = ok && hipMemcpyAsync(c->tdesc, td.data(), td.size() * sizeof(TensorDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
-    ok = ok && hipMemcpyAsync(c->tau, tau0.data(), tau0.size() * sizeof(uint32_t), hipMemcpyHostToDevice, c->stream) == hipSuccess;
-    c->nseg_total = (uint32_t)segs.size();
-    if (!segs.empty())
-        ok = ok && hipMemcpyAsync(c->segtab, segs.data(), segs.size() * sizeof(SegDesc), hipMemcpyHostToDevice, c->stream) == hipSuccess;
-    if (ok) {
-        launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
-        launch_fill_u32(c->tprev, 0u, (size_t)(W + 1) * J, c->stream);
-        launch_fill_u32(c->ghist, 0u, (size_t)J * HBINS, c->stream);
-        launch_fill_u32(c->tile_cnt, 0u, (size_t)c->ntiles + 4, c->stream);
-        launch_fill_u32((uint32_t *)c->stats, 0u, sizeof(DevStats) / 4, c->stream);
-        launch_fill_u32(c->flag, 0u, 16, c->stream);
-        launch_fill_u32((uint32_t *)c->segstate, 0u, (size_t)J * sizeof(SegState) / 4, c->stream);
-    }
+    ok = ok && upload_tables(c, td.data(), tau0.data(), toff.data(), segs.data()) == DGS_OK;
     ok = ok && hipStreamSynchronize(c->stream) == hipSuccess;
     ok = ok && hipGetLastError() == hipSuccess;
     if (!ok) {
@@ -637,12 +711,8 @@ int dgs_server_push(dgs_ctx *c, float *model, uint32_t worker_id, const uint32_t
     if (nnz && (!idx || !val)) return DGS_EINVAL;
     if (model && !aligned4(model)) return DGS_EINVAL;
     if (c->validate && nnz) {
-        launch_fill_u32(c->flag, 0u, 1, c->stream);
-        launch_validate_idx(idx, (uint32_t)nnz, c->n, c->flag, c->stream);
-        uint32_t bad = 0;
-        if (hipMemcpyAsync(&bad, c->flag, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
-        if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
-        if (bad) return DGS_EINVAL;
+        const int rc = validate_message(c, idx, nnz);
+        if (rc != DGS_OK) return rc;
     }
     ++c->calls_push;
     {
@@ -682,12 +752,8 @@ int dgs_server_push_model(dgs_ctx *c, float *model, const uint32_t *idx, const f
     if (nnz && (!idx || !val)) return DGS_EINVAL;
     if (!aligned4(model)) return DGS_EINVAL;
     if (c->validate && nnz) {
-        launch_fill_u32(c->flag, 0u, 1, c->stream);
-        launch_validate_idx(idx, (uint32_t)nnz, c->n, c->flag, c->stream);
-        uint32_t bad = 0;
-        if (hipMemcpyAsync(&bad, c->flag, 4, hipMemcpyDeviceToHost, c->stream) != hipSuccess) return DGS_EHIP;
-        if (hipStreamSynchronize(c->stream) != hipSuccess) return DGS_EHIP;
-        if (bad) return DGS_EINVAL;
+        const int rc = validate_message(c, idx, nnz);
+        if (rc != DGS_OK) return rc;
     }
     ++c->calls_push;
     {
@@ -757,7 +823,12 @@ int dgs_apply_sparse(dgs_ctx *c, float *dst, const uint32_t *idx, const float *v
     if (!c || !dst) return DGS_EINVAL;
     if (nnz > c->n) return DGS_EINVAL;
     if (nnz && (!idx || !val)) return DGS_EINVAL;
-    launch_apply(dst, idx, val, (uint32_t)nnz, sign, c->stream);
+    if (!aligned4(dst)) return DGS_EINVAL;
+    if (c->validate && nnz) {
+        const int rc = validate_message(c, idx, nnz);
+        if (rc != DGS_OK) return rc;
+    }
+    launch_apply(dst, c->n, idx, val, (uint32_t)nnz, sign, c->stream);
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     return DGS_OK;
 }

@@ -204,9 +204,11 @@ void launch_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J
 void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K,
                         const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag, void *stream,
                         void *ev0, void *ev1);
-void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
+void launch_apply(float *dst, uint32_t n, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream);
 void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream);
+// Host words -> device through kernel arguments (for the entry point that must not copy).
+void launch_put_words(uint32_t *dst, const uint32_t *src_host, size_t words, void *stream);
 void launch_pull_all_count(const float *row, const float *model, uint32_t n, uint32_t ntiles,
                            uint32_t *tile_cnt, void *stream);
 void launch_pull_all_scan(uint32_t *tile_cnt, uint32_t ntiles, uint32_t *total, void *stream);

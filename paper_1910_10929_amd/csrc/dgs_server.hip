@@ -58,20 +58,22 @@ void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t
                        idx, nnz, n, flag);
 }
 
-__global__ __launch_bounds__(256) void k_apply(float *dst, const uint32_t *idx, const float *val,
+// An index outside [0, n) is skipped, as in k_push: a corrupted message must not write
+// outside the destination.
+__global__ __launch_bounds__(256) void k_apply(float *dst, uint32_t n, const uint32_t *idx, const float *val,
                                                uint32_t nnz, float sign)
 {
     const uint32_t e = blockIdx.x * 256 + threadIdx.x;
     if (e >= nnz) return;
     const uint32_t i = idx[e];
-    dst[i] = __builtin_fmaf(sign, val[e], dst[i]);
+    if (i < n) dst[i] = __builtin_fmaf(sign, val[e], dst[i]);
 }
 
-void launch_apply(float *dst, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
+void launch_apply(float *dst, uint32_t n, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream)
 {
     if (nnz == 0) return;
-    hipLaunchKernelGGL(k_apply, dim3((nnz + 255) / 256), dim3(256), 0, (hipStream_t)stream, dst, idx,
+    hipLaunchKernelGGL(k_apply, dim3((nnz + 255) / 256), dim3(256), 0, (hipStream_t)stream, dst, n, idx,
                        val, nnz, sign);
 }
 
@@ -182,6 +184,27 @@ void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream)
     size_t blocks = (count + 255) / 256;
     if (blocks > 4096) blocks = 4096;
     hipLaunchKernelGGL(k_fill_u32, dim3((uint32_t)blocks), dim3(256), 0, (hipStream_t)stream, p, v, count);
+}
+
+// A small host table carried to the device inside kernel arguments (no copy engine, no
+// staging buffer): PUT_WORDS 32-bit words per launch.
+constexpr uint32_t PUT_WORDS = 768;
+struct PutChunk { uint32_t w[PUT_WORDS]; };
+
+__global__ __launch_bounds__(256) void k_put_words(uint32_t *dst, const PutChunk c, uint32_t count)
+{
+    for (uint32_t i = threadIdx.x; i < count; i += 256) dst[i] = c.w[i];
+}
+
+void launch_put_words(uint32_t *dst, const uint32_t *src_host, size_t words, void *stream)
+{
+    for (size_t o = 0; o < words; o += PUT_WORDS) {
+        PutChunk c;
+        const uint32_t cnt = (uint32_t)((words - o < PUT_WORDS) ? (words - o) : PUT_WORDS);
+        for (uint32_t i = 0; i < cnt; ++i) c.w[i] = src_host[o + i];
+        for (uint32_t i = cnt; i < PUT_WORDS; ++i) c.w[i] = 0;
+        hipLaunchKernelGGL(k_put_words, dim3(1), dim3(256), 0, (hipStream_t)stream, dst + o, c, cnt);
+    }
 }
 
 // ---------------------------------------------------------------------------

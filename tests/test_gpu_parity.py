@@ -377,3 +377,45 @@ def test_density_schedule_beyond_the_plan_cache(oracle, torch_mod):
     assert st.internal_errors == 0
     assert st.exact_calls <= 2 * (2 * len(schedule) + 1)      # the last three steps are predicted
     ctx.close()
+
+
+@pytest.mark.parametrize("sign", [-1.0, 0.5])
+def test_apply_sparse_sign_and_range(oracle, torch_mod, sign):
+    """dgs_apply_sparse (Algorithm 1/3 apply line; Eq. 5 has sign +1) with other signs: one fma
+    per named entry, everything else untouched; an index outside the buffer is skipped, and
+    refused before anything is written when validation is on."""
+    torch = torch_mod
+    rng = np.random.default_rng(77)
+    sizes = [5000, 70_001, 1234]
+    off = synth.offsets_from_sizes(sizes)
+    n = int(off[-1])
+    ctx = dgs.Context(off, W=0)
+    theta0 = rng.standard_normal(n).astype(np.float32)
+    idx = np.sort(rng.choice(n, 3000, replace=False)).astype(np.uint32)
+    val = rng.standard_normal(3000).astype(np.float32)
+    val[:50] = theta0[idx[:50]] * np.float32(1.0 + 2.0 ** -20)
+    want = theta0.copy()
+    oracle.apply_sparse(want, idx, val, sign)
+    theta = to_dev(theta0)
+    ctx.apply_sparse(theta, to_dev(idx), to_dev(val), idx.size, sign)
+    torch.cuda.synchronize()
+    assert_state_match(theta.cpu().numpy(), want, f"apply sign {sign}")
+    # a corrupted message: one index past the end
+    bad = idx.copy()
+    bad[-1] = n + 5
+    want2 = want.copy()
+    oracle.apply_sparse(want2, idx[:-1], val[:-1], sign)
+    guard = torch.zeros(n + 64, dtype=torch.float32, device="cuda:0")
+    guard[:n].copy_(theta)
+    ctx.apply_sparse(guard[:n], to_dev(bad), to_dev(val), bad.size, sign)
+    torch.cuda.synchronize()
+    assert_state_match(guard[:n].cpu().numpy(), want2, "out-of-range entry skipped")
+    assert not guard[n:].any().item(), "write past the destination"
+    ctx.set_option(dgs.OPT_VALIDATE, 1)
+    before = guard.clone()
+    with pytest.raises(dgs.DgsError) as ei:
+        ctx.apply_sparse(guard[:n], to_dev(bad), to_dev(val), bad.size, sign)
+    assert ei.value.code == dgs.DGS_EINVAL
+    torch.cuda.synchronize()
+    assert torch.equal(guard, before)
+    ctx.close()

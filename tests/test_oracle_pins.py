@@ -503,9 +503,14 @@ def test_printed_server_form_without_secondary_compression(oracle):
         si, sv = oracle.server_pull_all_sent(model_s, sent, k)
         assert np.array_equal(di, si) and np.array_equal(dv, sv), e
         assert np.array_equal(sent[k], model_s)
-    with pytest.raises(Exception):                              # capacity
-        oracle.server_push_model(model_s, np.array([1, 2, 3], np.uint32), np.ones(3, np.float32))
+    # capacity: three nonzeros do not fit two slots; the refused call changes nothing
+    oracle.server_push_model(model_s, np.array([1, 2, 3], np.uint32), np.ones(3, np.float32))
+    before = sent[0].copy()
+    with pytest.raises(Exception):
         oracle.server_pull_all_sent(model_s, sent, 0, capacity=2)
+    assert np.array_equal(bits(sent[0]), bits(before))
+    gi, gv = oracle.server_pull_all_sent(model_s, sent, 0, capacity=3)   # exactly enough
+    assert np.array_equal(gi, np.array([1, 2, 3], np.uint32)) and np.array_equal(gv, -np.ones(3, np.float32))
 
 
 def test_double_pull_returns_next_k(oracle):
@@ -547,6 +552,60 @@ def test_pull_all_without_secondary_compression(oracle):
     assert np.array_equal(idx, want_pos.astype(np.uint32))
     assert np.array_equal(val, want_val)
     assert not diff[1].any()
+
+
+def test_pull_all_capacity_branch(oracle):
+    """Algorithm 2 with the compression switch off, on the difference rows: a message that
+    does not fit `capacity` is refused, the count is still reported, and the row is left
+    as it was; with exactly enough room it goes through."""
+    n = 64
+    diff = np.zeros((1, n), np.float32)
+    pos = np.array([3, 9, 10, 40, 63])
+    diff[0, pos] = np.array([1.5, -2.0, 1e-40, -0.25, 7.0], np.float32)   # one subnormal: still nonzero
+    before = diff[0].copy()
+    lib = oracle.lib()
+    import ctypes
+    idx = np.zeros(8, np.uint32)
+    val = np.zeros(8, np.float32)
+    cnt = ctypes.c_uint64(0)
+    f32p, u32p = ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_uint32)
+    rc = lib.dgs_oracle_server_pull_all(diff[0].ctypes.data_as(f32p), n, idx.ctypes.data_as(u32p),
+                                        val.ctypes.data_as(f32p), 4, ctypes.byref(cnt))
+    assert rc != 0 and cnt.value == 5
+    assert np.array_equal(bits(diff[0]), bits(before)) and not idx.any() and not val.any()
+    with pytest.raises(Exception):
+        oracle.server_pull_all(diff, 0, capacity=4)
+    gi, gv = oracle.server_pull_all(diff, 0, capacity=5)
+    assert np.array_equal(gi, pos.astype(np.uint32)) and np.array_equal(bits(gv), bits(before[pos]))
+    assert not diff[0].any()
+
+
+@pytest.mark.parametrize("sign", [1.0, -1.0, 0.5, -0.333251953125])
+def test_apply_sparse_is_one_fma_with_the_sign(oracle, sign):
+    """Worker applies decode(G): theta[idx] = fma(sign, val, theta[idx]) (Eq. 5 has sign +1),
+    against exact rational arithmetic; entries not named stay untouched."""
+    rng = np.random.default_rng(21)
+    n = 300
+    theta = rng.standard_normal(n).astype(np.float32)
+    idx = np.sort(rng.choice(n, 120, replace=False)).astype(np.uint32)
+    val = rng.standard_normal(120).astype(np.float32)
+    val[:6] = theta[idx[:6]] * np.float32(1.0 + 2.0 ** -20)      # near-cancellation when sign = -1
+    val[6:9] = np.array([1e-40, -2e-45, 3e-39], np.float32)      # subnormal values
+    theta[idx[6:9]] = np.array([-1e-41, 1e-45, 1e-38], np.float32)
+    want = theta.copy()
+    for e, i in enumerate(idx):
+        want[i] = exact_fma_f32(np.float32(sign), val[e], theta[i])
+    got = theta.copy()
+    oracle.apply_sparse(got, idx, val, sign)
+    assert np.array_equal(bits(got), bits(want))
+    if sign not in (1.0, -1.0):
+        two_step = theta.copy()
+        two_step[idx] = (np.float32(sign) * val).astype(np.float32) + theta[idx]
+        assert np.any(bits(two_step) != bits(want)), "no case separates one rounding from two"
+    else:
+        flipped = theta.copy()
+        flipped[idx] = theta[idx] - np.float32(sign) * val
+        assert np.any(bits(flipped) != bits(want)), "the sign is not observable"
 
 
 def test_hand_example(oracle):
