@@ -161,6 +161,29 @@ int dgs_worker_step(dgs_ctx *ctx, const float *grad, float *momentum, float *res
                     uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/);
 
 /*
+ * dgs_worker_step for callers that cannot allocate device memory or copy to it: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments,
+ * arithmetic and results as dgs_worker_step, without a context: the layout is given with the
+ * call (offsets: host, J + 1 entries, as for dgs_create), the work is enqueued on `hip_stream`
+ * (NULL = the default stream), and the workspace is an array of DGS_STATIC_SCRATCH_BYTES bytes
+ * that the library holds in device memory on every GPU it runs on, until the process ends.
+ * The call makes no hipMalloc / hipFree / hipHostMalloc, creates no events, issues no copies
+ * and does not wait: the layout tables travel as kernel arguments.
+ * Limits: J <= DGS_STATIC_MAX_TENSORS, and dgs_workspace_bytes(offsets, J, 0) <=
+ * DGS_STATIC_SCRATCH_BYTES (about 1e7 parameters); beyond them DGS_ECAPACITY is returned and
+ * nothing is enqueued.  Nothing is remembered between calls (each starts from a cleared
+ * workspace and takes the two-pass path), so it is slower than a context.
+ * All calls on one GPU share that GPU's array: two calls whose work overlaps on the GPU (two
+ * streams, two threads) race; order them.
+ */
+#define DGS_STATIC_SCRATCH_BYTES (48u << 20)
+#define DGS_STATIC_MAX_TENSORS 256
+int dgs_worker_step_static(const uint64_t *offsets /*host*/, uint32_t J, const float *grad,
+                           float *momentum, float *residual, float lr, float m, double density,
+                           uint32_t *idx_out, float *val_out, uint64_t *nnz_out /*host*/,
+                           void *hip_stream);
+
+/*
  * Give the server side its per-worker difference buffers: W rows of n floats,
  * row-major, row w = D_w = M - v_w in the notation of Eq. 1-6 (the part of the
  * accumulated update M that worker w has not been sent yet).  The caller

@@ -5,6 +5,7 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -691,6 +692,98 @@ int dgs_worker_step(dgs_ctx *c, const float *grad, float *momentum, float *resid
     if (!aligned4(grad) || !aligned4(state) || !aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
     ++c->calls_worker;
     return run_selection(c, OP_FMA, SEL_WORKER, grad, state, lr, m, density, 0, idx_out, val_out, nnz_out,
+                         DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT, DGS_PROF_WORKER_SEGMENTED);
+}
+
+// ---------------------------------------------------------------------------
+// the entry point that allocates nothing
+// ---------------------------------------------------------------------------
+
+namespace {
+
+// Scratch of dgs_worker_step_static: in place of the caller-allocated workspace of a context.
+// One copy per GPU, held until the process ends.
+static __device__ __align__(256) unsigned char scratch[DGS_STATIC_SCRATCH_BYTES];
+
+constexpr int STATIC_MAX_DEVICES = 64;
+constexpr uint32_t STATIC_MAX_SEGS = 1024;
+void *g_scratch_ptr[STATIC_MAX_DEVICES];   // device address of `scratch`, per device (0 = not asked yet)
+std::mutex g_scratch_mutex;
+
+// Device address of this GPU's copy of `scratch`, resolved once per device with that device
+// current.  The array's name is only a host-side handle: everything on the host uses the
+// address returned here.
+int static_scratch(void **out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= STATIC_MAX_DEVICES) return DGS_EHIP;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            return DGS_EHIP;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    *out = g_scratch_ptr[dev];
+    return DGS_OK;
+}
+
+}  // namespace
+
+int dgs_worker_step_static(const uint64_t *offsets, uint32_t J, const float *grad, float *momentum,
+                           float *residual, float lr, float m, double density, uint32_t *idx_out,
+                           float *val_out, uint64_t *nnz_out, void *hip_stream)
+{
+    if (!check_offsets(offsets, J) || !grad || !idx_out || !val_out) return DGS_EINVAL;
+    if (!momentum && !residual) return DGS_EINVAL;
+    if (momentum && residual) return DGS_ENOTSUP;
+    if (!(density > 0.0) || density > 1.0) return DGS_EINVAL;
+    if (!(m >= 0.0f) || !(m < 1.0f)) return DGS_EINVAL;
+    if (residual && m != 0.0f) return DGS_EINVAL;
+    if (!std::isfinite(lr)) return DGS_EINVAL;
+    float *state = momentum ? momentum : residual;
+    if (!aligned4(grad) || !aligned4(state) || !aligned4(idx_out) || !aligned4(val_out)) return DGS_EINVAL;
+    // limits: the tables live on this call's stack, the workspace in the static array
+    if (J > DGS_STATIC_MAX_TENSORS) return DGS_ECAPACITY;
+    const Layout L = make_layout(offsets, J, 0);
+    if (L.total > DGS_STATIC_SCRATCH_BYTES) return DGS_ECAPACITY;
+    uint32_t nseg_total = 0;
+    for (uint32_t j = 0; j < J; ++j) nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+    if (nseg_total > STATIC_MAX_SEGS) return DGS_ECAPACITY;
+    void *ws = nullptr;
+    int rc = static_scratch(&ws);
+    if (rc != DGS_OK) return rc;
+
+    // a context that lives on this stack: no heap, no pinned memory, no events
+    uint64_t offs[DGS_STATIC_MAX_TENSORS + 1];
+    uint32_t nseg[DGS_STATIC_MAX_TENSORS];
+    double hint_density[1] = {0.0};
+    TensorDesc td[DGS_STATIC_MAX_TENSORS];
+    uint32_t tau0[DGS_STATIC_MAX_TENSORS], toff[DGS_STATIC_MAX_TENSORS + 1];
+    SegDesc segs[STATIC_MAX_SEGS + 1];
+    PlanEntry plan[DGS_STATIC_MAX_TENSORS];
+    for (uint32_t j = 0; j <= J; ++j) offs[j] = offsets[j];
+    dgs_ctx c;
+    c.no_alloc = true;
+    c.stream = (hipStream_t)hip_stream;
+    c.J = J;
+    c.W = 0;
+    c.n = (uint32_t)offsets[J];
+    c.ntiles = (c.n + TILE - 1) / TILE;
+    c.nquads = (c.ntiles + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+    c.offsets.borrow(offs);
+    c.nseg.borrow(nseg);
+    c.hint_density.borrow(hint_density);
+    c.plan_stage = plan;               // one density per call: only the first cache slot is used
+    carve_workspace(&c, ws, L);
+    fill_tables(&c, td, tau0, toff, segs);
+    // every call starts from a clean workspace (the array keeps the previous call's contents);
+    // with no threshold hints the step takes the two-pass path
+    rc = upload_tables(&c, td, tau0, toff, segs);
+    if (rc != DGS_OK) return rc;
+    return run_selection(&c, OP_FMA, SEL_WORKER, grad, state, lr, m, density, 0, idx_out, val_out, nnz_out,
                          DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT, DGS_PROF_WORKER_SEGMENTED);
 }
 

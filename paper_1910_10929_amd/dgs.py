@@ -28,6 +28,7 @@ EXPORTS = [
     "dgs_apply_sparse", "dgs_set_option", "dgs_get_stats", "dgs_profile_read", "dgs_strerror",
     "dgs_server_attach_sent", "dgs_server_push_model", "dgs_server_pull_sent",
     "dgs_wire_bytes", "dgs_encode", "dgs_decode", "dgs_server_pull_all_sent",
+    "dgs_worker_step_static",
 ]
 
 
@@ -65,6 +66,8 @@ def lib():
         L.dgs_nnz.argtypes = [_vp, ctypes.c_double, _u64p]
         L.dgs_worker_step.argtypes = [_vp, _vp, _vp, _vp, ctypes.c_float, ctypes.c_float,
                                       ctypes.c_double, _vp, _vp, _u64p]
+        L.dgs_worker_step_static.argtypes = [_u64p, ctypes.c_uint32, _vp, _vp, _vp, ctypes.c_float,
+                                             ctypes.c_float, ctypes.c_double, _vp, _vp, _u64p, _vp]
         L.dgs_server_attach.argtypes = [_vp, _vp]
         L.dgs_server_push.argtypes = [_vp, _vp, ctypes.c_uint32, _vp, _vp, ctypes.c_uint64]
         L.dgs_server_pull.argtypes = [_vp, ctypes.c_uint32, ctypes.c_double, _vp, _vp, _u64p]
@@ -107,6 +110,21 @@ def workspace_bytes(offsets, W: int) -> int:
 
 def _ptr(t) -> int:
     return 0 if t is None else t.data_ptr()
+
+
+def worker_step_static(offsets, grad, state, lr: float, m: float, density: float, idx_out, val_out,
+                       residual_mode: bool = False, stream=None) -> int:
+    """dgs_worker_step_static: the worker step without a context, on the library's static scratch
+    (no device allocation inside the call).  Returns K."""
+    import torch
+    off, p = _offsets_arg(offsets)
+    K = ctypes.c_uint64(0)
+    mom, res = (None, state) if residual_mode else (state, None)
+    st = stream if stream is not None else torch.cuda.current_stream(grad.device)
+    _check(lib().dgs_worker_step_static(p, len(off) - 1, _ptr(grad), _ptr(mom), _ptr(res), lr, m, density,
+                                        _ptr(idx_out), _ptr(val_out), ctypes.byref(K), st.cuda_stream),
+           "dgs_worker_step_static")
+    return int(K.value)
 
 
 @dataclass
