@@ -53,14 +53,17 @@ enum {
     DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
     DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */
     DGS_OPT_STREAM_QUADS = 5,/* 4096-element groups per workgroup of the streaming kernel */
-    DGS_OPT_SEGMENTED = 6,   /* selection of large tensors by the multi-workgroup kernels:
-                                0 automatic (by tensor size and density), 1 every tensor of at
-                                least 65536 elements, 2 never */
-    DGS_OPT_REPAIR_ROUND = 7 /* 1 (default): behind the multi-workgroup selection, enqueue the kernels
-                                that collect again, with a fresh threshold, the tensors whose
-                                predicted threshold failed (they return at once when there is none,
-                                about 20 us per call); 0: such tensors go straight to the slow
-                                single-workgroup selection from the state buffer */
+    DGS_OPT_SEGMENTED = 6,   /* which tensors continue through the multi-kernel chain behind the
+                                selection: 0 automatic (candidate lists too long for one workgroup,
+                                dense requests), 1 every tensor of at least 65536 elements, 2 never */
+    DGS_OPT_REPAIR_ROUND = 7,/* 1 (default): the selection launch carries the workgroups that collect
+                                again, with a fresh threshold, the tensors whose predicted threshold
+                                failed (they wait inside the launch and return at once when their
+                                tensor is fine); 0: such tensors are selected from the state buffer
+                                by one workgroup (slow on large tensors) */
+    DGS_OPT_SPIN_LIMIT = 8   /* polls after which a waiting workgroup of the selection gives up
+                                (default 2^20, far beyond any wait that ends); it is then counted
+                                in dgs_stats.internal_errors */
 };
 
 /* Kernel classes reported by dgs_profile_read(). */
@@ -71,7 +74,7 @@ enum {
     DGS_PROF_PULL_SELECT = 3,
     DGS_PROF_PUSH = 4,
     DGS_PROF_EXACT_EXTRA = 5,   /* second (collecting) pass of the non-predicted path */
-    DGS_PROF_WORKER_SEGMENTED = 6, /* multi-workgroup selection kernels, first begin to last end */
+    DGS_PROF_WORKER_SEGMENTED = 6, /* chain kernels behind the selection, first begin to last end */
     DGS_PROF_PULL_SEGMENTED = 7,
     DGS_PROF_ENCODE = 8,        /* dgs_encode */
     DGS_PROF_DECODE = 9,        /* dgs_decode */
@@ -81,12 +84,12 @@ enum {
 typedef struct dgs_stats {
     uint64_t calls_worker, calls_pull, calls_push;
     uint64_t exact_calls;      /* calls that ran the two-pass (non-predicted) path */
-    uint64_t fallback_tensors; /* tensors whose prediction failed and were re-selected densely */
+    uint64_t fallback_tensors; /* tensors selected from the buffers by one workgroup after everything else failed */
     uint64_t fallback_elems;   /* elements re-read by those */
     uint64_t candidates;       /* candidates collected by streaming passes */
     uint64_t internal_errors;  /* must stay 0 */
-    uint64_t segmented_tensors; /* tensors resolved by the multi-workgroup selection kernels */
-    uint64_t repaired_tensors;  /* of those, after a second collection with a fresh threshold */
+    uint64_t segmented_tensors; /* tensors resolved through the chain kernels */
+    uint64_t repaired_tensors;  /* tensors resolved after a second collection with a fresh threshold */
 } dgs_stats;
 
 /*

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdgs.so")
-SOURCES = ["dgs_stream.hip", "dgs_select.hip", "dgs_segmented.hip", "dgs_server.hip", "dgs_api.hip"]
+SOURCES = ["dgs_stream.hip", "dgs_select.hip", "dgs_chain.hip", "dgs_server.hip", "dgs_api.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",

@@ -24,7 +24,7 @@ size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
     size_t tile_desc, tdesc, plans, tau, hint2, tprev, ghist, tile_cnt, heads, slots, ord, stats, flag;
-    size_t segtab, segcnt, segG1, segQ, segOut, segstate, pfxlist, total;
+    size_t segtab, segcnt, segG1, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -37,13 +37,32 @@ bool check_offsets(const uint64_t *offsets, uint32_t J)
     return true;
 }
 
-// Segments of tensor [off, off + n): its tiles cut into runs of SEG_TILES.
-uint32_t tensor_segments(uint64_t off, uint64_t n)
+// Parts of tensor [off, off + n): its tiles cut into equal runs of `scale` x SEG_TILES tiles
+// (longer runs for a tensor that would otherwise have more than SEG_MAX_PER_TENSOR parts).
+// Every tensor has at least one part.  `scale` grows with the layout (layout_scale) so that
+// the selection launch stays at a few workgroups per compute unit.
+uint32_t part_tiles(uint64_t off, uint64_t n, uint32_t scale)
 {
-    if (n < SEG_MIN_N) return 0;
-    const uint64_t tlo = off / TILE, thi = (off + n - 1) / TILE;
-    const uint64_t nseg = (thi - tlo + 1 + SEG_TILES - 1) / SEG_TILES;
-    return nseg <= SEG_MAX_PER_TENSOR ? (uint32_t)nseg : 0u;
+    const uint64_t nt = (off + n - 1) / TILE - off / TILE + 1;
+    uint64_t per = (uint64_t)SEG_TILES * scale;
+    if ((nt + per - 1) / per > SEG_MAX_PER_TENSOR)
+        per = ((nt + SEG_MAX_PER_TENSOR - 1) / SEG_MAX_PER_TENSOR + SEG_TILES - 1) / SEG_TILES * SEG_TILES;
+    return (uint32_t)per;
+}
+
+uint32_t tensor_segments(uint64_t off, uint64_t n, uint32_t scale)
+{
+    const uint64_t nt = (off + n - 1) / TILE - off / TILE + 1;
+    const uint64_t per = part_tiles(off, n, scale);
+    return (uint32_t)((nt + per - 1) / per);
+}
+
+uint32_t layout_scale(const uint64_t *offsets, uint32_t J)
+{
+    const uint64_t ntiles = (offsets[J] + TILE - 1) / TILE;
+    const uint64_t target = 512ull * SEG_TILES;      // tiles that give about 512 parts
+    const uint64_t s = (ntiles + target - 1) / target;
+    return (uint32_t)(s < 1 ? 1 : (s > 64 ? 64 : s));
 }
 
 Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
@@ -51,10 +70,11 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     const uint64_t n = offsets[J];
     const size_t ntiles = (size_t)((n + TILE - 1) / TILE);
     size_t nseg_total = 0, ncap = 0;
+    const uint32_t scale = layout_scale(offsets, J);
     for (uint32_t j = 0; j < J; ++j) {
-        const uint32_t ns = tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+        const uint32_t ns = tensor_segments(offsets[j], offsets[j + 1] - offsets[j], scale);
         nseg_total += ns;
-        ncap += ns ? 1 : 0;
+        ncap += (offsets[j + 1] - offsets[j] >= SEG_MIN_N) ? 1 : 0;
     }
     Layout L;
     size_t o = 0;
@@ -74,7 +94,6 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
     L.segcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segG1 = o;     o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
-    L.segQ = o;      o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segOut = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint2));
     L.segstate = o;  o = align_up(o + (size_t)J * sizeof(SegState));
     L.pfxlist = o;   o = align_up(o + (ncap * PFX_CAP + 1) * sizeof(uint4));
@@ -137,12 +156,12 @@ struct dgs_ctx {
     DevStats *stats = nullptr;
     uint32_t *flag = nullptr;
     SegDesc *segtab = nullptr;
-    uint32_t *segcnt = nullptr, *segG1 = nullptr, *segQ = nullptr;
+    uint32_t *segcnt = nullptr, *segG1 = nullptr;
     uint2 *segOut = nullptr;
     SegState *segstate = nullptr;
     uint4 *pfxlist = nullptr;
     uint32_t nseg_total = 0;
-    HostArr<uint32_t> nseg;            // per tensor: segments (0 = never segmented)
+    HostArr<uint32_t> nseg;            // per tensor: parts (at least one)
     float *diff = nullptr;
     float *sent = nullptr;             // W rows: what each worker has been sent (model - sent_k form)
     // plan cache
@@ -157,6 +176,7 @@ struct dgs_ctx {
     int margin_pct = 50;
     int seg_mode = SEG_MODE_AUTO;
     bool repair_round = true;
+    uint32_t spin_limit = 1u << 20;    // polls before a waiting workgroup of the selection gives up
     uint32_t stream_quads = 0;         // 0 = automatic
     // host counters
     uint64_t calls_worker = 0, calls_pull = 0, calls_push = 0, exact_calls = 0;
@@ -189,15 +209,15 @@ struct ProfSlot {
 };
 
 // k_j = ceil(density * n_j) in IEEE double; k2 = rank that sets the next predicted threshold.
-// Which tensors take the segmented chain: its launches cost about 55 us whatever it is given,
-// and one workgroup copes with a candidate list of up to one and a half times its LDS list (the
-// rest lives in global scratch) in less than that.  So a tensor goes segmented by itself only if it is very
-// large or its list would exceed that; once the chain runs anyway, every capable tensor whose
-// list outgrows LDS joins it.
+// Which tensors take the chain kernels behind the selection: those of at least SEG_MIN_N
+// elements whose hinted candidate list is longer than one workgroup selects from
+// (SEL_LIST_MAX), and, for a dense request, all of that size (one workgroup would crawl
+// through the tensor itself).
 void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out, uint64_t *K_out,
                uint32_t *nseg_active, uint64_t *wire_words_out)
 {
-    auto plan_with = [&](uint64_t list_limit) -> uint32_t {
+    {
+        const uint64_t list_limit = SEL_LIST_MAX;
         uint64_t K = 0, words = 0;
         uint32_t active = 0;
         for (uint32_t j = 0; j < c->J; ++j) {
@@ -214,12 +234,11 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
             if (k2p > nj) k2p = nj;
             out[j].k2_pull = (uint32_t)k2p;
             bool seg = false;
-            if (c->nseg[j] != 0 && c->seg_mode != SEG_MODE_NEVER) {
+            if (nj >= SEG_MIN_N && c->seg_mode != SEG_MODE_NEVER) {
                 if (density > DENSE_DENSITY)
                     seg = true;   // dense request: the chain reads the tensor itself, one workgroup would crawl
                 else
-                    seg = c->seg_mode == SEG_MODE_ALWAYS || nj >= SEG_AUTO_N ||
-                          (k2 > k2p ? k2 : k2p) > list_limit;
+                    seg = c->seg_mode == SEG_MODE_ALWAYS || (k2 > k2p ? k2 : k2p) > list_limit;
             }
             out[j].seg = seg ? 1u : 0u;
             // wire form: local indices of b bits each, the tensor's block padded to whole words
@@ -236,9 +255,7 @@ void fill_plan(const dgs_ctx *c, double density, int margin_pct, PlanEntry *out,
         *nseg_active = active;
         *K_out = K;
         *wire_words_out = words;
-        return active;
-    };
-    if (plan_with(SEL_LDS_LIST + SEL_LDS_LIST / 2) != 0) plan_with(SEL_LDS_LIST);
+    }
 }
 
 int upload(dgs_ctx *c, void *dst, const void *src, size_t bytes);
@@ -355,16 +372,16 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     sa.lr = lr;
 
     const bool have_seg = c->plan_slot[slot].nseg_active != 0;
+    uint32_t *tprev = c->tprev + (size_t)hint_set * c->J;
     if (dense_req && have_seg) {
         // dense request with large tensors: the accumulate pass also histograms the keys, and
-        // k_pick turns that into a lower bound of each k-th key; the segmented chain then reads
-        // the tensors themselves
+        // k_pick turns that into a lower bound of each k-th key; the chain then reads the
+        // tensors themselves
         ProfSlot ps(c, prof_stream);
         const uint32_t blocks = stream_blocks(c, MODE_HIST, &sa.quads_per_block);
         launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
         ps.launched();
-        launch_pick(c->tdesc, plan, c->ghist, tau, c->tprev + (size_t)hint_set * c->J, c->stats, c->J, c->stream,
-                    nullptr, nullptr);
+        launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, c->stream);
     } else if (dense_req) {
         if (op_stream == OP_FMA) {
             ProfSlot ps(c, prof_stream);
@@ -381,8 +398,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
             ps.launched();
         }
         {
-            launch_pick(c->tdesc, plan, c->ghist, tau, c->tprev + (size_t)hint_set * c->J, c->stats, c->J, c->stream,
-                        nullptr, nullptr);
+            launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, c->stream);
             ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
             StreamArgs sb = sa;
             if (op_again == OP_IDENT) sb.grad = nullptr;
@@ -403,75 +419,42 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.model = (op_stream == OP_SUB) ? grad : nullptr;
     se.tdesc = c->tdesc;
     se.plan = plan;
+    se.segtab = c->segtab;
     se.tau = tau;
     se.tile_cnt = c->tile_cnt;
     se.heads = c->heads;
     se.slots = c->slots;
     se.ord = c->ord;
     se.hint2 = c->hint2 + (size_t)hint_set * c->J;
-    se.tprev = c->tprev + (size_t)hint_set * c->J;
-    se.exact_mode = exact ? 1u : 0u;
+    se.tprev = tprev;
+    se.ghist = c->ghist;
+    se.segstate = c->segstate;
+    se.segcnt = c->segcnt;
+    se.segG1 = c->segG1;
+    se.segOut = c->segOut;
+    se.pfxlist = c->pfxlist;
     se.out_idx = idx_out;
     se.out_val = val_out;
     se.stats = c->stats;
+    se.toff = c->toff;
     se.m = m;
-    se.force_dense = dense_req ? 1u : 0u;
+    se.n = c->n;
+    se.ntiles = c->ntiles;
+    se.J = c->J;
+    se.nparts = c->nseg_total;
+    se.dense = dense_req ? 1u : 0u;
     se.write_hint = dense_req ? 0u : 1u;
-    se.segstate = c->segstate;
-    if (have_seg) {
-        SegArgs sg{};
-        sg.state = state;
-        sg.model = se.model;
-        sg.tdesc = c->tdesc;
-        sg.plan = plan;
-        sg.segtab = c->segtab;
-        sg.tau = tau;
-        sg.hint2 = se.hint2;
-        sg.tprev = se.tprev;
-        sg.tile_cnt = c->tile_cnt;
-        sg.heads = c->heads;
-        sg.slots = c->slots;
-        sg.ord = c->ord;
-        sg.whist = c->ghist;
-        sg.segstate = c->segstate;
-        sg.segcnt = c->segcnt;
-        sg.segG1 = c->segG1;
-        sg.segQ = c->segQ;
-        sg.segOut = c->segOut;
-        sg.pfxlist = c->pfxlist;
-        sg.out_idx = idx_out;
-        sg.out_val = val_out;
-        sg.stats = c->stats;
-        sg.m = m;
-        sg.write_hint = dense_req ? 0u : 1u;
-        sg.dense = dense_req ? 1u : 0u;
-        sg.exact_mode = exact ? 1u : 0u;
-        sg.nseg_total = c->nseg_total;
-        sg.J = c->J;
-        sg.round = 0;
-        sg.pending = c->flag + 8;
-        se.pending = sg.pending;
-        sg.repair = c->repair_round ? 1u : 0u;
-        ProfSlot ps(c, prof_seg);
-        launch_segmented(op_select, sg, c->stream, ps.ev0, c->repair_round ? nullptr : ps.ev1);
-        // repair round for the tensors whose prediction failed: collect again from `state`
-        // with a threshold taken from a fresh histogram, then the same chain once more
-        // (all of these kernels return at once when nothing is pending)
-        if (c->repair_round) {
-            if (!dense_req) {   // a dense request has no candidate lists to collect again
-                StreamArgs sr = sa;
-                if (op_again == OP_IDENT) sr.grad = nullptr;
-                launch_seg_recollect(op_again, sr, op_again == OP_IDENT ? aligned16(state) : vec, sg, c->stream);
-            }
-            sg.round = 1;
-            sg.exact_mode = 1u;
-            launch_segmented(op_select, sg, c->stream, nullptr, ps.ev1);
-        }
-        ps.launched();
-    }
+    se.exact_mode = exact ? 1u : 0u;
+    se.repair = (c->repair_round && !dense_req) ? 1u : 0u;   // a dense request has no lists to collect again
+    se.spin_limit = c->spin_limit;
     {
         ProfSlot ps(c, prof_select);
-        launch_select(op_select, se, c->J, c->stream, ps.ev0, ps.ev1);
+        launch_select(op_select, se, c->stream, ps.ev0, ps.ev1);
+        ps.launched();
+    }
+    if (have_seg) {
+        ProfSlot ps(c, prof_seg);
+        launch_chain(op_select, se, c->stream, ps.ev0, ps.ev1);
         ps.launched();
     }
     if (!dense_req) c->hint_density[hint_set] = density;
@@ -501,7 +484,6 @@ void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
     c->segtab = (SegDesc *)(c->ws + L.segtab);
     c->segcnt = (uint32_t *)(c->ws + L.segcnt);
     c->segG1 = (uint32_t *)(c->ws + L.segG1);
-    c->segQ = (uint32_t *)(c->ws + L.segQ);
     c->segOut = (uint2 *)(c->ws + L.segOut);
     c->segstate = (SegState *)(c->ws + L.segstate);
     c->pfxlist = (uint4 *)(c->ws + L.pfxlist);
@@ -513,22 +495,24 @@ void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, Seg
 {
     const uint32_t J = c->J, W = c->W;
     uint32_t pfx_slots = 0, nsegs = 0;
+    const uint32_t scale = layout_scale(&c->offsets[0], J);
     for (uint32_t j = 0; j < J; ++j) {
         td[j].off = (uint32_t)c->offsets[j];
         td[j].n = (uint32_t)(c->offsets[j + 1] - c->offsets[j]);
         td[j].big = td[j].n > SMALL_N ? 1u : 0u;
         td[j].pad0 = td[j].pad1 = 0;
-        const uint32_t ns = tensor_segments(c->offsets[j], c->offsets[j + 1] - c->offsets[j]);
+        const uint32_t ns = tensor_segments(c->offsets[j], c->offsets[j + 1] - c->offsets[j], scale);
+        const uint32_t per = part_tiles(c->offsets[j], c->offsets[j + 1] - c->offsets[j], scale);
         td[j].seg_first = nsegs;
         td[j].nseg = ns;
-        td[j].pfx_slot = ns ? pfx_slots++ : 0u;
+        td[j].pfx_slot = (td[j].n >= SEG_MIN_N) ? pfx_slots++ : 0u;
         c->nseg[j] = ns;
         const uint32_t tlo = td[j].off / TILE, thi = (td[j].off + td[j].n - 1) / TILE;
         for (uint32_t sidx = 0; sidx < ns; ++sidx) {
             SegDesc d;
             d.j = j;
-            d.tile0 = tlo + sidx * SEG_TILES;
-            d.ntiles = (thi + 1 - d.tile0 < SEG_TILES) ? (thi + 1 - d.tile0) : SEG_TILES;
+            d.tile0 = tlo + sidx * per;
+            d.ntiles = (thi + 1 - d.tile0 < per) ? (thi + 1 - d.tile0) : per;
             d.sidx = sidx;
             segs[nsegs++] = d;
         }
@@ -627,7 +611,8 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
 
     // host-side plan: tensor and tile descriptors
     uint32_t nseg_total = 0;
-    for (uint32_t j = 0; j < J; ++j) nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+    for (uint32_t j = 0; j < J; ++j)
+        nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j], layout_scale(offsets, J));
     std::vector<TensorDesc> td(J);
     std::vector<uint32_t> tau0((size_t)(W + 1) * J);
     std::vector<SegDesc> segs(nseg_total + 1);
@@ -750,7 +735,8 @@ int dgs_worker_step_static(const uint64_t *offsets, uint32_t J, const float *gra
     const Layout L = make_layout(offsets, J, 0);
     if (L.total > DGS_STATIC_SCRATCH_BYTES) return DGS_ECAPACITY;
     uint32_t nseg_total = 0;
-    for (uint32_t j = 0; j < J; ++j) nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j]);
+    for (uint32_t j = 0; j < J; ++j)
+        nseg_total += tensor_segments(offsets[j], offsets[j + 1] - offsets[j], layout_scale(offsets, J));
     if (nseg_total > STATIC_MAX_SEGS) return DGS_ECAPACITY;
     void *ws = nullptr;
     int rc = static_scratch(&ws);
@@ -1014,6 +1000,10 @@ int dgs_set_option(dgs_ctx *c, int option, int64_t value)
         c->seg_mode = (int)value;
         return DGS_OK;
     case DGS_OPT_REPAIR_ROUND: c->repair_round = value != 0; return DGS_OK;
+    case DGS_OPT_SPIN_LIMIT:
+        if (value < 1 || value > (1ll << 30)) return DGS_EINVAL;
+        c->spin_limit = (uint32_t)value;
+        return DGS_OK;
     case DGS_OPT_STREAM_QUADS:
         if (value < 0 || value > (1 << 20)) return DGS_EINVAL;
         c->stream_quads = (uint32_t)value;

@@ -34,29 +34,35 @@ constexpr uint32_t HSHIFT = 31 - HBITS;
 // Selection workgroup.
 constexpr uint32_t SEL_THREADS = 1024;
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
-constexpr uint32_t SEL_LDS_LIST = 16384;           // candidates kept in LDS (128 KB)
+constexpr uint32_t SEL_LDS_LIST = 8192;            // candidates kept in LDS (64 KB); longer lists continue in global scratch
+constexpr uint32_t SEL_LIST_MAX = 24576;           // longest candidate list one workgroup selects from
 // Above this density candidates stop paying off; such requests select densely.
 constexpr double DENSE_DENSITY = 1.0 / 32.0;
 
-// Segmented selection: tensors too large (or requests too dense) for one workgroup
-// are cut into segments of SEG_TILES tiles, and the exact selection runs as a chain
-// of short kernels with one workgroup per segment.
-constexpr uint32_t SEG_TILES = 256;
+// Parts.  Every tensor is cut into parts of up to SEG_TILES tiles, one workgroup each: a part
+// joins its tiles' candidates into one ordered list, and the workgroup that arrives last for a
+// tensor selects from the parts' lists.  Tensors whose candidate lists outgrow one workgroup
+// (or whose request is dense) continue through the chain kernels, one workgroup per part.
+#ifndef DGS_SEG_TILES          // (a CPU test build shrinks the parts so that small layouts have several)
+#define DGS_SEG_TILES 256
+#endif
+constexpr uint32_t SEG_TILES = DGS_SEG_TILES;
 constexpr uint32_t SEG_THREADS = 256;
-constexpr uint32_t SEG_MIN_N = 65536;              // smaller tensors never go segmented
-constexpr uint32_t SEG_AUTO_N = 1u << 22;          // tensors this large always do
+constexpr uint32_t SEG_MIN_N = 65536;              // smaller tensors never take the chain
+constexpr uint32_t SEG_AUTO_N = 1u << 22;          // (kept for the plan: tensors this large always may)
 constexpr uint32_t SEG_LOWBITS = 12;               // key bits resolved by the second level
 constexpr uint32_t SEG_WBINS = 2048;               // window of key >> SEG_LOWBITS above the threshold
 constexpr uint32_t SEG_LBINS = 1u << SEG_LOWBITS;
 constexpr uint32_t PFX_CAP = 8192;                 // candidates sharing the k-th key's prefix, per tensor
-constexpr uint32_t SEG_MAX_PER_TENSOR = 8192;      // per-segment counters kept in LDS by the ranking kernel
-// SEG_ACTIVE + r: being resolved by round r of the chain (0 = first attempt, 1 = repair);
-// SEG_PENDING: the first attempt failed, the repair round collects again with a threshold
-// taken from a fresh histogram; SEG_COUNT: the k-th key is known but too many entries share
-// its prefix, the repair round counts the segments against it; SEG_ALL: k_j = n_j, every element
-// is sent; SEG_FALLBACK / SEG_ZEROFILL: left to k_select.
-enum SegStatus { SEG_IDLE = 0, SEG_FALLBACK = 2, SEG_ZEROFILL = 3, SEG_PENDING = 4, SEG_COUNT = 5, SEG_ALL = 6,
-                 SEG_ACTIVE = 8 };
+constexpr uint32_t SEG_MAX_PER_TENSOR = 1024;      // parts per tensor whose list positions fit the selection's LDS
+// Status of a tensor inside one selection call.
+//   SEG_IDLE      nothing decided yet
+//   SEG_DONE      selected and emitted
+//   SEG_ACTIVE    the chain kernels finish it (prefix of the k-th key known)
+//   SEG_ALL       k_j = n_j: the chain's emission sends every element
+//   SEG_PENDING   the prediction failed: the parts collect again with a fresh threshold
+//   SEG_FALLBACK  left to the dense single-workgroup selection
+enum SegStatus { SEG_IDLE = 0, SEG_DONE = 1, SEG_FALLBACK = 2, SEG_PENDING = 4, SEG_ALL = 6, SEG_ACTIVE = 8 };
 enum SegMode { SEG_MODE_AUTO = 0, SEG_MODE_ALWAYS = 1, SEG_MODE_NEVER = 2 };
 
 struct TensorDesc {
@@ -87,14 +93,18 @@ struct SegDesc {
     uint32_t sidx;    // index of the segment within its tensor
 };
 
-struct SegState {        // per tensor, rewritten by every segmented selection
+struct SegState {        // per tensor, rewritten by every selection
     uint32_t status;     // SegStatus
     uint32_t pfx;        // key >> SEG_LOWBITS of the k-th entry
     uint32_t r2;         // its rank among the entries sharing that prefix
     uint32_t T;          // the k-th key
     uint32_t pfxcount;   // entries appended to the prefix list
-    uint32_t ovf;        // a tile of the tensor overflowed its candidate slots
-    uint32_t pad0, pad1;
+    uint32_t pad0, pad1, pad2;
+    // Hand-over between the workgroups of one launch (all zero between launches):
+    uint32_t arrive[4];  // parts that have finished: [0] join, [1] re-histogram, [2] re-collection, [3] chain prefix
+    uint32_t verdict;    // 0 = not decided; else 0x100 | SegStatus, written by the last joining part
+    uint32_t tau_ready;  // 1: the fresh threshold of a pending tensor is in place
+    uint32_t seen[2];    // readers of verdict / tau_ready that have passed (the last one clears)
 };
 
 struct DevStats {
@@ -132,54 +142,32 @@ struct SelectArgs {
     const float *model;           // SEL_PULL_V only: values are model - state
     const TensorDesc *tdesc;
     const PlanEntry *plan;
+    const SegDesc *segtab;        // the parts, tensor after tensor
     uint32_t *tau;                // hints of this stream, updated
-    const uint32_t *tile_cnt;
-    const uint2 *heads;
-    const uint2 *slots;
-    uint2 *ord;                   // ordered candidates of tensor j start at CAPT * (first tile + j)
+    uint32_t *tile_cnt;
+    uint2 *heads;
+    uint2 *slots;
+    uint2 *ord;                   // ordered candidates of a part start at CAPT * (tile0 + j)
     uint32_t *hint2;              // per tensor: candidates expected at the hinted threshold (0 = unknown)
     uint32_t *tprev;              // per tensor: k-th key of the previous selection on this stream (0 = unknown)
-    uint32_t *out_idx;
-    float *out_val;
-    DevStats *stats;
-    float m;                      // SEL_WORKER: sent entries keep m * a
-    uint32_t force_dense;         // select every tensor straight from `state`
-    uint32_t write_hint;
-    uint32_t exact_mode;          // the threshold came from this step's histogram
-    const SegState *segstate;     // tensors planned as segmented are skipped unless they fell back
-    uint32_t *pending;            // cleared for the next call
-};
-
-struct SegArgs {
-    float *state;
-    const float *model;           // SEL_PULL_V only
-    const TensorDesc *tdesc;
-    const PlanEntry *plan;
-    const SegDesc *segtab;
-    uint32_t *tau;                // hints of this stream, updated
-    uint32_t *hint2;
-    uint32_t *tprev;              // per tensor: k-th key of the previous selection on this stream
-    const uint32_t *tile_cnt;
-    const uint2 *heads;
-    const uint2 *slots;
-    uint2 *ord;                   // ordered candidates of a segment start at CAPT * (tile0 + j)
-    uint32_t *whist;              // per tensor HBINS counters, all zero between uses (first SEG_WBINS used)
+    uint32_t *ghist;              // per tensor HBINS counters, all zero between uses
     SegState *segstate;
-    uint32_t *segcnt;             // per segment: candidates
-    uint32_t *segG1;              // per segment: candidates with a larger key prefix than the k-th
-    uint32_t *segQ;               // per segment: candidates equal to the k-th key (SEG_COUNT only)
-    uint2 *segOut;                // per segment: (output position within the tensor, ties to take)
-    uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, segment, 0)
+    uint32_t *segcnt;             // per part: candidates (bit 31: a tile of the part overflowed)
+    uint32_t *segG1;              // per part: candidates with a larger key prefix than the k-th
+    uint2 *segOut;                // per part: (output position within the tensor, ties to take)
+    uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, part, 0)
     uint32_t *out_idx;
     float *out_val;
     DevStats *stats;
-    float m;
-    uint32_t write_hint, exact_mode, nseg_total, J;
-    uint32_t round;               // 0: first attempt, 1: repair of the tensors left SEG_PENDING
-    uint32_t repair;              // a repair round follows round 0 (else failures go straight to k_select)
-    uint32_t dense;               // dense request: no candidate lists, the chain reads the tensor itself
-                                  // (every element with key >= tau, tau from this call's histogram)
-    uint32_t *pending;            // number of tensors left SEG_PENDING by round 0 (reset by k_select)
+    const uint32_t *toff;         // J + 1 tensor offsets
+    float m;                      // SEL_WORKER: sent entries keep m * a
+    uint32_t n, ntiles, J, nparts;
+    uint32_t dense;               // dense request: no candidate lists; tensors with parts take the chain
+                                  // reading their own elements, the others select from the state buffer
+    uint32_t write_hint;
+    uint32_t exact_mode;          // the threshold came from this call's histogram
+    uint32_t repair;              // the launch carries the re-collecting workgroups
+    uint32_t spin_limit;          // polls before a waiting workgroup gives up
 };
 
 // Host-callable launchers (defined next to the kernels).
@@ -187,14 +175,12 @@ struct SegArgs {
 void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream,
                    void *ev0, void *ev1);
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream, const SegState *only_pending,
-                 const uint32_t *pending);
-// Repair round, first half: histogram pass, pick and collecting pass over the segments
-// of the tensors left SEG_PENDING (reads `state` only).
-void launch_seg_recollect(int op, const StreamArgs &a, bool vec, const SegArgs &g, void *stream);
-void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1);
-// The five kernels of the segmented selection, in order, on `stream`.
-void launch_segmented(int op, const SegArgs &a, void *stream, void *ev0, void *ev1);
+                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream);
+// The selection: one launch for every tensor (join, exact k-th key, ordered emission, state
+// fix-up, next hint; failed predictions are collected again inside the same launch).
+void launch_select(int op, const SelectArgs &a, void *stream, void *ev0, void *ev1);
+// What remains for tensors left SEG_ACTIVE / SEG_ALL (very long candidate lists, dense requests).
+void launch_chain(int op, const SelectArgs &a, void *stream, void *ev0, void *ev1);
 void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32_t *idx,
                  const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1);
 void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t *flag, void *stream);

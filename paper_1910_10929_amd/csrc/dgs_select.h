@@ -28,6 +28,15 @@ __device__ __forceinline__ void fix_sent(float *state, uint32_t ix, float val, f
     else store_scattered(&state[ix], state[ix] + val);
 }
 
+// An index that came out of a candidate list is used as an address: one outside the buffer
+// (a corrupted list) is counted as an internal error and never dereferenced.
+__device__ __forceinline__ bool index_ok(const SelectArgs &A, uint32_t ix)
+{
+    if (ix < A.n) return true;
+    atomicAdd(&A.stats->internal_errors, 1ull);
+    return false;
+}
+
 template <int OP>
 struct SrcDense {          // the tensor itself: position p <-> element off + p
     static constexpr bool AGG = false;
@@ -331,8 +340,8 @@ __device__ __forceinline__ void select_emit(const Src src, const uint32_t cN, co
                 ix[i] = 0;
                 if (sel) {
                     if (pos < k) {
-                        at[i] = pos;
                         ix[i] = src.index(p);
+                        if (index_ok(A, ix[i])) at[i] = pos;
                     }
                     ++pos;
                 }
@@ -424,8 +433,8 @@ __device__ __forceinline__ uint32_t hint_relaxed(uint32_t tau_cur, uint32_t kmin
 // add and candidate i (in index order) at x_i, the zeros below x_i number x_i - off - i;
 // the P candidates for which that is < z lie inside the leading run [off, off + z + P),
 // which is sent whole (z zeros and P candidates); the other candidates follow.
-template <int OP>
-__device__ __forceinline__ void zero_fill_emit(const SrcList src, const uint32_t c, const TensorDesc &td,
+template <int OP, class Src>
+__device__ __forceinline__ void zero_fill_emit(const Src src, const uint32_t c, const TensorDesc &td,
                                                const PlanEntry &pe, const SelectArgs &A, uint32_t *wsum)
 {
     const uint32_t tid = threadIdx.x;
@@ -446,7 +455,7 @@ __device__ __forceinline__ void zero_fill_emit(const SrcList src, const uint32_t
         const float v = __uint_as_float(src.bits(p));
         A.out_idx[pe.outoff + z + p] = ix;
         A.out_val[pe.outoff + z + p] = v;
-        fix_sent<OP>(A.state, ix, v, A.m);
+        if (index_ok(A, ix)) fix_sent<OP>(A.state, ix, v, A.m);
     }
 }
 

@@ -1,20 +1,48 @@
-// Pick (histogram -> candidate threshold) and the single-workgroup selection of libdgs.
+// Pick (histogram -> candidate threshold) and the selection kernel of libdgs: per tensor the
+// exact k-th largest magnitude with the lowest-index tie rule ("thr <- R% of |x|" in
+// Algorithms 1-3), the ordered emission ("encode()"), the state fix-up (Eq. 12 / Eq. 6) and
+// the next threshold hint -- all tensors in one launch.
 #include "dgs_select.h"
 
 namespace dgs {
 
 // ---------------------------------------------------------------------------
-// pick: streaming-pass histogram -> candidate threshold (non-predicted path)
+// pick: key histogram (bits [30:19], nonzero keys only) -> candidate threshold
 // ---------------------------------------------------------------------------
+
+// h: HBINS counters in LDS.  Thread 0 receives the threshold whose candidates number at
+// least pe.k2 (or every nonzero when there are fewer), and the middle of the bucket that holds
+// the k-th key (anchors the window histograms).  Contains find_ranks' three barriers.
+template <int NW>
+__device__ __forceinline__ void pick_from_hist(const uint32_t *h, const PlanEntry &pe, uint32_t *rowsum, int *res,
+                                               uint32_t &tau_out, uint32_t &tprev_out)
+{
+    find_ranks<HBINS, NW>(h, pe.k2, pe.k, 0u, rowsum, res);
+    const int b2 = res[0], b1 = res[2];
+    // the histogram holds the nonzero keys only: a rank beyond its total means
+    // "fewer nonzeros than that", and every nonzero is collected
+    uint32_t t;
+    if (b2 < 0 && b1 < 0) {
+        t = 1;
+    } else if (b2 < 0) {
+        t = (b1 > 0) ? (1u << HSHIFT) : 1u;
+    } else if (b2 > 0) {
+        t = (uint32_t)b2 << HSHIFT;
+    } else if (b1 > 0) {
+        t = 1u << HSHIFT;
+    } else {
+        t = 1;   // the k-th key is tiny or zero: collect every nonzero
+    }
+    tau_out = t;
+    tprev_out = (b1 >= 0) ? (((uint32_t)b1 << HSHIFT) + (1u << (HSHIFT - 1))) : 0u;
+}
 
 __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const PlanEntry *plan,
                                               uint32_t *ghist, uint32_t *tau, uint32_t *tprev,
-                                              DevStats *stats, const SegState *only_pending,
-                                              const uint32_t *pending)
+                                              DevStats *stats)
 {
     const uint32_t j = blockIdx.x;
     if (!tdesc[j].big) return;
-    if (only_pending && (*pending == 0 || only_pending[j].status != SEG_PENDING)) return;
     __shared__ uint32_t h[HBINS];
     __shared__ uint32_t rowsum[64];
     __shared__ int res[6];
@@ -24,283 +52,426 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
         g[b] = 0;   // leave the histogram clean for the next use
     }
     const PlanEntry pe = plan[j];
-    find_ranks<HBINS, 4>(h, pe.k2, pe.k, 0u, rowsum, res);
+    uint32_t t, tp;
+    pick_from_hist<4>(h, pe, rowsum, res, t, tp);
     if (threadIdx.x == 0) {
-        const int b2 = res[0], b1 = res[2];
-        // the histogram holds the nonzero keys only: a rank beyond its total means
-        // "fewer nonzeros than that", and every nonzero is collected
-        uint32_t t;
-        if (b2 < 0 && b1 < 0) {
-            t = 1;
-        } else if (b2 < 0) {
-            t = (b1 > 0) ? (1u << HSHIFT) : 1u;
-        } else if (b2 > 0) {
-            t = (uint32_t)b2 << HSHIFT;
-        } else if (b1 > 0) {
-            t = 1u << HSHIFT;
-        } else {
-            t = 1;   // the k-th key is tiny or zero: collect every nonzero
-        }
         tau[j] = t;
-        // where the k-th key lies (middle of its bucket): anchors the window histogram of
-        // the segmented selection
-        tprev[j] = (b1 >= 0) ? (((uint32_t)b1 << HSHIFT) + (1u << (HSHIFT - 1))) : 0u;
+        tprev[j] = tp;
     }
 }
 
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream, const SegState *only_pending,
-                 const uint32_t *pending)
+                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream)
 {
     hipLaunchKernelGGL(k_pick, dim3(J), dim3(256), 0, (hipStream_t)stream, tdesc, plan, ghist, tau, tprev,
-                       stats, only_pending, pending);
+                       stats);
 }
 
-constexpr uint32_t SEL_ROWS = 12;                                  // rows of 16 tiles per wavefront and batch
-constexpr uint32_t SEL_CNT_LOADS = (SEL_ROWS + 3) / 4;             // count loads per lane, 64 tiles each
-constexpr uint32_t SEL_WAVE_TILES = SEL_ROWS * 16;                 // 192
-constexpr uint32_t SEL_BATCH_TILES = SEL_WAVES * SEL_WAVE_TILES;   // 3072
-
-// One workgroup per tensor.  Big tensors: join the per-tile candidate slots into
-// one ordered list (LDS; lists that outgrow it continue in global scratch), then
-// select on the list; if the list is short or a tile overflowed, select densely
-// from the state buffer.  Small tensors always select densely.
+// ---------------------------------------------------------------------------
+// the selection kernel
+// ---------------------------------------------------------------------------
 //
-// The join: a batch of tiles is dealt out to the wavefronts in equal runs of whole
-// rows (16 consecutive tiles).  A wavefront fetches the counts of its run, one tile
-// per lane, and the first line of every tile (its first 8 candidates), 4 lanes per
-// tile and a row per load, before the counts are known.  Counts are handed to the
-// tiles' lanes by lane permutation and scanned row by row in registers; one exchange
-// of the wavefronts' totals through LDS gives every tile its list position, and the
-// lanes drop their two entries into place.  Tiles with more than 8 candidates, and a
-// first tile shared with the previous tensor, take a per-tile loop.
-template <int OP>
-__global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
-                                                        const uint32_t *__restrict__ tile_cnt,
-                                                        const uint2 *__restrict__ heads,
-                                                        const uint2 *__restrict__ slots)
+// Grid: block b < P is the JOIN of part b (1024 threads).  With the re-collecting roles
+// enabled, ceil(P / B_GROUP) RE-HISTOGRAM blocks follow, then as many RE-COLLECTION blocks,
+// each looking after B_GROUP consecutive parts in turn (they act on tensors of several parts
+// whose prediction failed, and pass over everything else).
+//
+//   JOIN      compacts the candidates the streaming pass left in the part's tiles into one
+//             ordered list.  The workgroup that arrives last for a tensor (the only one, for a
+//             tensor of one part) gathers the parts' lists and SELECTS: exact k-th key, ordered
+//             emission, state fix-up, next hint.  A tensor planned for the chain kernels only
+//             gets its key window resolved here.  If the prediction failed (fewer candidates
+//             than k, an overflowed tile, a list beyond one workgroup's reach) the tensor is
+//             left pending: a tensor of one part is collected again on the spot, for the others
+//             the verdict releases the waiting roles.
+//   RE-HISTOGRAM  every part counts the keys of its own elements; the last one derives a fresh
+//             threshold and publishes it.
+//   RE-COLLECTION every part compacts its elements at or above that threshold straight from
+//             the buffers into its list; the last one selects as above.  What still fails then
+//             (one value filling the tensor, say) is selected from the buffers by that one
+//             workgroup -- slow, never wrong.
+//
+// Waiting is only ever for blocks with a lower index, which the hardware dispatches first,
+// and every wait is bounded (A.spin_limit polls).
+
+constexpr uint32_t B_GROUP = 8;   // parts looked after by one re-collecting workgroup
+
+struct PartShared {
+    SelShared S;
+    uint32_t pbase[SEG_MAX_PER_TENSOR + 1];   // first list position of every part of the tensor
+    uint32_t wtot[SEL_WAVES];
+    uint32_t bc;
+};
+
+// Entry e of a crowded or border tile: heads for q < HEAD, slots beyond.
+__device__ __forceinline__ uint2 tile_entry(const uint2 *hd, const uint2 *sl, uint32_t q)
 {
-    __shared__ SelShared S;
-    __shared__ uint2 llist[SEL_LDS_LIST];
-    const uint32_t j = blockIdx.x;
+    return (q < HEAD) ? hd[q] : sl[q];
+}
+
+// JOIN of one part: the candidates of tensor j in tiles [sd.tile0, sd.tile0 + sd.ntiles), in
+// index order, through `put(position, entry)`.  Returns the count; `ovf` is set if a tile had
+// overflowed its slots.  Rounds of 256 tiles: four lanes per tile fetch its count and its
+// first line (8 candidates) at once; a workgroup scan of the counts gives every tile its list
+// position; crowded tiles and a first tile shared with the previous tensor take a per-entry loop.
+template <class Put>
+__device__ __forceinline__ uint32_t join_part(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd,
+                                              PartShared &P, bool &ovf_out, Put put)
+{
     const uint32_t tid = threadIdx.x;
-    const TensorDesc td = A.tdesc[j];
-    const PlanEntry pe = A.plan[j];
     const uint32_t tlo = td.off / TILE;
-    const uint32_t thi = (td.off + td.n - 1) / TILE;
-    const bool head_shared = (td.off % TILE) != 0;   // first tile starts inside an earlier tensor
-    bool dense = (!td.big) || A.force_dense;
-    if (j == 0 && tid == 0 && A.pending) *A.pending = 0;   // every reader of this call has finished
-    if (pe.seg) {
-        // planned for the segmented kernels; only a tensor they handed over is taken here
-        const uint32_t status = A.segstate[j].status;
-        if (status == SEG_FALLBACK) dense = true;
-        else if (status != SEG_ZEROFILL) return;
-    }
-    bool zerofill = false;
-    uint32_t c = 0;
-    uint32_t kmin = 0xFFFFFFFFu;                     // smallest candidate key
-    const uint32_t tau_cur = td.big ? A.tau[j] : TAU_NEVER;
-    const uint32_t hint2_cur = (td.big && A.write_hint) ? A.hint2[j] : 0u;
-    // The join counts the entries into the window histogram as it places them.  Every candidate
-    // key is >= the collection threshold, so the window starts there -- or, when that lies far
-    // below (a relaxed hint), 1024 buckets under the k-th key of the previous call.
-    const uint32_t tprev_cur = td.big ? A.tprev[j] : 0u;
-    const uint32_t win_join = max(tau_cur >> 11, max(tprev_cur >> 11, 1024u) - 1024u);
-    uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;   // this tensor's ordered list in global scratch
-    if (tid == 0) S.kmin = 0xFFFFFFFFu;
-
-    if (!dense) {
-        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) S.h[b] = 0;   // complete before the join's barrier
-        const uint32_t ntl = thi - tlo + 1;
-        const uint32_t lane = lane_id(), wave = tid >> 6;
-        const uint32_t qw = lane >> 2, sub = lane & 3u;
-        uint32_t ovf = 0;
-        auto join_batch = [&](const uint32_t cb) __attribute__((always_inline)) {
-            const uint32_t nb = min(ntl - cb, SEL_BATCH_TILES);
-            const uint32_t rows = (nb + 16 * SEL_WAVES - 1) / (16 * SEL_WAVES);   // per wavefront, 1..SEL_ROWS
-            const uint32_t w0 = cb + wave * rows * 16;                            // first tile of this wavefront's run
-            // counts of the run, one tile per lane and load
-            uint32_t w[SEL_CNT_LOADS];
-#pragma unroll
-            for (uint32_t u = 0; u < SEL_CNT_LOADS; ++u) {
-                const uint32_t sl = u * 64 + lane;
-                w[u] = (sl < rows * 16 && w0 + sl < ntl) ? tile_cnt[tlo + w0 + sl] : 0u;
-            }
-            // first line of every tile of the run
-            uint4 pf[SEL_ROWS];
-#pragma unroll
-            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
-                const uint32_t tl = w0 + it * 16 + qw;
-                pf[it] = make_uint4(0, 0, 0, 0);
-                if (it < rows && tl < ntl) pf[it] = ((const uint4 *)(heads + (size_t)(tlo + tl) * HEAD))[sub];
-            }
-            // a first tile shared with the previous tensor: that tensor's candidates come first
-            uint32_t start0 = 0;
-            if (head_shared && w0 == 0) {
-                const uint32_t ww = (uint32_t)__builtin_amdgcn_readfirstlane((int)w[0]);
-                if (ww != CNT_OVERFLOW) {
-                    start0 = ww & 0xFFFFu;
-                    if (lane == 0) w[0] = ww >> 16;
-                }
-            }
-#pragma unroll
-            for (uint32_t u = 0; u < SEL_CNT_LOADS; ++u) {
-                if (w[u] == CNT_OVERFLOW) { ovf = 1; w[u] = 0; }
-                else if (!(head_shared && w0 == 0 && u == 0 && lane == 0)) w[u] &= 0xFFFFu;
-            }
-            // positions inside the run: the counts go to the tiles' lanes, rows are scanned in turn
-            // (per tile: count in the low half, position in the high half -- a run holds at
-            // most 192 * CAPT entries)
-            uint32_t cp[SEL_ROWS];
-            uint32_t run = 0;
-#pragma unroll
-            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
-                cp[it] = 0;
-                if (it < rows) {                                                  // uniform
-                    const uint32_t n_t = (uint32_t)__builtin_amdgcn_ds_bpermute(
-                        (int)((((it & 3u) * 16u) + qw) * 4u), (int)w[it >> 2]);
-                    const uint32_t incl = wave_incl_scan(sub == 0 ? n_t : 0u);    // over the row's tiles
-                    cp[it] = n_t | ((run + incl - n_t) << 16);
-                    run += (uint32_t)__builtin_amdgcn_readlane((int)incl, 63);
-                }
-            }
-            if (lane == 0) S.wsum[wave] = run;
-            __syncthreads();
-            uint32_t before = 0, tot = 0;
-#pragma unroll
-            for (uint32_t x = 0; x < SEL_WAVES; ++x) {
-                const uint32_t v = S.wsum[x];
-                if (x < wave) before += v;
-                tot += v;
-            }
-            const uint32_t base = c + before;
-            c += tot;
-            // entries into place
-#pragma unroll
-            for (uint32_t it = 0; it < SEL_ROWS; ++it) {
-                const uint32_t tl = w0 + it * 16 + qw;
-                const uint32_t n_t = cp[it] & 0xFFFFu;
-                if (n_t == 0) continue;
-                const uint32_t start = (tl == 0) ? start0 : 0u;
-                const uint32_t pos = base + (cp[it] >> 16);
-                uint32_t i0 = 0;
-                if (start == 0) {
-                    if (2 * sub < n_t) {
-                        put_entry(llist, glist, pos + 2 * sub, make_uint2(pf[it].x, pf[it].y));
-                        kmin = min(kmin, pf[it].y & 0x7FFFFFFFu);
-                        window_count(S.h, win_join, pf[it].y & 0x7FFFFFFFu);
-                    }
-                    if (2 * sub + 1 < n_t) {
-                        put_entry(llist, glist, pos + 2 * sub + 1, make_uint2(pf[it].z, pf[it].w));
-                        kmin = min(kmin, pf[it].w & 0x7FFFFFFFu);
-                        window_count(S.h, win_join, pf[it].w & 0x7FFFFFFFu);
-                    }
-                    i0 = HEAD;
-                }
-                if (i0 < n_t) {
-                    // the rest of a crowded tile: the four lanes interleave, each with four
-                    // independent loads at a time (entry q of the tile: heads for q < HEAD,
-                    // slots beyond)
-                    const uint2 *hd = heads + (size_t)(tlo + tl) * HEAD;
-                    const uint2 *sl = slots + (size_t)(tlo + tl) * CAPT;
-                    for (uint32_t i = i0 + sub; i < n_t; i += 16) {
-                        uint2 e[4];
-#pragma unroll
-                        for (uint32_t v = 0; v < 4; ++v) {
-                            const uint32_t q = start + i + 4 * v;
-                            e[v] = (i + 4 * v < n_t) ? ((q < HEAD) ? hd[q] : sl[q]) : make_uint2(0, 0);
-                        }
-#pragma unroll
-                        for (uint32_t v = 0; v < 4; ++v) {
-                            if (i + 4 * v < n_t) {
-                                put_entry(llist, glist, pos + i + 4 * v, e[v]);
-                                kmin = min(kmin, e[v].y & 0x7FFFFFFFu);
-                                window_count(S.h, win_join, e[v].y & 0x7FFFFFFFu);
-                            }
-                        }
-                    }
-                }
-            }
-        };
-        // the first batch (up to 3072 tiles: all there is, as a rule) stands outside the loop, so
-        // that what the loop keeps in registers across its rounds does not weigh on it
-        join_batch(0);
-        for (uint32_t cb = SEL_BATCH_TILES; cb < ntl; cb += SEL_BATCH_TILES) {
-            __syncthreads();   // wsum is reused
-            join_batch(cb);
+    const bool head_shared = (td.off % TILE) != 0;
+    const uint32_t qt = tid >> 2, sub = tid & 3u;
+    uint32_t base = 0;
+    int ovf = 0;
+    for (uint32_t r0 = 0; r0 < sd.ntiles; r0 += SEL_THREADS / 4) {
+        const uint32_t tl = r0 + qt;
+        const bool in = tl < sd.ntiles;
+        const uint32_t t = sd.tile0 + tl;
+        uint32_t w = 0;
+        uint4 pf = make_uint4(0, 0, 0, 0);
+        if (in) {
+            w = A.tile_cnt[t];
+            pf = ((const uint4 *)(A.heads + (size_t)t * HEAD))[sub];
         }
-        kmin = wave_min_to_last(kmin);
-        if (lane_id() == 63) atomicMin(&S.kmin, kmin);
-        const bool any_ovf = __syncthreads_or((int)ovf) != 0;   // also orders the list writes
-        kmin = S.kmin;
-        if (!any_ovf && c < pe.k && tau_cur <= 1u) zerofill = true;   // every nonzero is already here
-        else if (any_ovf || c < pe.k) dense = true;
-        if (!dense && c > SEL_LDS_LIST) {
-            // the list outgrew LDS: complete the global copy
-            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
-            __syncthreads();
-        }
-        if (tid == 0) {
-            if (dense) {
-                atomicAdd(&A.stats->fallback_tensors, 1ull);
-                atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
-            } else {
-                atomicAdd(&A.stats->candidates, (unsigned long long)c);
-            }
-        }
-    }
-
-    if (zerofill) {
-        if (c <= SEL_LDS_LIST) zero_fill_emit<OP>(SrcList{llist}, c, td, pe, A, S.wsum);
-        else zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, S.wsum);
-        if (A.write_hint && tid == 0) {
-            A.tau[j] = 1u;
-            A.hint2[j] = 0u;
-            A.tprev[j] = 0u;
-        }
-        return;
-    }
-
-    // ---- rank whose key becomes the next predicted threshold
-    uint32_t R = 0, Eq = 0;
-    if (td.big && A.write_hint)
-        R = hint_rank<OP>(td, pe, !dense && !A.exact_mode, c, hint2_cur, A.m, &Eq);
-
-    uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
-    // the join's histogram stands if no candidate lies below the threshold (none can)
-    const bool win_ready = (kmin != 0xFFFFFFFFu) && (kmin >> 11) >= (tau_cur >> 11);
-    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (win_ready ? win_join : (kmin >> 11));
-    const uint32_t win_min = (win_ready && win_join > (kmin >> 11)) ? 1u : 0u;   // entries below the window
-    if (dense) {
-        if (td.n <= 2 * SEL_LDS_LIST) {
-            uint32_t *lv = (uint32_t *)llist;
-            __syncthreads();
-            for (uint32_t p = tid; p < td.n; p += SEL_THREADS)
-                lv[p] = __float_as_uint(row_value<OP>(A.state, A.model, td.off + p));
-            __syncthreads();
-            SrcDenseLds src{lv, td.off};
-            select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, S, A, pe.outoff,
-                               &tau_next, &expect, &q_e, &t_k);
+        uint32_t n_t = 0, start = 0;
+        if (w == CNT_OVERFLOW) {
+            ovf = 1;
+        } else if (head_shared && t == tlo) {
+            start = w & 0xFFFFu;      // the previous tensor's candidates come first in this tile
+            n_t = w >> 16;
         } else {
-            SrcDense<OP> src{A.state, A.model, td.off};
-            select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, S, A, pe.outoff,
-                               &tau_next, &expect, &q_e, &t_k);
+            n_t = w & 0xFFFFu;
         }
-    } else if (c <= SEL_LDS_LIST) {
-        SrcList src{llist};
-        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, S, A, pe.outoff,
+        if (start + n_t > CAPT) {   // no tile holds more than its slots: a corrupted count
+            ovf = 1;
+            n_t = 0;
+            start = 0;
+        }
+        uint32_t total;
+        const uint32_t excl = block_excl_scan<SEL_WAVES>(sub == 0 ? n_t : 0u, P.S.wsum, total);
+        const uint32_t pos = base + (sub == 0 ? excl : excl - n_t);
+        base += total;
+        if (n_t == 0) continue;
+        uint32_t i0 = 0;
+        if (start == 0) {
+            if (2 * sub < n_t) put(pos + 2 * sub, make_uint2(pf.x, pf.y));
+            if (2 * sub + 1 < n_t) put(pos + 2 * sub + 1, make_uint2(pf.z, pf.w));
+            i0 = HEAD;
+        }
+        if (i0 < n_t) {
+            const uint2 *hd = A.heads + (size_t)t * HEAD;
+            const uint2 *sl = A.slots + (size_t)t * CAPT;
+            for (uint32_t i = i0 + sub; i < n_t; i += 16) {
+                uint2 e[4];
+#pragma unroll
+                for (uint32_t v = 0; v < 4; ++v)
+                    e[v] = (i + 4 * v < n_t) ? tile_entry(hd, sl, start + i + 4 * v) : make_uint2(0, 0);
+#pragma unroll
+                for (uint32_t v = 0; v < 4; ++v)
+                    if (i + 4 * v < n_t) put(pos + i + 4 * v, e[v]);
+            }
+        }
+    }
+    ovf_out = __syncthreads_or(ovf) != 0;
+    return base;
+}
+
+// Elements of tensor j inside the part, as rows of 256 consecutive elements per wavefront
+// (4 per lane): the wavefronts take the part's tiles in equal consecutive runs, so that the
+// order of wavefronts is the order of indices.
+struct DenseRun {
+    uint32_t t0, t1;     // this wavefront's tiles [t0, t1) of the flat buffer
+    uint32_t lo, hi;     // the tensor's elements [lo, hi)
+};
+
+__device__ __forceinline__ DenseRun dense_run(const TensorDesc &td, const SegDesc &sd)
+{
+    const uint32_t wave = threadIdx.x >> 6;
+    const uint32_t per = (sd.ntiles + SEL_WAVES - 1) / SEL_WAVES;
+    DenseRun r;
+    r.t0 = sd.tile0 + min(wave * per, sd.ntiles);
+    r.t1 = sd.tile0 + min((wave + 1) * per, sd.ntiles);
+    r.lo = td.off;
+    r.hi = td.off + td.n;
+    return r;
+}
+
+// RE-HISTOGRAM of one part: key bits [30:19] of the tensor's nonzero elements in the part,
+// into lh (HBINS counters in LDS, zeroed here).  Ends with a barrier.
+template <int OP>
+__device__ __forceinline__ void dense_hist(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd, uint32_t *lh)
+{
+    for (uint32_t b = threadIdx.x; b < HBINS; b += SEL_THREADS) lh[b] = 0;
+    __syncthreads();
+    const DenseRun r = dense_run(td, sd);
+    const uint32_t lane = lane_id();
+    for (uint32_t t = r.t0; t < r.t1; ++t) {
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t e0 = t * TILE + row * 256 + lane * 4;
+            uint32_t key[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const uint32_t e = e0 + x;
+                key[x] = (e >= r.lo && e < r.hi) ? (__float_as_uint(row_value<OP>(A.state, A.model, e)) & 0x7FFFFFFFu)
+                                                : 0u;
+            }
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (key[x] != 0) atomicAdd(&lh[key[x] >> HSHIFT], 1u);
+        }
+    }
+    __syncthreads();
+}
+
+// RE-COLLECTION of one part: the tensor's elements in the part with key >= tau, in index
+// order, through `put(position, entry)`; nothing is written when there are more than `cap`.
+// Two passes over the part (count, then place).  Returns the count.
+template <int OP, class Put>
+__device__ __forceinline__ uint32_t dense_compact(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd,
+                                                  uint32_t tau, uint32_t cap, PartShared &P, Put put)
+{
+    const DenseRun r = dense_run(td, sd);
+    const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    uint32_t mine = 0;
+    for (uint32_t t = r.t0; t < r.t1; ++t) {
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t e0 = t * TILE + row * 256 + lane * 4;
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const uint32_t e = e0 + x;
+                if (e >= r.lo && e < r.hi &&
+                    (__float_as_uint(row_value<OP>(A.state, A.model, e)) & 0x7FFFFFFFu) >= tau)
+                    ++mine;
+            }
+        }
+    }
+    const uint32_t wsum_ = wave_sum(mine);
+    __syncthreads();
+    if (lane == 0) P.wtot[wave] = wsum_;
+    __syncthreads();
+    uint32_t before = 0, total = 0;
+#pragma unroll
+    for (uint32_t x = 0; x < SEL_WAVES; ++x) {
+        const uint32_t v = P.wtot[x];
+        if (x < wave) before += v;
+        total += v;
+    }
+    if (total > cap) return total;
+    uint32_t run = before;
+    for (uint32_t t = r.t0; t < r.t1; ++t) {
+#pragma unroll
+        for (int row = 0; row < 4; ++row) {
+            const uint32_t e0 = t * TILE + row * 256 + lane * 4;
+            uint32_t bits[4];
+            bool f[4];
+            uint64_t mk[4];
+#pragma unroll
+            for (int x = 0; x < 4; ++x) {
+                const uint32_t e = e0 + x;
+                const bool in = e >= r.lo && e < r.hi;
+                bits[x] = in ? __float_as_uint(row_value<OP>(A.state, A.model, e)) : 0u;
+                f[x] = in && (bits[x] & 0x7FFFFFFFu) >= tau;
+                mk[x] = ballot64(f[x]);
+            }
+            if ((mk[0] | mk[1] | mk[2] | mk[3]) != 0) {
+                uint32_t p = run + mbcnt64(mk[0]) + mbcnt64(mk[1]) + mbcnt64(mk[2]) + mbcnt64(mk[3]);
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    if (f[x]) {
+                        put(p, make_uint2(e0 + x, bits[x]));
+                        ++p;
+                    }
+                }
+                run += (uint32_t)(__popcll(mk[0]) + __popcll(mk[1]) + __popcll(mk[2]) + __popcll(mk[3]));
+            }
+        }
+    }
+    return total;
+}
+
+// Dense request on a tensor that takes the chain: how many of the part's elements reach the
+// threshold, counted into the tensor's window histogram (LDS h, SEG_WBINS bins).
+template <int OP>
+__device__ __forceinline__ uint32_t dense_window_count(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd,
+                                                       uint32_t tau, uint32_t win_base, uint32_t *h, uint32_t *wsum)
+{
+    const uint64_t lo = max((uint64_t)td.off, (uint64_t)sd.tile0 * TILE);
+    const uint64_t hi = min((uint64_t)td.off + td.n, ((uint64_t)sd.tile0 + sd.ntiles) * TILE);
+    uint32_t mine = 0;
+    for (uint64_t e = lo + threadIdx.x; e < hi; e += SEL_THREADS) {
+        const uint32_t key = __float_as_uint(row_value<OP>(A.state, A.model, (uint32_t)e)) & 0x7FFFFFFFu;
+        if (key >= tau) {
+            const uint32_t hi12 = key >> SEG_LOWBITS;
+            const uint32_t w = (hi12 > win_base) ? (hi12 - win_base) : 0u;
+            atomicAdd(&h[min(w, SEG_WBINS - 1u)], 1u);
+            ++mine;
+        }
+    }
+    return block_sum(mine, wsum, SEL_WAVES);
+}
+
+// First bin (key >> SEG_LOWBITS) of the window histogram of a tensor that takes the chain.
+// Candidates start at the collection threshold; when that lies far below the k-th key of the
+// previous selection on this stream (a relaxed hint), the window is centred on that key
+// instead, so that it reaches half an octave to either side of it.  Keys below the window are
+// counted into bin 0, which then holds no usable rank.
+__device__ __forceinline__ uint32_t seg_window_base(uint32_t tau_cur, uint32_t t_prev)
+{
+    const uint32_t b_tau = tau_cur >> SEG_LOWBITS;
+    const uint32_t b_prev = t_prev >> SEG_LOWBITS;
+    const uint32_t b_mid = (b_prev > SEG_WBINS / 2) ? (b_prev - SEG_WBINS / 2) : 0u;
+    return max(b_tau, b_mid);
+}
+
+// The last part of a tensor that takes the chain: the tensor's window histogram (global, c
+// candidates in all) -> the 19-bit prefix of the k-th key, its rank among the entries sharing
+// it, and the next hint.  Returns the tensor's status (SEG_ACTIVE, SEG_ALL, or 0 = failed);
+// thread 0 writes segstate / hints.  h: SEG_WBINS words of LDS.
+template <int OP>
+__device__ __forceinline__ uint32_t window_step(const SelectArgs &A, const TensorDesc &td, const PlanEntry &pe,
+                                                uint32_t j, uint32_t c, bool ovf, uint32_t tau_cur, uint32_t tprev_cur,
+                                                bool exact_mode, PartShared &P)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t *h = P.S.h;
+    uint32_t *gh = A.ghist + (size_t)j * HBINS;
+    uint32_t mylow = 0xFFFFFFFFu;
+    if (tid == 0) P.S.kmin = 0xFFFFFFFFu;
+    __syncthreads();
+    for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+        const uint32_t v = ld_dev(&gh[b]);
+        h[b] = v;
+        if (v) st_dev(&gh[b], 0u);   // clean for the next use
+        if (v && mylow == 0xFFFFFFFFu) mylow = b;
+    }
+    if (mylow != 0xFFFFFFFFu) atomicMin(&P.S.kmin, mylow);
+    const uint32_t win_base = seg_window_base(tau_cur, tprev_cur);
+    const int bin_min = (win_base > (tau_cur >> SEG_LOWBITS)) ? 1 : 0;   // bin 0 mixes in lower keys
+    uint32_t R = 0, Eq = 0;
+    if (A.write_hint) R = hint_rank<OP>(td, pe, !exact_mode, c, A.hint2[j], A.m, &Eq);
+    const bool measurable = (R != 0) && (c >= R);
+    const uint32_t qlow = max(c / 4u, min(c, 16u));
+    const uint32_t third = measurable ? Eq : ((R != 0 && c != 0) ? (c - qlow + 1u) : 0u);
+    find_ranks<SEG_WBINS, SEL_WAVES>(h, pe.k, measurable ? R : pe.k, third, P.S.rowsum, P.S.res);
+    const int bk = P.S.res[0], bR = P.S.res[2];
+    const uint32_t lowest = P.S.kmin;
+    const bool all = (pe.k == td.n);   // everything is sent: no threshold to find
+    const bool ok = all || (!ovf && (c >= pe.k) && bk >= bin_min && bk < (int)SEG_WBINS - 1);
+    if (tid == 0 && ok) {
+        SegState *st = &A.segstate[j];
+        st->pfxcount = 0;
+        st->pfx = win_base + (uint32_t)max(bk, 0);
+        st->r2 = (uint32_t)P.S.res[1];
+        st->T = 0;
+        atomicAdd(&A.stats->candidates, (unsigned long long)c);
+        atomicAdd(&A.stats->segmented_tensors, 1ull);
+        if (A.write_hint) {
+            uint32_t tn = 0, expect = 0;
+            if (measurable && bR >= bin_min && bR < (int)SEG_WBINS - 1) {
+                const uint32_t edge = (win_base + (uint32_t)bR) << SEG_LOWBITS;
+                tn = edge ? edge : 1u;
+                expect = R - (uint32_t)P.S.res[3] + h[bR];
+                const int bE = P.S.res[4];
+                if (bE >= bin_min && bE < (int)SEG_WBINS - 1)
+                    tn = hint_scaled(tn, (win_base + (uint32_t)bE) << SEG_LOWBITS, tau_cur);
+            }
+            if (tn == 0 && !measurable && R != 0 && lowest != 0xFFFFFFFFu && (int)lowest >= bin_min &&
+                P.S.res[4] >= (int)lowest && P.S.res[4] < (int)SEG_WBINS - 1) {
+                const uint32_t kmin = max((win_base + lowest) << SEG_LOWBITS, tau_cur);
+                tn = hint_extrapolated(kmin, c, R, qlow, ((uint32_t)P.S.res[4] - lowest + 1u) << SEG_LOWBITS);
+                expect = R;
+            }
+            if (tn == 0) {
+                const uint32_t kmin = (lowest == 0xFFFFFFFFu || (int)lowest < bin_min) ? 0xFFFFFFFFu
+                                                             : max((win_base + lowest) << SEG_LOWBITS, tau_cur);
+                tn = hint_relaxed(tau_cur, kmin);
+                expect = 0;
+            }
+            if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;
+            A.tau[j] = tn;
+            A.hint2[j] = expect;
+        }
+    }
+    __syncthreads();
+    return all ? (uint32_t)SEG_ALL : (ok ? (uint32_t)SEG_ACTIVE : 0u);
+}
+
+// Selection of a whole tensor straight from the buffers by this one workgroup: small tensors,
+// dense requests on tensors outside the chain, and whatever the re-collection could not
+// resolve.  Exact for any data; slow on large tensors.
+template <int OP>
+__device__ __forceinline__ void dense_select(const SelectArgs &A, const TensorDesc &td, const PlanEntry &pe, uint32_t j,
+                                             uint32_t tau_cur, PartShared &P, uint2 *llist)
+{
+    const uint32_t tid = threadIdx.x;
+    uint32_t R = 0, Eq = 0;
+    if (td.big && A.write_hint) R = hint_rank<OP>(td, pe, false, 0u, 0u, A.m, &Eq);
+    uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
+    if (td.n <= 2 * SEL_LDS_LIST) {
+        uint32_t *lv = (uint32_t *)llist;
+        __syncthreads();
+        for (uint32_t p = tid; p < td.n; p += SEL_THREADS)
+            lv[p] = __float_as_uint(row_value<OP>(A.state, A.model, td.off + p));
+        __syncthreads();
+        SrcDenseLds src{lv, td.off};
+        select_emit<OP, 4>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, P.S, A, pe.outoff,
                            &tau_next, &expect, &q_e, &t_k);
     } else {
-        SrcList src{glist};
-        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, S, A, pe.outoff,
+        SrcDense<OP> src{A.state, A.model, td.off};
+        select_emit<OP, 8>(src, td.n, pe.k, R, 0u, 0xFFFFFFFFu, 0u, false, 0xFFFFFFFFu, P.S, A, pe.outoff,
                            &tau_next, &expect, &q_e, &t_k);
     }
-
     if (td.big && A.write_hint && tid == 0) {
         uint32_t tn = tau_next;
         if (tn == 0) {
-            tn = hint_relaxed(tau_cur, dense ? 0xFFFFFFFFu : kmin);
+            tn = hint_relaxed(tau_cur, 0xFFFFFFFFu);
+            expect = 0;
+        }
+        if (tn >= 0x7F800000u) tn = 0x7F7FFFFFu;
+        A.tau[j] = tn;
+        A.hint2[j] = expect;
+        A.tprev[j] = t_k;
+    }
+}
+
+// The tensor's candidates are in `llist` (first SEL_LDS_LIST) and `glist` (beyond): exact
+// selection, emission, fix-up and the next hint.  win_*: the window histogram in P.S.h counted
+// while the list was built (single-part tensors), see select_emit.
+template <int OP>
+__device__ __forceinline__ void list_select(const SelectArgs &A, const TensorDesc &td, const PlanEntry &pe, uint32_t j,
+                                            uint32_t c, uint32_t kmin, uint32_t tau_cur, uint32_t hint2_cur,
+                                            uint32_t win_join, bool win_counted, bool exact_mode, PartShared &P,
+                                            uint2 *llist, uint2 *glist)
+{
+    const uint32_t tid = threadIdx.x;
+    if (c > SEL_LDS_LIST) {
+        // the list outgrew LDS: complete the global copy
+        for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
+        __syncthreads();
+    }
+    uint32_t R = 0, Eq = 0;
+    if (A.write_hint) R = hint_rank<OP>(td, pe, !exact_mode, c, hint2_cur, A.m, &Eq);
+    uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
+    // the histogram counted on the way stands if no candidate lies below the threshold (none can)
+    const bool win_ready = win_counted && (kmin != 0xFFFFFFFFu) && (kmin >> 11) >= (tau_cur >> 11);
+    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (win_ready ? win_join : (kmin >> 11));
+    const uint32_t win_min = (win_ready && win_join > (kmin >> 11)) ? 1u : 0u;   // entries below the window
+    if (c <= SEL_LDS_LIST) {
+        SrcList src{llist};
+        select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, P.S, A, pe.outoff,
+                           &tau_next, &expect, &q_e, &t_k);
+    } else {
+        SrcList src{glist};
+        select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, P.S, A, pe.outoff,
+                           &tau_next, &expect, &q_e, &t_k);
+    }
+    if (A.write_hint && tid == 0) {
+        uint32_t tn = tau_next;
+        if (tn == 0) {
+            tn = hint_relaxed(tau_cur, kmin);
             expect = 0;
         } else if (q_e != 0) {
             tn = hint_scaled(tn, q_e, tau_cur);
@@ -312,17 +483,384 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A,
     }
 }
 
+// The candidates of a tensor of several parts, addressed by list position through the parts'
+// global lists (pbase: first position of every part, in LDS).
+struct SrcParts {
+    static constexpr bool AGG = true;
+    const uint2 *ord;
+    const SegDesc *parts;      // the tensor's parts
+    const uint32_t *pbase;
+    uint32_t nseg, j;
+    __device__ __forceinline__ uint2 get(uint32_t p) const
+    {
+        uint32_t lo = 0, hi = nseg;       // last part whose first position is <= p
+        while (hi - lo > 1) {
+            const uint32_t mid = (lo + hi) >> 1;
+            if (pbase[mid] <= p) lo = mid;
+            else hi = mid;
+        }
+        return ld_dev(&ord[(size_t)(parts[lo].tile0 + j) * CAPT + (p - pbase[lo])]);
+    }
+    __device__ __forceinline__ uint32_t bits(uint32_t p) const { return get(p).y; }
+    __device__ __forceinline__ uint32_t index(uint32_t p) const { return get(p).x; }
+};
 
-void launch_select(int op, const SelectArgs &a, uint32_t J, void *stream, void *ev0, void *ev1)
+// What the workgroup that completes a tensor's candidate lists does with them (`round` 0: the
+// streaming pass's candidates, 1: re-collected with a fresh threshold).  Returns the tensor's
+// status: SEG_DONE, SEG_ACTIVE / SEG_ALL (the chain kernels go on), or SEG_PENDING (round 0
+// only: collect again).
+//   multi: the lists are the parts' global lists (counts in segcnt) and are gathered here;
+//   otherwise the single part's list is in llist / glist (or, for a tensor that takes the
+//   chain, in its global list only) with count c0, overflow ovf0, smallest key (or a lower
+//   bound of it) kmin0, and -- win_counted -- the window histogram counted on the way.
+//   tau_cur, tprev_cur: the threshold the lists were collected with and the anchor of the window
+//   histograms (handed in: in round 1 they were published by another workgroup of this launch).
+template <int OP>
+__device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const TensorDesc &td, const PlanEntry &pe,
+                                                  uint32_t j, int round, bool multi, uint32_t c0, bool ovf0,
+                                                  uint32_t kmin0, uint32_t tau_cur, uint32_t tprev_cur,
+                                                  uint32_t win_join, bool win_counted, PartShared &P, uint2 *llist)
+{
+    const uint32_t tid = threadIdx.x;
+    const uint32_t tlo = td.off / TILE;
+    uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;      // = the first part's list
+    const bool exact_mode = A.exact_mode || round != 0;
+    const uint32_t hint2_cur = A.write_hint ? A.hint2[j] : 0u;
+    const bool have_pbase = td.nseg <= SEG_MAX_PER_TENSOR;
+    // The longest list this workgroup selects from.  A tensor of several parts is gathered in
+    // place: what does not fit the LDS list goes to the first part's global list, which must
+    // end before the second part's begins.
+    const uint32_t list_max = multi ? max(SEL_LDS_LIST, min(SEL_LIST_MAX, A.segtab[td.seg_first].ntiles * CAPT))
+                                    : SEL_LIST_MAX;
+    uint32_t c = c0, kmin = kmin0;
+    bool ovf = ovf0;
+    if (multi) {
+        // counts of the parts -> list positions
+        uint32_t o = 0;
+        c = 0;
+        for (uint32_t s0 = 0; s0 < td.nseg; s0 += SEL_THREADS) {
+            const uint32_t s = s0 + tid;
+            uint32_t cnt = (s < td.nseg) ? ld_dev(&A.segcnt[td.seg_first + s]) : 0u;
+            if (cnt >> 31) o = 1;
+            cnt &= 0x7FFFFFFFu;
+            uint32_t tot;
+            const uint32_t ex = block_excl_scan<SEL_WAVES>(cnt, P.S.wsum, tot);
+            if (s < td.nseg && have_pbase) P.pbase[s] = c + ex;
+            c += tot;
+        }
+        if (tid == 0 && have_pbase) P.pbase[td.nseg] = c;
+        ovf = __syncthreads_or((int)o) != 0;
+    }
+    uint32_t status = 0;
+    // every nonzero is in the lists (a dense request has no lists: it falls back instead)
+    const bool zerofill = !A.dense && !ovf && c < pe.k && tau_cur <= 1u && (!multi || have_pbase);
+    if (pe.seg) status = window_step<OP>(A, td, pe, j, c, ovf, tau_cur, tprev_cur, exact_mode, P);
+    if (status == 0 && zerofill) {
+        // the message is completed with the tensor's lowest-index zeros
+        if (multi) {
+            zero_fill_emit<OP>(SrcParts{A.ord, A.segtab + td.seg_first, P.pbase, td.nseg, j}, c, td, pe, A, P.S.wsum);
+        } else if (pe.seg) {
+            zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
+        } else if (c > SEL_LDS_LIST) {
+            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
+            wait_mem();
+            __syncthreads();
+            zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
+        } else {
+            zero_fill_emit<OP>(SrcList{llist}, c, td, pe, A, P.S.wsum);
+        }
+        if (A.write_hint && tid == 0) {
+            A.tau[j] = 1u;
+            A.hint2[j] = 0u;
+            A.tprev[j] = 0u;
+        }
+        if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
+        status = SEG_DONE;
+    } else if (!pe.seg && !ovf && c >= pe.k && c <= list_max && (!multi || have_pbase)) {
+        if (multi) {
+            // gather the parts' lists into one (positions beyond the LDS list land in the first
+            // part's global list: on dead space, or on the very entry that is being moved)
+            if (tid == 0) P.S.kmin = 0xFFFFFFFFu;
+            __syncthreads();
+            const SrcParts src{A.ord, A.segtab + td.seg_first, P.pbase, td.nseg, j};
+            uint32_t km = 0xFFFFFFFFu;
+            for (uint32_t q0 = 0; q0 < c; q0 += 4 * SEL_THREADS) {
+                uint2 e[4];
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t q = q0 + u * SEL_THREADS + tid;
+                    e[u] = (q < c) ? src.get(q) : make_uint2(0, 0);
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < 4; ++u) {
+                    const uint32_t q = q0 + u * SEL_THREADS + tid;
+                    if (q < c) {
+                        put_entry(llist, glist, q, e[u]);
+                        km = min(km, e[u].y & 0x7FFFFFFFu);
+                    }
+                }
+            }
+            km = wave_min_to_last(km);
+            if (lane_id() == 63) atomicMin(&P.S.kmin, km);
+            wait_mem();
+            __syncthreads();
+            kmin = P.S.kmin;
+        }
+        list_select<OP>(A, td, pe, j, c, kmin, tau_cur, hint2_cur, win_join, win_counted && !multi, exact_mode, P,
+                        llist, glist);
+        if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
+        status = SEG_DONE;
+    }
+    if (status == 0) status = (round == 0 && A.repair) ? (uint32_t)SEG_PENDING : (uint32_t)SEG_FALLBACK;
+    if (status == SEG_FALLBACK) {
+        if (tid == 0) {
+            atomicAdd(&A.stats->fallback_tensors, 1ull);
+            atomicAdd(&A.stats->fallback_elems, (unsigned long long)td.n);
+        }
+        dense_select<OP>(A, td, pe, j, tau_cur, P, llist);
+        status = SEG_DONE;
+    } else if (round != 0 && tid == 0) {
+        atomicAdd(&A.stats->repaired_tensors, 1ull);
+    }
+    if (tid == 0) A.segstate[j].status = status;
+    return status;
+}
+
+// RE-HISTOGRAM (role 1) or RE-COLLECTION (role 2) of one part; returns at once unless the
+// part's tensor has several parts and was left pending by the JOIN.
+template <int OP>
+__device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t role, uint32_t part, PartShared &P,
+                                               uint2 *llist)
+{
+    const uint32_t tid = threadIdx.x;
+    const SegDesc sd = A.segtab[part];
+    const uint32_t j = sd.j;
+    const TensorDesc td = A.tdesc[j];
+    const PlanEntry pe = A.plan[j];
+    const bool multi = td.nseg > 1;
+    SegState *st = &A.segstate[j];
+    uint2 *plist = A.ord + (size_t)(sd.tile0 + j) * CAPT;       // this part's list
+    const uint32_t part_cap = sd.ntiles * CAPT;
+    if (!multi) return;
+    const uint32_t verdict = wait_word(&st->verdict, A.spin_limit, &P.bc);
+    if (tid == 0) {
+        if (verdict == 0) atomicAdd(&A.stats->internal_errors, 1ull);   // gave up waiting
+        reader_done(&st->seen[0], 2u * td.nseg, &st->verdict);
+    }
+    if ((verdict & 0xFFu) != SEG_PENDING) return;
+    uint32_t *gh = A.ghist + (size_t)j * HBINS;
+    if (role == 1) {
+        uint32_t *lh = (uint32_t *)llist;
+        dense_hist<OP>(A, td, sd, lh);
+        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS) {
+            const uint32_t v = lh[b];
+            if (v) atomicAdd(&gh[b], v);
+        }
+        if (!arrive_last(&st->arrive[1], td.nseg, &P.bc)) return;
+        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS) {
+            const uint32_t v = ld_dev(&gh[b]);
+            lh[b] = v;
+            if (v) st_dev(&gh[b], 0u);
+        }
+        uint32_t tau_new = 0, tprev_new = 0;
+        pick_from_hist<SEL_WAVES>(lh, pe, P.S.rowsum, P.S.res, tau_new, tprev_new);
+        if (tid == 0) {
+            st_dev(&A.tau[j], tau_new);
+            st_dev(&A.tprev[j], tprev_new);
+        }
+        wait_mem();
+        __syncthreads();
+        if (tid == 0) st_dev(&st->tau_ready, 1u);
+        return;
+    }
+    const uint32_t ready = wait_word(&st->tau_ready, A.spin_limit, &P.bc);
+    if (tid == 0) {
+        if (ready == 0) atomicAdd(&A.stats->internal_errors, 1ull);
+        reader_done(&st->seen[1], td.nseg, &st->tau_ready);
+    }
+    if (ready == 0) return;
+    const uint32_t tau_new = ld_dev(&A.tau[j]);
+    const uint32_t tprev_new = ld_dev(&A.tprev[j]);
+    const uint32_t win2 = seg_window_base(tau_new, tprev_new);
+    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+    __syncthreads();
+    uint32_t c2;
+    if (pe.seg) {
+        c2 = dense_compact<OP>(A, td, sd, tau_new, part_cap, P, [&](uint32_t pos, uint2 e) {
+            plist[pos] = e;
+            const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+            const uint32_t w = (hi12 > win2) ? (hi12 - win2) : 0u;
+            atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
+        });
+        __syncthreads();
+        if (c2 <= part_cap) {
+            for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+                const uint32_t v = P.S.h[b];
+                if (v) atomicAdd(&gh[b], v);
+            }
+        }
+    } else {
+        c2 = dense_compact<OP>(A, td, sd, tau_new, part_cap, P, [&](uint32_t pos, uint2 e) { st_dev(&plist[pos], e); });
+    }
+    if (tid == 0) st_dev(&A.segcnt[part], min(c2, 0x7FFFFFFFu) | (c2 > part_cap ? 0x80000000u : 0u));
+    if (!arrive_last(&st->arrive[2], td.nseg, &P.bc)) return;
+    tensor_select<OP>(A, td, pe, j, 1, true, 0u, false, 0xFFFFFFFFu, tau_new, tprev_new, 0u, false, P, llist);
+}
+
+template <int OP>
+__global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
+{
+    __shared__ PartShared P;
+    __shared__ uint2 llist[SEL_LDS_LIST];
+    const uint32_t tid = threadIdx.x;
+    if (blockIdx.x >= A.nparts) {
+        // RE-HISTOGRAM / RE-COLLECTION: this workgroup looks after B_GROUP consecutive parts
+        const uint32_t nb = (A.nparts + B_GROUP - 1) / B_GROUP;
+        const uint32_t b = blockIdx.x - A.nparts;
+        const uint32_t role = (b < nb) ? 1u : 2u;
+        const uint32_t first = (role == 1 ? b : b - nb) * B_GROUP;
+        for (uint32_t part = first; part < min(first + B_GROUP, A.nparts); ++part)
+            recollect_part<OP>(A, role, part, P, llist);
+        return;
+    }
+    const uint32_t part = blockIdx.x;
+    const SegDesc sd = A.segtab[part];
+    const uint32_t j = sd.j;
+    const TensorDesc td = A.tdesc[j];
+    const PlanEntry pe = A.plan[j];
+    const bool multi = td.nseg > 1;
+    SegState *st = &A.segstate[j];
+    uint2 *plist = A.ord + (size_t)(sd.tile0 + j) * CAPT;       // this part's list
+    const uint32_t part_cap = sd.ntiles * CAPT;
+    const bool chain_dense = A.dense && pe.seg;                  // the chain reads the tensor itself
+
+    {
+        // ------------------------------------------------------------------ JOIN
+        if (!td.big || (A.dense && !pe.seg)) {
+            if (sd.sidx != 0) return;
+            if (tid == 0) st->status = SEG_DONE;
+            dense_select<OP>(A, td, pe, j, td.big ? A.tau[j] : TAU_NEVER, P, llist);
+            return;
+        }
+        const uint32_t tau_cur = A.tau[j];
+        const uint32_t tprev_cur = A.tprev[j];
+        uint32_t cs = 0, kmin = 0xFFFFFFFFu;
+        bool ovf = false;
+        // window of the single-workgroup selection: starts at the collection threshold or, when
+        // that lies far below (a relaxed hint), 1024 buckets under the previous k-th key
+        const uint32_t win_join = max(tau_cur >> 11, max(tprev_cur >> 11, 1024u) - 1024u);
+        const uint32_t win_seg = seg_window_base(tau_cur, tprev_cur);
+        if (pe.seg || !multi) {
+            for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+            if (tid == 0) P.S.kmin = 0xFFFFFFFFu;
+            __syncthreads();
+        }
+        if (chain_dense) {
+            cs = dense_window_count<OP>(A, td, sd, tau_cur, win_seg, P.S.h, P.S.wsum);
+        } else if (pe.seg) {
+            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) {
+                st_dev(&plist[pos], e);               // read by the chain kernels, and by a zero fill
+                const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+                const uint32_t w = (hi12 > win_seg) ? (hi12 - win_seg) : 0u;
+                atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
+            });
+        } else if (multi) {
+            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) { st_dev(&plist[pos], e); });
+        } else {
+            uint2 *glist = plist;
+            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) {
+                put_entry(llist, glist, pos, e);
+                kmin = min(kmin, e.y & 0x7FFFFFFFu);
+                window_count(P.S.h, win_join, e.y & 0x7FFFFFFFu);
+            });
+            kmin = wave_min_to_last(kmin);
+            if (lane_id() == 63) atomicMin(&P.S.kmin, kmin);
+            wait_mem();
+            __syncthreads();
+            kmin = P.S.kmin;
+        }
+        if (pe.seg) {
+            // the part's share of the tensor's window histogram
+            __syncthreads();
+            uint32_t *gh = A.ghist + (size_t)j * HBINS;
+            for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+                const uint32_t v = P.S.h[b];
+                if (v) atomicAdd(&gh[b], v);
+            }
+        }
+        if (multi) {
+            if (tid == 0) st_dev(&A.segcnt[part], cs | (ovf ? 0x80000000u : 0u));
+            if (!arrive_last(&st->arrive[0], td.nseg, &P.bc)) return;
+        } else if (pe.seg) {
+            if (tid == 0) A.segcnt[part] = cs;
+            wait_mem();       // the histogram is read back below
+            __syncthreads();
+        }
+        uint32_t status = tensor_select<OP>(A, td, pe, j, 0, multi, cs, ovf, kmin, tau_cur, tprev_cur, win_join, true, P, llist);
+        if (multi) {
+            if (A.repair) {
+                wait_mem();
+                __syncthreads();
+                if (tid == 0) st_dev(&st->verdict, 0x100u | status);
+            }
+            return;
+        }
+        if (status != SEG_PENDING) return;
+        // ---- a tensor of one part whose prediction failed: collect again on the spot
+        uint32_t *lh = (uint32_t *)llist;
+        dense_hist<OP>(A, td, sd, lh);
+        uint32_t tau_new = 0, tprev_new = 0;
+        pick_from_hist<SEL_WAVES>(lh, pe, P.S.rowsum, P.S.res, tau_new, tprev_new);
+        if (tid == 0) {
+            A.tau[j] = tau_new;
+            A.tprev[j] = tprev_new;
+            P.bc = tau_new;
+        }
+        __syncthreads();
+        tau_new = P.bc;
+        for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+        __syncthreads();
+        const uint32_t win2 = seg_window_base(tau_new, tprev_new);
+        const uint32_t cap = pe.seg ? part_cap : min(part_cap, SEL_LIST_MAX);
+        uint32_t c2;
+        if (pe.seg) {
+            c2 = dense_compact<OP>(A, td, sd, tau_new, cap, P, [&](uint32_t pos, uint2 e) {
+                plist[pos] = e;
+                const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+                const uint32_t w = (hi12 > win2) ? (hi12 - win2) : 0u;
+                atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
+            });
+            __syncthreads();
+            if (c2 <= cap) {
+                uint32_t *gh = A.ghist + (size_t)j * HBINS;
+                for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+                    const uint32_t v = P.S.h[b];
+                    if (v) atomicAdd(&gh[b], v);
+                }
+                if (tid == 0) A.segcnt[part] = c2;
+            }
+        } else {
+            uint2 *glist = plist;
+            c2 = dense_compact<OP>(A, td, sd, tau_new, cap, P, [&](uint32_t pos, uint2 e) { put_entry(llist, glist, pos, e); });
+        }
+        wait_mem();
+        __syncthreads();
+        // kmin unknown (0 keeps the window honest: it is counted again from the list)
+        tensor_select<OP>(A, td, pe, j, 1, false, c2, c2 > cap, tau_new, tau_new, tprev_new, 0u, false, P, llist);
+        return;
+    }
+
+}
+
+void launch_select(int op, const SelectArgs &a, void *stream, void *ev0, void *ev1)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (op == SEL_WORKER)
-        launch_k(k_select<SEL_WORKER>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads,
-                 a.slots);
-    else if (op == SEL_PULL)
-        launch_k(k_select<SEL_PULL>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads, a.slots);
-    else
-        launch_k(k_select<SEL_PULL_V>, dim3(J), dim3(SEL_THREADS), st, ev0, ev1, a, a.tile_cnt, a.heads, a.slots);
+    if (a.nparts == 0) return;
+    const uint32_t nb = (a.nparts + B_GROUP - 1) / B_GROUP;
+    const dim3 grid(a.nparts + (a.repair ? 2u * nb : 0u)), block(SEL_THREADS);
+    if (op == SEL_WORKER) launch_k(k_select<SEL_WORKER>, grid, block, st, ev0, ev1, a);
+    else if (op == SEL_PULL) launch_k(k_select<SEL_PULL>, grid, block, st, ev0, ev1, a);
+    else launch_k(k_select<SEL_PULL_V>, grid, block, st, ev0, ev1, a);
 }
 
 }  // namespace dgs

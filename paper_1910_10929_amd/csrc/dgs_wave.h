@@ -29,6 +29,90 @@ __device__ __forceinline__ uint32_t uniform(uint32_t v) { return __builtin_amdgc
 // non-temporal ones by 15 us.
 __device__ __forceinline__ void store_scattered(float *p, float v) { __builtin_nontemporal_store(v, p); }
 
+// ---------------------------------------------------------------------------
+// hand-over between workgroups of one launch
+// ---------------------------------------------------------------------------
+// The L2 caches of the chip's eight dies (XCDs) are not coherent with each other, and a
+// device-wide release fence writes back a die's whole L2 (measured: a streaming pass whose
+// workgroups each fence runs 15 x longer).  So what one workgroup hands to another inside a
+// launch goes through memory explicitly: written with device-scope stores (write-through),
+// read with device-scope loads (never a stale line of the reader's L2), and the writer waits
+// for its stores to be acknowledged before it signals through a device-scope atomic.
+__device__ __forceinline__ void st_dev(uint32_t *p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(uint2 *p, uint2 v)
+{
+    __hip_atomic_store((unsigned long long *)p, ((unsigned long long)v.y << 32) | v.x, __ATOMIC_RELAXED,
+                       __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t ld_dev(const uint32_t *p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint2 ld_dev(const uint2 *p)
+{
+    const unsigned long long x =
+        __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_uint2((uint32_t)x, (uint32_t)(x >> 32));
+}
+// All vector memory operations of this wavefront (stores and atomics included) are complete.
+#ifdef DGS_HOST_EMULATION   // CPU build of the kernels for sanitizer runs: no such instruction, nothing to wait for
+__device__ __forceinline__ void wait_mem() {}
+#else
+__device__ __forceinline__ void wait_mem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+#endif
+
+// The workgroup has finished its share of a per-tensor phase: after every wavefront's stores
+// are acknowledged, one device-scope atomic counts it in.  Returns true in every thread of the
+// workgroup that arrives last of `expected` (it then also clears the counter for the next
+// launch).  `bc` is one word of LDS.  Contains two barriers.
+__device__ __forceinline__ bool arrive_last(uint32_t *counter, uint32_t expected, uint32_t *bc)
+{
+    wait_mem();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        const uint32_t old = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool last = (old + 1u == expected);
+        if (last) st_dev(counter, 0u);
+        *bc = last ? 1u : 0u;
+    }
+    __syncthreads();
+    return *bc != 0;
+}
+
+// Thread 0 polls a word another workgroup of this launch will set (device-scope loads, sleeping
+// in between); the value is handed to the whole workgroup through `bc`.  Bounded: after
+// `limit` polls it gives up and returns 0.  Only ever waits for workgroups with a lower block
+// index, which the hardware has dispatched before this one.  Contains two barriers.
+__device__ __forceinline__ uint32_t wait_word(const uint32_t *p, uint32_t limit, uint32_t *bc)
+{
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        uint32_t v = 0;
+        for (uint32_t spin = 0; spin < limit; ++spin) {
+            v = ld_dev(p);
+            if (v != 0) break;
+            __builtin_amdgcn_s_sleep(20);
+        }
+        *bc = v;
+    }
+    __syncthreads();
+    return *bc;
+}
+
+// One reader of a hand-over word has passed; the last of `readers` clears the word and the
+// count for the next launch.  Call from one thread.
+__device__ __forceinline__ void reader_done(uint32_t *seen, uint32_t readers, uint32_t *word)
+{
+    const uint32_t old = __hip_atomic_fetch_add(seen, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + 1u == readers) {
+        st_dev(word, 0u);
+        st_dev(seen, 0u);
+    }
+}
+
 // Plain launch, or a launch whose begin and / or end is stamped into an event.
 template <class K, class... Args>
 static void launch_k(K kernel, dim3 grid, dim3 block, hipStream_t st, void *ev0, void *ev1, Args... args)

@@ -137,9 +137,10 @@ def test_segmented_server_pull(oracle):
 
 
 def test_automatic_mode_mixes_both_selections(oracle):
-    """Default mode: the 4.2M-element tensor goes segmented by size, the 300k one stays
-    on the single-workgroup path at density 1e-3 and goes segmented at 0.03 (its
-    candidate list no longer fits one workgroup's LDS)."""
+    """Default mode: at density 1e-3 both large tensors are selected inside the selection
+    launch (their parts joined by several workgroups, the last one selecting); at 0.03 the
+    4.2M-element tensor's candidate list is too long for one workgroup and goes through the
+    chain kernels, the 300k one still does not."""
     off = synth.offsets_from_sizes([4_200_000, 64, 300_000])
     n = int(off[-1])
     scales = synth.tensor_scales(3, 50)
@@ -148,16 +149,15 @@ def test_automatic_mode_mixes_both_selections(oracle):
     for rho in (1e-3, 0.03):
         st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), rho)
         assert st.fallback_tensors == 0
-        assert st.segmented_tensors == (3 if rho == 1e-3 else 6)
+        assert st.segmented_tensors == (0 if rho == 1e-3 else 3)
 
 
 @pytest.mark.parametrize("seg_mode", [None, dgs.SEG_NEVER], ids=["auto", "never"])
 def test_single_workgroup_join_over_several_batches(oracle, seg_mode):
-    """Tensors of more than 3072 tiles that stay on the single-workgroup path (below the
-    size where the multi-workgroup chain takes over by itself, or above it with that chain
-    switched off) are joined in several batches; the second tensor starts inside a tile of
-    the first.  A crowded stretch (every element a candidate in a few tiles) spills into the
-    per-tile slots on the way."""
+    """Tensors of thousands of tiles whose candidate lists one workgroup can select from: their
+    parts are joined by many workgroups and gathered by the last one (with the chain switched
+    off as well); the second tensor starts inside a tile of the first.  A crowded stretch
+    (every element a candidate in a few tiles) spills into the per-tile slots on the way."""
     sizes = [3_400_017, 3_900_000, 5000] if seg_mode is None else [3_400_017, 7_000_001, 5000]
     off = synth.offsets_from_sizes(sizes)
     scales = synth.tensor_scales(len(sizes), 55)
