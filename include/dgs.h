@@ -63,7 +63,9 @@ enum {
                                 by one workgroup (slow on large tensors) */
     DGS_OPT_SPIN_LIMIT = 8   /* polls after which a waiting workgroup of the selection gives up
                                 (default 2^20, far beyond any wait that ends); it is then counted
-                                in dgs_stats.internal_errors */
+                                in dgs_stats.internal_errors.  A tensor whose prediction failed in
+                                that launch is then left unselected: after a call that raised
+                                internal_errors the outputs and the context are not to be used */
 };
 
 /* Kernel classes reported by dgs_profile_read(). */
@@ -107,6 +109,22 @@ size_t dgs_workspace_bytes(const uint64_t *offsets, uint32_t J, uint32_t W);
  * untouched by the caller until dgs_destroy().  `hip_stream` is a hipStream_t
  * (NULL = the default stream).  Uploads the launch plan and clears the
  * workspace's counters on that stream, then waits for that to finish.
+ */
+/*
+ * What a context remembers between calls.  Besides the layout it keeps, per tensor, the
+ * threshold hints that make the one-pass path possible: one set for worker steps and one per
+ * server worker slot (W sets).  A hint describes the buffer it was learned from, so a context
+ * serves ONE worker state (momentum or residual buffer) and, per slot, one difference or sent
+ * row: stepping two different states through the same context alternately stays exact -- a
+ * failed prediction is always collected again -- but pays that second collection on most
+ * calls.  Give every state its own context (the workspace is about 4.4 bytes per element).
+ * Calls on one context must not overlap; contexts are independent.
+ *
+ * Launch plans (k_j, output offsets, wire layout) are cached per density, 8 densities per
+ * context, least recently used evicted.  While the context's stream is being captured into a
+ * HIP graph a density that is not yet cached returns DGS_ENOTSUP (planning copies tables to
+ * the device, which a capture must not contain): call once with that density before the
+ * capture.  Plans used during a capture are never evicted.
  */
 int dgs_create(dgs_ctx **out, const uint64_t *offsets /*host*/, uint32_t J, uint32_t W,
                void *workspace, size_t workspace_bytes, void *hip_stream);

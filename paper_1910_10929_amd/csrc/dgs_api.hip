@@ -2,6 +2,7 @@
 // kernel sequencing.  All arithmetic of the method runs in the kernels.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -24,7 +25,7 @@ size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
     size_t tile_desc, tdesc, plans, tau, hint2, tprev, ghist, tile_cnt, heads, slots, ord, stats, flag;
-    size_t segtab, segcnt, segG1, segOut, segstate, pfxlist, total;
+    size_t segtab, grptab, grpcnt, segcnt, segG1, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -92,6 +93,8 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.stats = o;     o = align_up(o + sizeof(DevStats));
     L.flag = o;      o = align_up(o + 64);
     L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
+    L.grptab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));      // groups <= parts
+    L.grpcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segG1 = o;     o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segOut = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint2));
@@ -156,6 +159,10 @@ struct dgs_ctx {
     DevStats *stats = nullptr;
     uint32_t *flag = nullptr;
     SegDesc *segtab = nullptr;
+    SegDesc *grptab = nullptr;
+    uint32_t *grpcnt = nullptr;
+    uint32_t ngroups = 0, gparts = 1;  // join groups; parts per group
+    uint32_t bgroup = 8;               // parts per re-collecting workgroup (about 2048 tiles)
     uint32_t *segcnt = nullptr, *segG1 = nullptr;
     uint2 *segOut = nullptr;
     SegState *segstate = nullptr;
@@ -370,6 +377,8 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     sa.ntiles = c->ntiles;
     sa.nquads = c->nquads;
     sa.lr = lr;
+    // the state goes back write-through while it fits the last-level cache, non-temporal beyond
+    sa.store_mode = ((size_t)c->n * sizeof(float) > (192u << 20)) ? STORE_NT : STORE_WT;
 
     const bool have_seg = c->plan_slot[slot].nseg_active != 0;
     uint32_t *tprev = c->tprev + (size_t)hint_set * c->J;
@@ -420,6 +429,11 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.tdesc = c->tdesc;
     se.plan = plan;
     se.segtab = c->segtab;
+    se.grptab = c->grptab;
+    se.grpcnt = c->grpcnt;
+    se.ngroups = c->ngroups;
+    se.gparts = c->gparts;
+    se.bgroup = c->bgroup;
     se.tau = tau;
     se.tile_cnt = c->tile_cnt;
     se.heads = c->heads;
@@ -482,6 +496,8 @@ void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
     c->stats = (DevStats *)(c->ws + L.stats);
     c->flag = (uint32_t *)(c->ws + L.flag);
     c->segtab = (SegDesc *)(c->ws + L.segtab);
+    c->grptab = (SegDesc *)(c->ws + L.grptab);
+    c->grpcnt = (uint32_t *)(c->ws + L.grpcnt);
     c->segcnt = (uint32_t *)(c->ws + L.segcnt);
     c->segG1 = (uint32_t *)(c->ws + L.segG1);
     c->segOut = (uint2 *)(c->ws + L.segOut);
@@ -491,7 +507,7 @@ void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
 
 // Tensor, segment and initial-threshold tables of a layout, into host arrays of J,
 // (W + 1) J, J + 1 and (sum of tensor_segments) entries; fills c->nseg and c->nseg_total.
-void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, SegDesc *segs)
+void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, SegDesc *segs, SegDesc *groups)
 {
     const uint32_t J = c->J, W = c->W;
     uint32_t pfx_slots = 0, nsegs = 0;
@@ -500,7 +516,7 @@ void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, Seg
         td[j].off = (uint32_t)c->offsets[j];
         td[j].n = (uint32_t)(c->offsets[j + 1] - c->offsets[j]);
         td[j].big = td[j].n > SMALL_N ? 1u : 0u;
-        td[j].pad0 = td[j].pad1 = 0;
+        td[j].grp_first = td[j].ngrp = 0;
         const uint32_t ns = tensor_segments(c->offsets[j], c->offsets[j + 1] - c->offsets[j], scale);
         const uint32_t per = part_tiles(c->offsets[j], c->offsets[j + 1] - c->offsets[j], scale);
         td[j].seg_first = nsegs;
@@ -520,6 +536,31 @@ void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, Seg
     }
     for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)c->offsets[j];
     c->nseg_total = nsegs;
+    c->bgroup = scale >= 8 ? 1u : 8u / scale;
+    // Join groups: runs of `gparts` consecutive parts (about GROUP_TILES tiles).  The launch takes
+    // the groups of the tensors with several groups first: those tensors end with a gather and
+    // a selection by the last group to arrive, the critical path of the launch.
+    const uint32_t gparts = std::max<uint32_t>(1u, GROUP_TILES / (SEG_TILES * scale));
+    c->gparts = gparts;
+    uint32_t g = 0;
+    for (uint32_t pass = 0; pass < 2; ++pass)
+        for (uint32_t j = 0; j < J; ++j) {
+            const uint32_t ng = (td[j].nseg + gparts - 1) / gparts;
+            if ((pass == 0) != (ng > 1)) continue;
+            td[j].grp_first = g;
+            td[j].ngrp = ng;
+            for (uint32_t gi = 0; gi < ng; ++gi) {
+                const SegDesc &first = segs[td[j].seg_first + gi * gparts];
+                const SegDesc &last = segs[td[j].seg_first + std::min(td[j].nseg, (gi + 1) * gparts) - 1];
+                SegDesc d;
+                d.j = j;
+                d.tile0 = first.tile0;
+                d.ntiles = last.tile0 + last.ntiles - first.tile0;
+                d.sidx = gi;
+                groups[g++] = d;
+            }
+        }
+    c->ngroups = g;
 }
 
 // Host -> device: a copy on the stream, or -- for the context that must not allocate or copy
@@ -535,13 +576,15 @@ int upload(dgs_ctx *c, void *dst, const void *src, size_t bytes)
 }
 
 // Tables up, counters cleared: what a context's workspace holds before its first call.
-int upload_tables(dgs_ctx *c, const TensorDesc *td, const uint32_t *tau0, const uint32_t *toff, const SegDesc *segs)
+int upload_tables(dgs_ctx *c, const TensorDesc *td, const uint32_t *tau0, const uint32_t *toff, const SegDesc *segs,
+                  const SegDesc *groups)
 {
     const uint32_t J = c->J, W = c->W;
     int rc = upload(c, c->toff, toff, ((size_t)J + 1) * sizeof(uint32_t));
     if (rc == DGS_OK) rc = upload(c, c->tdesc, td, (size_t)J * sizeof(TensorDesc));
     if (rc == DGS_OK) rc = upload(c, c->tau, tau0, (size_t)(W + 1) * J * sizeof(uint32_t));
     if (rc == DGS_OK) rc = upload(c, c->segtab, segs, (size_t)c->nseg_total * sizeof(SegDesc));
+    if (rc == DGS_OK) rc = upload(c, c->grptab, groups, (size_t)c->ngroups * sizeof(SegDesc));
     if (rc != DGS_OK) return rc;
     launch_fill_u32(c->hint2, 0u, (size_t)(W + 1) * J, c->stream);
     launch_fill_u32(c->tprev, 0u, (size_t)(W + 1) * J, c->stream);
@@ -617,12 +660,13 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     std::vector<uint32_t> tau0((size_t)(W + 1) * J);
     std::vector<SegDesc> segs(nseg_total + 1);
     std::vector<uint32_t> toff(J + 1);
+    std::vector<SegDesc> groups(nseg_total + 1);
     c->nseg.assign(J, 0u);
-    fill_tables(c, td.data(), tau0.data(), toff.data(), segs.data());
+    fill_tables(c, td.data(), tau0.data(), toff.data(), segs.data(), groups.data());
 
     bool ok = true;
     ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
-    ok = ok && upload_tables(c, td.data(), tau0.data(), toff.data(), segs.data()) == DGS_OK;
+    ok = ok && upload_tables(c, td.data(), tau0.data(), toff.data(), segs.data(), groups.data()) == DGS_OK;
     ok = ok && hipStreamSynchronize(c->stream) == hipSuccess;
     ok = ok && hipGetLastError() == hipSuccess;
     if (!ok) {
@@ -749,6 +793,7 @@ int dgs_worker_step_static(const uint64_t *offsets, uint32_t J, const float *gra
     TensorDesc td[DGS_STATIC_MAX_TENSORS];
     uint32_t tau0[DGS_STATIC_MAX_TENSORS], toff[DGS_STATIC_MAX_TENSORS + 1];
     SegDesc segs[STATIC_MAX_SEGS + 1];
+    SegDesc groups[STATIC_MAX_SEGS + 1];
     PlanEntry plan[DGS_STATIC_MAX_TENSORS];
     for (uint32_t j = 0; j <= J; ++j) offs[j] = offsets[j];
     dgs_ctx c;
@@ -764,10 +809,10 @@ int dgs_worker_step_static(const uint64_t *offsets, uint32_t J, const float *gra
     c.hint_density.borrow(hint_density);
     c.plan_stage = plan;               // one density per call: only the first cache slot is used
     carve_workspace(&c, ws, L);
-    fill_tables(&c, td, tau0, toff, segs);
+    fill_tables(&c, td, tau0, toff, segs, groups);
     // every call starts from a clean workspace (the array keeps the previous call's contents);
     // with no threshold hints the step takes the two-pass path
-    rc = upload_tables(&c, td, tau0, toff, segs);
+    rc = upload_tables(&c, td, tau0, toff, segs, groups);
     if (rc != DGS_OK) return rc;
     return run_selection(&c, OP_FMA, SEL_WORKER, grad, state, lr, m, density, 0, idx_out, val_out, nnz_out,
                          DGS_PROF_WORKER_STREAM, DGS_PROF_WORKER_SELECT, DGS_PROF_WORKER_SEGMENTED);

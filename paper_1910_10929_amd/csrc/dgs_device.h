@@ -34,8 +34,9 @@ constexpr uint32_t HSHIFT = 31 - HBITS;
 // Selection workgroup.
 constexpr uint32_t SEL_THREADS = 1024;
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
-constexpr uint32_t SEL_LDS_LIST = 8192;            // candidates kept in LDS (64 KB); longer lists continue in global scratch
-constexpr uint32_t SEL_LIST_MAX = 24576;           // longest candidate list one workgroup selects from
+constexpr uint32_t SEL_LDS_LIST = 12288;           // candidates kept in LDS (96 KB); longer lists continue in global scratch
+constexpr uint32_t SEL_LIST_MAX = 24576;           // longest candidate list one workgroup is planned for
+constexpr uint32_t SEL_LIST_HARD = 65536;          // longest it accepts when a tail has grown beyond the plan
 // Above this density candidates stop paying off; such requests select densely.
 constexpr double DENSE_DENSITY = 1.0 / 32.0;
 
@@ -47,6 +48,13 @@ constexpr double DENSE_DENSITY = 1.0 / 32.0;
 #define DGS_SEG_TILES 256
 #endif
 constexpr uint32_t SEG_TILES = DGS_SEG_TILES;
+// Join groups.  The candidates of consecutive parts of a tensor, up to about GROUP_TILES tiles,
+// are joined by one workgroup: a tensor of one group is selected by that workgroup straight
+// from LDS with no hand-over, larger tensors hand their groups' lists to the last to arrive.
+#ifndef DGS_GROUP_TILES
+#define DGS_GROUP_TILES 4096
+#endif
+constexpr uint32_t GROUP_TILES = DGS_GROUP_TILES;
 constexpr uint32_t SEG_THREADS = 256;
 constexpr uint32_t SEG_MIN_N = 65536;              // smaller tensors never take the chain
 constexpr uint32_t SEG_AUTO_N = 1u << 22;          // (kept for the plan: tensors this large always may)
@@ -72,7 +80,8 @@ struct TensorDesc {
     uint32_t seg_first;  // first entry of this tensor in the segment table
     uint32_t nseg;       // segments (0: the tensor never goes segmented)
     uint32_t pfx_slot;   // which PFX_CAP-sized block of the prefix list belongs to it
-    uint32_t pad0, pad1;
+    uint32_t grp_first;  // first entry of this tensor in the group table
+    uint32_t ngrp;       // its join groups (>= 1)
 };
 
 struct PlanEntry {
@@ -120,6 +129,7 @@ struct DevStats {
 // difference row);  OP_SUB: a = grad - state, nothing stored (pull on model - sent_k).
 enum StreamOp { OP_FMA = 0, OP_IDENT = 1, OP_SUB = 2 };
 enum StreamMode { MODE_PLAIN = 0, MODE_COLLECT = 1, MODE_HIST = 2 };
+enum StoreMode { STORE_PLAIN = 0, STORE_WT = 1, STORE_NT = 2 };
 // What happens to a sent entry: SEL_WORKER state <- m * val;  SEL_PULL state <- +0;
 // SEL_PULL_V state <- state + val (the values themselves are model - state).
 enum SelectOp { SEL_WORKER = 0, SEL_PULL = 1, SEL_PULL_V = 2 };
@@ -135,6 +145,7 @@ struct StreamArgs {
     uint32_t *ghist;              // per tensor HBINS counters
     uint32_t n, ntiles, nquads, quads_per_block, J;
     float lr;
+    uint32_t store_mode;          // OP_FMA: how the state is written back (StoreMode)
 };
 
 struct SelectArgs {
@@ -143,6 +154,7 @@ struct SelectArgs {
     const TensorDesc *tdesc;
     const PlanEntry *plan;
     const SegDesc *segtab;        // the parts, tensor after tensor
+    const SegDesc *grptab;        // the join groups in launch order (tensors of several groups first)
     uint32_t *tau;                // hints of this stream, updated
     uint32_t *tile_cnt;
     uint2 *heads;
@@ -153,6 +165,7 @@ struct SelectArgs {
     uint32_t *ghist;              // per tensor HBINS counters, all zero between uses
     SegState *segstate;
     uint32_t *segcnt;             // per part: candidates (bit 31: a tile of the part overflowed)
+    uint32_t *grpcnt;             // per join group: the same, for the lists joined by groups
     uint32_t *segG1;              // per part: candidates with a larger key prefix than the k-th
     uint2 *segOut;                // per part: (output position within the tensor, ties to take)
     uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, part, 0)
@@ -162,12 +175,14 @@ struct SelectArgs {
     const uint32_t *toff;         // J + 1 tensor offsets
     float m;                      // SEL_WORKER: sent entries keep m * a
     uint32_t n, ntiles, J, nparts;
+    uint32_t ngroups, gparts;     // join groups; parts per group
     uint32_t dense;               // dense request: no candidate lists; tensors with parts take the chain
                                   // reading their own elements, the others select from the state buffer
     uint32_t write_hint;
     uint32_t exact_mode;          // the threshold came from this call's histogram
     uint32_t repair;              // the launch carries the re-collecting workgroups
     uint32_t spin_limit;          // polls before a waiting workgroup gives up
+    uint32_t bgroup;              // parts looked after by one re-collecting workgroup
 };
 
 // Host-callable launchers (defined next to the kernels).

@@ -477,13 +477,16 @@ __device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
     return (uint32_t)x;
 }
 
-// Ordered-list entry: LDS while it fits, global scratch beyond.
+// Ordered-list entry: LDS while it fits, global scratch beyond.  The global lists are only ever
+// written through to memory (st_dev): a cached store by this workgroup would sit in its L2
+// and shadow what a workgroup elsewhere on the chip writes to the same place later in the
+// launch, when the tensor is collected again.
 __device__ __forceinline__ void put_entry(uint2 *llist, uint2 *glist, uint32_t pos, uint2 e)
 {
     if (pos < SEL_LDS_LIST) {
         llist[pos] = e;
     } else {
-        glist[pos] = e;
+        st_dev(&glist[pos], e);
         // keeps the two stores apart: merged into one store through a generic pointer they
         // would take the slow flat path into LDS
         asm volatile("" ::: "memory");

@@ -72,8 +72,8 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 // ---------------------------------------------------------------------------
 //
 // Grid: block b < P is the JOIN of part b (1024 threads).  With the re-collecting roles
-// enabled, ceil(P / B_GROUP) RE-HISTOGRAM blocks follow, then as many RE-COLLECTION blocks,
-// each looking after B_GROUP consecutive parts in turn (they act on tensors of several parts
+// enabled, ceil(P / bgroup) RE-HISTOGRAM blocks follow, then as many RE-COLLECTION blocks,
+// each looking after `bgroup` consecutive parts in turn (they act on tensors of several parts
 // whose prediction failed, and pass over everything else).
 //
 //   JOIN      compacts the candidates the streaming pass left in the part's tiles into one
@@ -94,12 +94,18 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 // Waiting is only ever for blocks with a lower index, which the hardware dispatches first,
 // and every wait is bounded (A.spin_limit polls).
 
-constexpr uint32_t B_GROUP = 8;   // parts looked after by one re-collecting workgroup
+constexpr uint32_t B_GROUP_MAX = 8;   // most parts one re-collecting workgroup looks after
 
 struct PartShared {
     SelShared S;
     uint32_t pbase[SEG_MAX_PER_TENSOR + 1];   // first list position of every part of the tensor
+    uint32_t pofs[SEG_MAX_PER_TENSOR];        // where every part's global list starts (entries into ord)
     uint32_t wtot[SEL_WAVES];
+    uint32_t vbuf[B_GROUP_MAX];               // verdicts of the tensors of a re-collecting workgroup's parts
+    uint32_t tile_pos[SEL_THREADS];           // JOIN: list position and count of every tile of the round
+    uint32_t tile_n[SEL_THREADS];
+    uint32_t crowd_tile[SEL_THREADS];         // JOIN: tiles of the round that take the per-entry loop,
+    uint32_t crowd_pos[SEL_THREADS];          //       their list positions
     uint32_t bc;
 };
 
@@ -109,69 +115,91 @@ __device__ __forceinline__ uint2 tile_entry(const uint2 *hd, const uint2 *sl, ui
     return (q < HEAD) ? hd[q] : sl[q];
 }
 
-// JOIN of one part: the candidates of tensor j in tiles [sd.tile0, sd.tile0 + sd.ntiles), in
-// index order, through `put(position, entry)`.  Returns the count; `ovf` is set if a tile had
-// overflowed its slots.  Rounds of 256 tiles: four lanes per tile fetch its count and its
-// first line (8 candidates) at once; a workgroup scan of the counts gives every tile its list
-// position; crowded tiles and a first tile shared with the previous tensor take a per-entry loop.
+// What a tile's counter word says about tensor td's candidates in tile t: how many, and after
+// how many of the previous tensor's (a first tile shared with it).  An overflowed tile, or a
+// count beyond the slots (a corrupted word), sets ovf and counts as empty.
+__device__ __forceinline__ void tile_counts(uint32_t w, uint32_t t, uint32_t tlo, bool head_shared, uint32_t &n_t,
+                                            uint32_t &start, int &ovf)
+{
+    n_t = 0;
+    start = 0;
+    if (w == CNT_OVERFLOW) {
+        ovf = 1;
+    } else if (head_shared && t == tlo) {
+        start = w & 0xFFFFu;      // the previous tensor's candidates come first in this tile
+        n_t = w >> 16;
+    } else {
+        n_t = w & 0xFFFFu;
+    }
+    if (start + n_t > CAPT) {
+        ovf = 1;
+        n_t = 0;
+        start = 0;
+    }
+}
+
+// JOIN of a run of tiles: the candidates of tensor j in tiles [sd.tile0, sd.tile0 + sd.ntiles),
+// in index order, through `put(position, entry)`.  Returns the count; `ovf` is set if a tile had
+// overflowed its slots.  Rounds of SEL_THREADS tiles.  Every lane takes one tile's count; a
+// workgroup scan of the counts gives every tile its list position.  The tiles' first lines (8
+// candidates, 64 bytes) are fetched as the contiguous stretch they are -- four lanes per line,
+// four lines per lane -- and put in place with the positions read back from LDS; crowded tiles
+// and a first tile shared with the previous tensor go to a worklist that the wavefronts then
+// copy entry by entry.
 template <class Put>
 __device__ __forceinline__ uint32_t join_part(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd,
                                               PartShared &P, bool &ovf_out, Put put)
 {
-    const uint32_t tid = threadIdx.x;
+    const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
     const uint32_t tlo = td.off / TILE;
     const bool head_shared = (td.off % TILE) != 0;
-    const uint32_t qt = tid >> 2, sub = tid & 3u;
     uint32_t base = 0;
     int ovf = 0;
-    for (uint32_t r0 = 0; r0 < sd.ntiles; r0 += SEL_THREADS / 4) {
-        const uint32_t tl = r0 + qt;
-        const bool in = tl < sd.ntiles;
-        const uint32_t t = sd.tile0 + tl;
-        uint32_t w = 0;
-        uint4 pf = make_uint4(0, 0, 0, 0);
-        if (in) {
-            w = A.tile_cnt[t];
-            pf = ((const uint4 *)(A.heads + (size_t)t * HEAD))[sub];
+    for (uint32_t r0 = 0; r0 < sd.ntiles; r0 += SEL_THREADS) {
+        // lines of this wavefront's 64 tiles: load v covers tiles 16 v .. 16 v + 15
+        uint4 pf[4];
+#pragma unroll
+        for (uint32_t v = 0; v < 4; ++v) {
+            const uint32_t tl = r0 + wave * 64u + v * 16u + (lane >> 2);
+            pf[v] = (tl < sd.ntiles) ? ((const uint4 *)(A.heads + (size_t)(sd.tile0 + tl) * HEAD))[lane & 3u]
+                                     : make_uint4(0, 0, 0, 0);
         }
-        uint32_t n_t = 0, start = 0;
-        if (w == CNT_OVERFLOW) {
-            ovf = 1;
-        } else if (head_shared && t == tlo) {
-            start = w & 0xFFFFu;      // the previous tensor's candidates come first in this tile
-            n_t = w >> 16;
-        } else {
-            n_t = w & 0xFFFFu;
-        }
-        if (start + n_t > CAPT) {   // no tile holds more than its slots: a corrupted count
-            ovf = 1;
-            n_t = 0;
-            start = 0;
-        }
+        const uint32_t t = sd.tile0 + r0 + tid;
+        const uint32_t w = (r0 + tid < sd.ntiles) ? A.tile_cnt[t] : 0u;
+        uint32_t n_t, start;
+        tile_counts(w, t, tlo, head_shared, n_t, start, ovf);
+        // one scan for both: list positions (low 19 bits: at most 2^18 candidates a round) and
+        // worklist slots of the crowded tiles (the bits above)
+        const bool crowded = n_t != 0 && (start != 0 || n_t > HEAD);
         uint32_t total;
-        const uint32_t excl = block_excl_scan<SEL_WAVES>(sub == 0 ? n_t : 0u, P.S.wsum, total);
-        const uint32_t pos = base + (sub == 0 ? excl : excl - n_t);
-        base += total;
-        if (n_t == 0) continue;
-        uint32_t i0 = 0;
-        if (start == 0) {
-            if (2 * sub < n_t) put(pos + 2 * sub, make_uint2(pf.x, pf.y));
-            if (2 * sub + 1 < n_t) put(pos + 2 * sub + 1, make_uint2(pf.z, pf.w));
-            i0 = HEAD;
+        const uint32_t excl = block_excl_scan<SEL_WAVES>(n_t | (crowded ? 1u << 19 : 0u), P.S.wsum, total);
+        const uint32_t pos = base + (excl & 0x7FFFFu);
+        const uint32_t nc = total >> 19;
+        base += total & 0x7FFFFu;
+        P.tile_pos[tid] = pos;
+        P.tile_n[tid] = crowded ? 0u : n_t;
+        if (crowded) {
+            P.crowd_tile[excl >> 19] = t;
+            P.crowd_pos[excl >> 19] = pos;
         }
-        if (i0 < n_t) {
-            const uint2 *hd = A.heads + (size_t)t * HEAD;
-            const uint2 *sl = A.slots + (size_t)t * CAPT;
-            for (uint32_t i = i0 + sub; i < n_t; i += 16) {
-                uint2 e[4];
+        __syncthreads();
 #pragma unroll
-                for (uint32_t v = 0; v < 4; ++v)
-                    e[v] = (i + 4 * v < n_t) ? tile_entry(hd, sl, start + i + 4 * v) : make_uint2(0, 0);
-#pragma unroll
-                for (uint32_t v = 0; v < 4; ++v)
-                    if (i + 4 * v < n_t) put(pos + i + 4 * v, e[v]);
-            }
+        for (uint32_t v = 0; v < 4; ++v) {
+            const uint32_t slot = wave * 64u + v * 16u + (lane >> 2);
+            const uint32_t n = P.tile_n[slot], p = P.tile_pos[slot], e0 = 2u * (lane & 3u);
+            if (e0 < n) put(p + e0, make_uint2(pf[v].x, pf[v].y));
+            if (e0 + 1 < n) put(p + e0 + 1, make_uint2(pf[v].z, pf[v].w));
         }
+        for (uint32_t q = wave; q < nc; q += SEL_WAVES) {
+            const uint32_t tc = P.crowd_tile[q], pc = P.crowd_pos[q];
+            uint32_t n_c, start_c;
+            int o = 0;
+            tile_counts(A.tile_cnt[tc], tc, tlo, head_shared, n_c, start_c, o);
+            const uint2 *hd = A.heads + (size_t)tc * HEAD;
+            const uint2 *sl = A.slots + (size_t)tc * CAPT;
+            for (uint32_t i = lane; i < n_c; i += 64) put(pc + i, tile_entry(hd, sl, start_c + i));
+        }
+        // (the next round rewrites positions and worklist behind the two barriers of its scan)
     }
     ovf_out = __syncthreads_or(ovf) != 0;
     return base;
@@ -289,6 +317,8 @@ __device__ __forceinline__ uint32_t dense_compact(const SelectArgs &A, const Ten
             }
         }
     }
+    // the two passes must have seen the same elements
+    if (lane == 0 && run - before != wsum_) atomicAdd(&A.stats->internal_errors, 1ull);
     return total;
 }
 
@@ -449,16 +479,18 @@ __device__ __forceinline__ void list_select(const SelectArgs &A, const TensorDes
     const uint32_t tid = threadIdx.x;
     if (c > SEL_LDS_LIST) {
         // the list outgrew LDS: complete the global copy
-        for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
+        for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) st_dev(&glist[p], llist[p]);
         __syncthreads();
     }
     uint32_t R = 0, Eq = 0;
     if (A.write_hint) R = hint_rank<OP>(td, pe, !exact_mode, c, hint2_cur, A.m, &Eq);
     uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
-    // the histogram counted on the way stands if no candidate lies below the threshold (none can)
-    const bool win_ready = win_counted && (kmin != 0xFFFFFFFFu) && (kmin >> 11) >= (tau_cur >> 11);
-    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (win_ready ? win_join : (kmin >> 11));
-    const uint32_t win_min = (win_ready && win_join > (kmin >> 11)) ? 1u : 0u;   // entries below the window
+    // the window placed by the hints serves if no candidate lies below the threshold (none can);
+    // a histogram counted on the way then stands as it is
+    const bool anchored = (win_join != 0xFFFFFFFFu) && (kmin != 0xFFFFFFFFu) && (kmin >> 11) >= (tau_cur >> 11);
+    const bool win_ready = win_counted && anchored;
+    const uint32_t win_base = (kmin == 0xFFFFFFFFu) ? 0xFFFFFFFFu : (anchored ? win_join : (kmin >> 11));
+    const uint32_t win_min = (anchored && win_join > (kmin >> 11)) ? 1u : 0u;   // entries below the window
     if (c <= SEL_LDS_LIST) {
         SrcList src{llist};
         select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, P.S, A, pe.outoff,
@@ -488,9 +520,9 @@ __device__ __forceinline__ void list_select(const SelectArgs &A, const TensorDes
 struct SrcParts {
     static constexpr bool AGG = true;
     const uint2 *ord;
-    const SegDesc *parts;      // the tensor's parts
-    const uint32_t *pbase;
-    uint32_t nseg, j;
+    const uint32_t *pbase;     // LDS: first list position of every part
+    const uint32_t *pofs;      // LDS: where every part's list starts in ord
+    uint32_t nseg;
     __device__ __forceinline__ uint2 get(uint32_t p) const
     {
         uint32_t lo = 0, hi = nseg;       // last part whose first position is <= p
@@ -499,7 +531,7 @@ struct SrcParts {
             if (pbase[mid] <= p) lo = mid;
             else hi = mid;
         }
-        return ld_dev(&ord[(size_t)(parts[lo].tile0 + j) * CAPT + (p - pbase[lo])]);
+        return ld_dev(&ord[(size_t)pofs[lo] + (p - pbase[lo])]);
     }
     __device__ __forceinline__ uint32_t bits(uint32_t p) const { return get(p).y; }
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return get(p).x; }
@@ -509,60 +541,73 @@ struct SrcParts {
 // streaming pass's candidates, 1: re-collected with a fresh threshold).  Returns the tensor's
 // status: SEG_DONE, SEG_ACTIVE / SEG_ALL (the chain kernels go on), or SEG_PENDING (round 0
 // only: collect again).
-//   multi: the lists are the parts' global lists (counts in segcnt) and are gathered here;
-//   otherwise the single part's list is in llist / glist (or, for a tensor that takes the
-//   chain, in its global list only) with count c0, overflow ovf0, smallest key (or a lower
-//   bound of it) kmin0, and -- win_counted -- the window histogram counted on the way.
+//   multi: the lists are global lists of several units -- the tensor's parts (by_parts: counts
+//   in segcnt) or its join groups (counts in grpcnt) -- and are gathered here; otherwise the
+//   one list is in llist / glist (or, for a tensor that takes the chain, in its global list
+//   only) with count c0, overflow ovf0, smallest key (or a lower bound of it) kmin0, and --
+//   win_counted -- the window histogram counted on the way.
+//   verdict: where the outcome is published for the re-collecting workgroups of the launch
+//   (null: nobody waits); a success is published as soon as it is certain, before the work.
 //   tau_cur, tprev_cur: the threshold the lists were collected with and the anchor of the window
 //   histograms (handed in: in round 1 they were published by another workgroup of this launch).
 template <int OP>
 __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const TensorDesc &td, const PlanEntry &pe,
-                                                  uint32_t j, int round, bool multi, uint32_t c0, bool ovf0,
-                                                  uint32_t kmin0, uint32_t tau_cur, uint32_t tprev_cur,
-                                                  uint32_t win_join, bool win_counted, PartShared &P, uint2 *llist)
+                                                  uint32_t j, int round, bool multi, bool by_parts, uint32_t c0,
+                                                  bool ovf0, uint32_t kmin0, uint32_t tau_cur, uint32_t tprev_cur,
+                                                  uint32_t win_join, bool win_counted, uint32_t *verdict,
+                                                  PartShared &P, uint2 *llist)
 {
     const uint32_t tid = threadIdx.x;
     const uint32_t tlo = td.off / TILE;
     uint2 *glist = A.ord + (size_t)(tlo + j) * CAPT;      // = the first part's list
     const bool exact_mode = A.exact_mode || round != 0;
     const uint32_t hint2_cur = A.write_hint ? A.hint2[j] : 0u;
-    const bool have_pbase = td.nseg <= SEG_MAX_PER_TENSOR;
+    const uint32_t nunits = by_parts ? td.nseg : td.ngrp;
+    const SegDesc *units = by_parts ? A.segtab + td.seg_first : A.grptab + td.grp_first;
+    const uint32_t *ucnt = by_parts ? A.segcnt + td.seg_first : A.grpcnt + td.grp_first;
+    const bool have_pbase = nunits <= SEG_MAX_PER_TENSOR;
     // The longest list this workgroup selects from.  A tensor of several parts is gathered in
     // place: what does not fit the LDS list goes to the first part's global list, which must
     // end before the second part's begins.
-    const uint32_t list_max = multi ? max(SEL_LDS_LIST, min(SEL_LIST_MAX, A.segtab[td.seg_first].ntiles * CAPT))
-                                    : SEL_LIST_MAX;
+    const uint32_t list_max = multi ? max(SEL_LDS_LIST, min(SEL_LIST_HARD, units[0].ntiles * CAPT))
+                                    : SEL_LIST_HARD;
     uint32_t c = c0, kmin = kmin0;
     bool ovf = ovf0;
     if (multi) {
-        // counts of the parts -> list positions
+        // counts of the units -> list positions
         uint32_t o = 0;
         c = 0;
-        for (uint32_t s0 = 0; s0 < td.nseg; s0 += SEL_THREADS) {
+        for (uint32_t s0 = 0; s0 < nunits; s0 += SEL_THREADS) {
             const uint32_t s = s0 + tid;
-            uint32_t cnt = (s < td.nseg) ? ld_dev(&A.segcnt[td.seg_first + s]) : 0u;
+            uint32_t cnt = (s < nunits) ? ld_dev(&ucnt[s]) : 0u;
             if (cnt >> 31) o = 1;
             cnt &= 0x7FFFFFFFu;
             uint32_t tot;
             const uint32_t ex = block_excl_scan<SEL_WAVES>(cnt, P.S.wsum, tot);
-            if (s < td.nseg && have_pbase) P.pbase[s] = c + ex;
+            if (s < nunits && have_pbase) {
+                P.pbase[s] = c + ex;
+                P.pofs[s] = (units[s].tile0 + j) * CAPT;   // below 2^32: n < 2^32
+            }
             c += tot;
         }
-        if (tid == 0 && have_pbase) P.pbase[td.nseg] = c;
+        if (tid == 0 && have_pbase) P.pbase[nunits] = c;
         ovf = __syncthreads_or((int)o) != 0;
     }
     uint32_t status = 0;
+    bool early = false;      // the verdict went out before the work
     // every nonzero is in the lists (a dense request has no lists: it falls back instead)
     const bool zerofill = !A.dense && !ovf && c < pe.k && tau_cur <= 1u && (!multi || have_pbase);
     if (pe.seg) status = window_step<OP>(A, td, pe, j, c, ovf, tau_cur, tprev_cur, exact_mode, P);
     if (status == 0 && zerofill) {
         // the message is completed with the tensor's lowest-index zeros
+        early = true;
+        if (verdict && tid == 0) st_dev(verdict, 0x100u | (uint32_t)SEG_DONE);
         if (multi) {
-            zero_fill_emit<OP>(SrcParts{A.ord, A.segtab + td.seg_first, P.pbase, td.nseg, j}, c, td, pe, A, P.S.wsum);
+            zero_fill_emit<OP>(SrcParts{A.ord, P.pbase, P.pofs, nunits}, c, td, pe, A, P.S.wsum);
         } else if (pe.seg) {
             zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
         } else if (c > SEL_LDS_LIST) {
-            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) glist[p] = llist[p];
+            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) st_dev(&glist[p], llist[p]);
             wait_mem();
             __syncthreads();
             zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
@@ -577,26 +622,32 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
         if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
         status = SEG_DONE;
     } else if (!pe.seg && !ovf && c >= pe.k && c <= list_max && (!multi || have_pbase)) {
+        early = true;
+        if (verdict && tid == 0) st_dev(verdict, 0x100u | (uint32_t)SEG_DONE);
         if (multi) {
             // gather the parts' lists into one (positions beyond the LDS list land in the first
             // part's global list: on dead space, or on the very entry that is being moved)
+            const bool count_win = (win_join != 0xFFFFFFFFu);   // the hinted window is counted on the way
+            for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
             if (tid == 0) P.S.kmin = 0xFFFFFFFFu;
             __syncthreads();
-            const SrcParts src{A.ord, A.segtab + td.seg_first, P.pbase, td.nseg, j};
+            const SrcParts src{A.ord, P.pbase, P.pofs, nunits};
             uint32_t km = 0xFFFFFFFFu;
-            for (uint32_t q0 = 0; q0 < c; q0 += 4 * SEL_THREADS) {
-                uint2 e[4];
+            constexpr uint32_t GU = 8;      // entries per thread in flight
+            for (uint32_t q0 = 0; q0 < c; q0 += GU * SEL_THREADS) {
+                uint2 e[GU];
 #pragma unroll
-                for (uint32_t u = 0; u < 4; ++u) {
+                for (uint32_t u = 0; u < GU; ++u) {
                     const uint32_t q = q0 + u * SEL_THREADS + tid;
                     e[u] = (q < c) ? src.get(q) : make_uint2(0, 0);
                 }
 #pragma unroll
-                for (uint32_t u = 0; u < 4; ++u) {
+                for (uint32_t u = 0; u < GU; ++u) {
                     const uint32_t q = q0 + u * SEL_THREADS + tid;
                     if (q < c) {
                         put_entry(llist, glist, q, e[u]);
                         km = min(km, e[u].y & 0x7FFFFFFFu);
+                        if (count_win) window_count(P.S.h, win_join, e[u].y & 0x7FFFFFFFu);
                     }
                 }
             }
@@ -606,8 +657,8 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
             __syncthreads();
             kmin = P.S.kmin;
         }
-        list_select<OP>(A, td, pe, j, c, kmin, tau_cur, hint2_cur, win_join, win_counted && !multi, exact_mode, P,
-                        llist, glist);
+        list_select<OP>(A, td, pe, j, c, kmin, tau_cur, hint2_cur, win_join,
+                        multi ? (win_join != 0xFFFFFFFFu) : win_counted, exact_mode, P, llist, glist);
         if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
         status = SEG_DONE;
     }
@@ -623,11 +674,16 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
         atomicAdd(&A.stats->repaired_tensors, 1ull);
     }
     if (tid == 0) A.segstate[j].status = status;
+    if (verdict && !early) {
+        wait_mem();
+        __syncthreads();
+        if (tid == 0) st_dev(verdict, 0x100u | status);
+    }
     return status;
 }
 
-// RE-HISTOGRAM (role 1) or RE-COLLECTION (role 2) of one part; returns at once unless the
-// part's tensor has several parts and was left pending by the JOIN.
+// RE-HISTOGRAM (role 1) or RE-COLLECTION (role 2) of one part of a tensor that the JOIN left
+// pending (the caller has seen that verdict).
 template <int OP>
 __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t role, uint32_t part, PartShared &P,
                                                uint2 *llist)
@@ -642,12 +698,6 @@ __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t rol
     uint2 *plist = A.ord + (size_t)(sd.tile0 + j) * CAPT;       // this part's list
     const uint32_t part_cap = sd.ntiles * CAPT;
     if (!multi) return;
-    const uint32_t verdict = wait_word(&st->verdict, A.spin_limit, &P.bc);
-    if (tid == 0) {
-        if (verdict == 0) atomicAdd(&A.stats->internal_errors, 1ull);   // gave up waiting
-        reader_done(&st->seen[0], 2u * td.nseg, &st->verdict);
-    }
-    if ((verdict & 0xFFu) != SEG_PENDING) return;
     uint32_t *gh = A.ghist + (size_t)j * HBINS;
     if (role == 1) {
         uint32_t *lh = (uint32_t *)llist;
@@ -676,7 +726,7 @@ __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t rol
     const uint32_t ready = wait_word(&st->tau_ready, A.spin_limit, &P.bc);
     if (tid == 0) {
         if (ready == 0) atomicAdd(&A.stats->internal_errors, 1ull);
-        reader_done(&st->seen[1], td.nseg, &st->tau_ready);
+        reader_done(&st->seen[1], td.nseg, 1u, &st->tau_ready);
     }
     if (ready == 0) return;
     const uint32_t tau_new = ld_dev(&A.tau[j]);
@@ -687,7 +737,7 @@ __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t rol
     uint32_t c2;
     if (pe.seg) {
         c2 = dense_compact<OP>(A, td, sd, tau_new, part_cap, P, [&](uint32_t pos, uint2 e) {
-            plist[pos] = e;
+            st_dev(&plist[pos], e);
             const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
             const uint32_t w = (hi12 > win2) ? (hi12 - win2) : 0u;
             atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
@@ -704,7 +754,8 @@ __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t rol
     }
     if (tid == 0) st_dev(&A.segcnt[part], min(c2, 0x7FFFFFFFu) | (c2 > part_cap ? 0x80000000u : 0u));
     if (!arrive_last(&st->arrive[2], td.nseg, &P.bc)) return;
-    tensor_select<OP>(A, td, pe, j, 1, true, 0u, false, 0xFFFFFFFFu, tau_new, tprev_new, 0u, false, P, llist);
+    tensor_select<OP>(A, td, pe, j, 1, true, true, 0u, false, 0xFFFFFFFFu, tau_new, tprev_new, 0xFFFFFFFFu, false,
+                      nullptr, P, llist);
 }
 
 template <int OP>
@@ -713,24 +764,50 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
     __shared__ PartShared P;
     __shared__ uint2 llist[SEL_LDS_LIST];
     const uint32_t tid = threadIdx.x;
-    if (blockIdx.x >= A.nparts) {
+    if (blockIdx.x >= A.ngroups) {
         // RE-HISTOGRAM / RE-COLLECTION: this workgroup looks after B_GROUP consecutive parts
-        const uint32_t nb = (A.nparts + B_GROUP - 1) / B_GROUP;
-        const uint32_t b = blockIdx.x - A.nparts;
+        const uint32_t nb = (A.nparts + A.bgroup - 1) / A.bgroup;
+        const uint32_t b = blockIdx.x - A.ngroups;
         const uint32_t role = (b < nb) ? 1u : 2u;
-        const uint32_t first = (role == 1 ? b : b - nb) * B_GROUP;
-        for (uint32_t part = first; part < min(first + B_GROUP, A.nparts); ++part)
-            recollect_part<OP>(A, role, part, P, llist);
+        const uint32_t first = (role == 1 ? b : b - nb) * A.bgroup;
+        const uint32_t cnt = min(first + A.bgroup, A.nparts) - first;
+        // the verdicts of the tensors these parts belong to: lane i waits for part i's tensor if
+        // that part is the first of its tensor in the group (parts of a tensor are consecutive),
+        // and signs off for all of the tensor's parts in the group at once
+        if (tid < B_GROUP_MAX) P.vbuf[tid] = 0;
+        __syncthreads();
+        if (tid < cnt) {
+            const SegDesc sd = A.segtab[first + tid];
+            const bool head = (tid == 0) || (A.segtab[first + tid - 1].j != sd.j);
+            if (A.tdesc[sd.j].nseg > 1 && head) {
+                SegState *st = &A.segstate[sd.j];
+                uint32_t mine = 1;
+                while (tid + mine < cnt && A.segtab[first + tid + mine].j == sd.j) ++mine;
+                uint32_t v = 0;
+                for (uint32_t spin = 0; spin < A.spin_limit; ++spin) {
+                    v = ld_dev(&st->verdict);
+                    if (v != 0) break;
+                    __builtin_amdgcn_s_sleep(4);
+                }
+                if (v == 0) atomicAdd(&A.stats->internal_errors, 1ull);   // gave up waiting
+                reader_done(&st->seen[0], 2u * A.tdesc[sd.j].nseg, mine, &st->verdict);
+                for (uint32_t i = 0; i < mine; ++i) P.vbuf[tid + i] = v;
+            }
+        }
+        __syncthreads();
+        for (uint32_t i = 0; i < cnt; ++i)
+            if ((P.vbuf[i] & 0xFFu) == SEG_PENDING) recollect_part<OP>(A, role, first + i, P, llist);
         return;
     }
-    const uint32_t part = blockIdx.x;
-    const SegDesc sd = A.segtab[part];
+    const SegDesc sd = A.grptab[blockIdx.x];      // this workgroup's join group
     const uint32_t j = sd.j;
     const TensorDesc td = A.tdesc[j];
     const PlanEntry pe = A.plan[j];
-    const bool multi = td.nseg > 1;
+    const bool multi = td.ngrp > 1;               // the groups' lists go to the last group to arrive
+    const bool has_parts = td.nseg > 1;           // a failed prediction is collected again part by part
+    const uint32_t part = td.seg_first;           // (the part, where the tensor has only one)
     SegState *st = &A.segstate[j];
-    uint2 *plist = A.ord + (size_t)(sd.tile0 + j) * CAPT;       // this part's list
+    uint2 *plist = A.ord + (size_t)(sd.tile0 + j) * CAPT;       // this group's list
     const uint32_t part_cap = sd.ntiles * CAPT;
     const bool chain_dense = A.dense && pe.seg;                  // the chain reads the tensor itself
 
@@ -750,23 +827,58 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
         // that lies far below (a relaxed hint), 1024 buckets under the previous k-th key
         const uint32_t win_join = max(tau_cur >> 11, max(tprev_cur >> 11, 1024u) - 1024u);
         const uint32_t win_seg = seg_window_base(tau_cur, tprev_cur);
-        if (pe.seg || !multi) {
+        uint32_t *verdict = (has_parts && A.repair) ? &st->verdict : nullptr;
+        uint32_t status;
+        if (pe.seg) {
+            // a tensor that takes the chain: lists, counts and window histogram part by part
+            const uint32_t p0 = td.seg_first + sd.sidx * A.gparts;
+            const uint32_t p1 = min(p0 + A.gparts, td.seg_first + td.nseg);
+            uint32_t *gh = A.ghist + (size_t)j * HBINS;
+            for (uint32_t p = p0; p < p1; ++p) {
+                const SegDesc ps = A.segtab[p];
+                uint2 *pl = A.ord + (size_t)(ps.tile0 + j) * CAPT;
+                for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+                __syncthreads();
+                bool o = false;
+                uint32_t cp;
+                if (chain_dense) {
+                    cp = dense_window_count<OP>(A, td, ps, tau_cur, win_seg, P.S.h, P.S.wsum);
+                } else {
+                    cp = join_part(A, td, ps, P, o, [&](uint32_t pos, uint2 e) {
+                        st_dev(&pl[pos], e);          // read by the chain kernels, and by a zero fill
+                        const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
+                        const uint32_t w = (hi12 > win_seg) ? (hi12 - win_seg) : 0u;
+                        atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
+                    });
+                }
+                __syncthreads();
+                for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+                    const uint32_t v = P.S.h[b];
+                    if (v) atomicAdd(&gh[b], v);
+                }
+                if (tid == 0) st_dev(&A.segcnt[p], cp | (o ? 0x80000000u : 0u));
+                cs += cp;
+                ovf = ovf || o;
+                __syncthreads();
+            }
+            if (multi) {
+                if (!arrive_last(&st->arrive[0], td.ngrp, &P.bc)) return;
+            } else {
+                wait_mem();       // counts and histogram are read back below
+                __syncthreads();
+            }
+            status = tensor_select<OP>(A, td, pe, j, 0, has_parts, true, cs, ovf, kmin, tau_cur, tprev_cur, win_join,
+                                       true, verdict, P, llist);
+        } else if (multi) {
+            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) { st_dev(&plist[pos], e); });
+            if (tid == 0) st_dev(&A.grpcnt[blockIdx.x], cs | (ovf ? 0x80000000u : 0u));
+            if (!arrive_last(&st->arrive[0], td.ngrp, &P.bc)) return;
+            status = tensor_select<OP>(A, td, pe, j, 0, true, false, cs, ovf, kmin, tau_cur, tprev_cur, win_join, true,
+                                       verdict, P, llist);
+        } else {
             for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
             if (tid == 0) P.S.kmin = 0xFFFFFFFFu;
             __syncthreads();
-        }
-        if (chain_dense) {
-            cs = dense_window_count<OP>(A, td, sd, tau_cur, win_seg, P.S.h, P.S.wsum);
-        } else if (pe.seg) {
-            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) {
-                st_dev(&plist[pos], e);               // read by the chain kernels, and by a zero fill
-                const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
-                const uint32_t w = (hi12 > win_seg) ? (hi12 - win_seg) : 0u;
-                atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
-            });
-        } else if (multi) {
-            cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) { st_dev(&plist[pos], e); });
-        } else {
             uint2 *glist = plist;
             cs = join_part(A, td, sd, P, ovf, [&](uint32_t pos, uint2 e) {
                 put_entry(llist, glist, pos, e);
@@ -778,33 +890,10 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
             wait_mem();
             __syncthreads();
             kmin = P.S.kmin;
+            status = tensor_select<OP>(A, td, pe, j, 0, false, false, cs, ovf, kmin, tau_cur, tprev_cur, win_join, true,
+                                       verdict, P, llist);
         }
-        if (pe.seg) {
-            // the part's share of the tensor's window histogram
-            __syncthreads();
-            uint32_t *gh = A.ghist + (size_t)j * HBINS;
-            for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
-                const uint32_t v = P.S.h[b];
-                if (v) atomicAdd(&gh[b], v);
-            }
-        }
-        if (multi) {
-            if (tid == 0) st_dev(&A.segcnt[part], cs | (ovf ? 0x80000000u : 0u));
-            if (!arrive_last(&st->arrive[0], td.nseg, &P.bc)) return;
-        } else if (pe.seg) {
-            if (tid == 0) A.segcnt[part] = cs;
-            wait_mem();       // the histogram is read back below
-            __syncthreads();
-        }
-        uint32_t status = tensor_select<OP>(A, td, pe, j, 0, multi, cs, ovf, kmin, tau_cur, tprev_cur, win_join, true, P, llist);
-        if (multi) {
-            if (A.repair) {
-                wait_mem();
-                __syncthreads();
-                if (tid == 0) st_dev(&st->verdict, 0x100u | status);
-            }
-            return;
-        }
+        if (has_parts) return;        // the re-collecting workgroups have the verdict
         if (status != SEG_PENDING) return;
         // ---- a tensor of one part whose prediction failed: collect again on the spot
         uint32_t *lh = (uint32_t *)llist;
@@ -821,11 +910,11 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
         for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
         __syncthreads();
         const uint32_t win2 = seg_window_base(tau_new, tprev_new);
-        const uint32_t cap = pe.seg ? part_cap : min(part_cap, SEL_LIST_MAX);
+        const uint32_t cap = pe.seg ? part_cap : min(part_cap, SEL_LIST_HARD);
         uint32_t c2;
         if (pe.seg) {
             c2 = dense_compact<OP>(A, td, sd, tau_new, cap, P, [&](uint32_t pos, uint2 e) {
-                plist[pos] = e;
+                st_dev(&plist[pos], e);
                 const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
                 const uint32_t w = (hi12 > win2) ? (hi12 - win2) : 0u;
                 atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
@@ -846,7 +935,8 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
         wait_mem();
         __syncthreads();
         // kmin unknown (0 keeps the window honest: it is counted again from the list)
-        tensor_select<OP>(A, td, pe, j, 1, false, c2, c2 > cap, tau_new, tau_new, tprev_new, 0u, false, P, llist);
+        tensor_select<OP>(A, td, pe, j, 1, false, true, c2, c2 > cap, tau_new, tau_new, tprev_new, 0xFFFFFFFFu, false,
+                          nullptr, P, llist);
         return;
     }
 
@@ -855,9 +945,9 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
 void launch_select(int op, const SelectArgs &a, void *stream, void *ev0, void *ev1)
 {
     hipStream_t st = (hipStream_t)stream;
-    if (a.nparts == 0) return;
-    const uint32_t nb = (a.nparts + B_GROUP - 1) / B_GROUP;
-    const dim3 grid(a.nparts + (a.repair ? 2u * nb : 0u)), block(SEL_THREADS);
+    if (a.ngroups == 0) return;
+    const uint32_t nb = (a.nparts + a.bgroup - 1) / a.bgroup;
+    const dim3 grid(a.ngroups + (a.repair ? 2u * nb : 0u)), block(SEL_THREADS);
     if (op == SEL_WORKER) launch_k(k_select<SEL_WORKER>, grid, block, st, ev0, ev1, a);
     else if (op == SEL_PULL) launch_k(k_select<SEL_PULL>, grid, block, st, ev0, ev1, a);
     else launch_k(k_select<SEL_PULL_V>, grid, block, st, ev0, ev1, a);

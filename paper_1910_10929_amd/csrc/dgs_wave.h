@@ -57,6 +57,24 @@ __device__ __forceinline__ uint2 ld_dev(const uint2 *p)
         __hip_atomic_load((const unsigned long long *)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     return make_uint2((uint32_t)x, (uint32_t)(x >> 32));
 }
+// 16-byte device-scope (write-through) store at base + byte_off; `base` must be wave-uniform
+// and the 16 bytes must lie within 1 MB of it.
+#ifdef DGS_HOST_EMULATION
+__device__ __forceinline__ void store_through16(float *base, uint32_t byte_off, f32x4 v)
+{
+    *(f32x4 *)((char *)base + byte_off) = v;
+}
+#else
+typedef unsigned u32x4_store __attribute__((__vector_size__(16)));
+__device__ __forceinline__ void store_through16(float *base, uint32_t byte_off, f32x4 v)
+{
+    const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(base, 0, 1 << 20, 0x00020000);
+    u32x4_store u;
+    __builtin_memcpy(&u, &v, 16);
+    __builtin_amdgcn_raw_buffer_store_b128(u, r, (int)byte_off, 0, 16);   // aux 16: sc1 = device scope
+}
+#endif
+
 // All vector memory operations of this wavefront (stores and atomics included) are complete.
 #ifdef DGS_HOST_EMULATION   // CPU build of the kernels for sanitizer runs: no such instruction, nothing to wait for
 __device__ __forceinline__ void wait_mem() {}
@@ -94,7 +112,7 @@ __device__ __forceinline__ uint32_t wait_word(const uint32_t *p, uint32_t limit,
         for (uint32_t spin = 0; spin < limit; ++spin) {
             v = ld_dev(p);
             if (v != 0) break;
-            __builtin_amdgcn_s_sleep(20);
+            __builtin_amdgcn_s_sleep(4);
         }
         *bc = v;
     }
@@ -102,12 +120,12 @@ __device__ __forceinline__ uint32_t wait_word(const uint32_t *p, uint32_t limit,
     return *bc;
 }
 
-// One reader of a hand-over word has passed; the last of `readers` clears the word and the
-// count for the next launch.  Call from one thread.
-__device__ __forceinline__ void reader_done(uint32_t *seen, uint32_t readers, uint32_t *word)
+// `count` readers of a hand-over word have passed; whoever completes the `readers` clears the
+// word and the count for the next launch.  Call from one thread.
+__device__ __forceinline__ void reader_done(uint32_t *seen, uint32_t readers, uint32_t count, uint32_t *word)
 {
-    const uint32_t old = __hip_atomic_fetch_add(seen, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (old + 1u == readers) {
+    const uint32_t old = __hip_atomic_fetch_add(seen, count, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old + count == readers) {
         st_dev(word, 0u);
         st_dev(seen, 0u);
     }

@@ -355,6 +355,14 @@ int main(int argc, char **argv)
         worker_server("flat 2^20", {1u << 20}, 0.01, 0.01, 1.0f, 0.9f, false, {1, 1, 1}, 0, o, 20);
         return 0;
     }
+    if (argc > 1 && std::string(argv[1]) == "rounds") {
+        // join groups of more tiles than a workgroup has lanes (build with the default DGS_GROUP_TILES):
+        // several rounds per group, the second tensor starting inside a tile of the first
+        Opts o;
+        worker_server("groups of several rounds", {1500017, 64, 2300000}, 0.001, 0.002, 1.0f, 0.9f, false, {1, 1, 1, 30, 30},
+                      0, o, 29);
+        return 0;
+    }
     const std::vector<uint64_t> ragged = {1, 7, 64, 1000, 8192, 8193, 9408, 3, 100003, 20000, 70001, 17, 65537, 12345};
     const std::vector<uint64_t> two = {150000, 64, 66000};
     Opts def, exact, always, never, norepair;

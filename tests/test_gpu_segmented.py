@@ -154,10 +154,11 @@ def test_automatic_mode_mixes_both_selections(oracle):
 
 @pytest.mark.parametrize("seg_mode", [None, dgs.SEG_NEVER], ids=["auto", "never"])
 def test_single_workgroup_join_over_several_batches(oracle, seg_mode):
-    """Tensors of thousands of tiles whose candidate lists one workgroup can select from: their
-    parts are joined by many workgroups and gathered by the last one (with the chain switched
-    off as well); the second tensor starts inside a tile of the first.  A crowded stretch
-    (every element a candidate in a few tiles) spills into the per-tile slots on the way."""
+    """Tensors of thousands of tiles whose candidate lists one workgroup can select from: a
+    tensor of up to 4096 tiles is joined by one workgroup in rounds of 1024 tiles, the
+    7M-element one by two whose lists the last to arrive gathers (with the chain switched off
+    as well); the second tensor starts inside a tile of the first.  A crowded stretch (every
+    element a candidate in a few tiles) spills into the per-tile slots on the way."""
     sizes = [3_400_017, 3_900_000, 5000] if seg_mode is None else [3_400_017, 7_000_001, 5000]
     off = synth.offsets_from_sizes(sizes)
     scales = synth.tensor_scales(len(sizes), 55)
@@ -167,6 +168,67 @@ def test_single_workgroup_join_over_several_batches(oracle, seg_mode):
         g[3_400_000:3_400_600] *= np.float32(50.0)      # crowded tiles across the tensor border
     st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), 1e-3, seg_mode=seg_mode)
     assert st.segmented_tensors == 0 and st.internal_errors == 0
+
+
+def test_recollection_after_a_join_that_outgrew_the_lds_list(oracle):
+    """Second step of a momentum run: the hinted threshold lets tens of thousands of candidates
+    through, the join of the 3.4M-element tensor (one workgroup, 13 parts) runs past the LDS
+    list into the first parts' global lists, the prediction is rejected, and the parts are
+    collected again by other workgroups into those same lists.  What the first workgroup wrote
+    there must not outlive it in a cache (every list entry is written through to memory).
+    Another layout uses the device memory first, so that stale contents differ from fresh ones."""
+    pre = synth.offsets_from_sizes([2_000_003, 1_500_000, 777])
+    rng = np.random.default_rng(57)
+    g0 = synth.gaussian_grads(pre, synth.tensor_scales(3, 58), rng)
+    run_worker_parity(oracle, pre, [g0, g0 * np.float32(30.0)], np.float32(1.0), np.float32(0.9), 0.01)
+    sizes = [3_400_017, 3_900_000, 5000]
+    off = synth.offsets_from_sizes(sizes)
+    scales = synth.tensor_scales(len(sizes), 55)
+    rng = np.random.default_rng(56)
+    grads = [synth.gaussian_grads(off, scales, rng) for _ in range(3)]
+    st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), 1e-3)
+    assert st.repaired_tensors >= 2 and st.fallback_tensors == 0 and st.internal_errors == 0
+
+
+def test_collapsed_scale_is_recollected_by_many_workgroups(oracle):
+    """A 2,359,296-element tensor (9 parts) whose gradient scale collapses by 1e6 and comes back:
+    fewer candidates than k pass the hinted threshold, the launch's other workgroups build a
+    fresh histogram and collect the parts again, the last of them selects.  No dense
+    re-selection by a single workgroup, and the result is the oracle's."""
+    off = synth.offsets_from_sizes([2_359_296, 64])
+    n = int(off[-1])
+    rng = np.random.default_rng(59)
+    g = [synth.gaussian(n, rng) for _ in range(6)]
+    grads = [g[0], g[1], g[2] * np.float32(1e-6), g[3] * np.float32(1e-6), g[4], g[5]]
+    st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.001, residual=True)
+    assert st.repaired_tensors >= 1 and st.fallback_tensors == 0 and st.segmented_tensors == 0
+
+
+def test_a_wait_that_gives_up_is_counted_and_every_kernel_ends(oracle):
+    """The workgroups that stand by to collect a tensor again poll for the verdict of its join
+    a bounded number of times.  With the bound set to one poll they give up before the verdict
+    is out: the launch still ends, the give-ups are counted as internal errors, and -- in the
+    steady regime, where no prediction fails -- the message is still the oracle's."""
+    off = synth.offsets_from_sizes([2_359_296, 300_000, 64])
+    n = int(off[-1])
+    rng = np.random.default_rng(60)
+    lr, m, rho = np.float32(1.0), np.float32(0.5), 0.001
+    ctx = dgs.Context(off, W=0)
+    w = Worker(ctx, density_max=rho)
+    s_ref = np.zeros(n, np.float32)
+    repaired = []
+    for t in range(9):
+        if t == 8:
+            assert repaired[-1] == repaired[-4], "the run has not settled: predictions still fail"
+            assert ctx.stats().internal_errors == 0
+            ctx.set_option(dgs.OPT_SPIN_LIMIT, 1)
+        g = synth.gaussian(n, rng)
+        wi, wv = oracle.worker_step(g, s_ref, off, lr, m, rho)
+        gi, gv = w.step(g, lr, m, rho)
+        assert_pairs_match(gi, gv, wi, wv, f"step {t}")
+        repaired.append(ctx.stats().repaired_tensors)
+    assert ctx.stats().internal_errors >= 1
+    ctx.close()
 
 
 @pytest.mark.parametrize("rho", [0.05, 0.5, 1.0])

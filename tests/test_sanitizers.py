@@ -37,14 +37,15 @@ def test_oracle_under_asan_ubsan(tmp_path):
 EMU_SOURCES = ["dgs_stream.hip", "dgs_select.hip", "dgs_chain.hip", "dgs_server.hip", "dgs_api.hip"]
 
 
-def build_emulated_kernels(outdir, seg_tiles=16, opt="-O2"):
+def build_emulated_kernels(outdir, seg_tiles=16, group_tiles=64, opt="-O2"):
     """The library's own .hip sources compiled as host C++ against tests/emu (a fiber-based
     emulation of workgroups, wavefront builtins and the few HIP calls used), with ASan + UBSan,
     linked with the oracle and the scenario driver."""
     clang = os.environ.get("DGS_HOST_CLANG", "/opt/rocm/llvm/bin/clang++")
     emu = os.path.join(HERE, "emu")
     csrc = os.path.join(ROOT, "paper_1910_10929_amd", "csrc")
-    flags = ["-std=c++17", opt, "-g", f"-I{emu}", f"-DDGS_SEG_TILES={seg_tiles}", "-ffp-contract=off",
+    flags = ["-std=c++17", opt, "-g", f"-I{emu}", f"-DDGS_SEG_TILES={seg_tiles}",
+             f"-DDGS_GROUP_TILES={group_tiles}", "-ffp-contract=off",
              "-fsanitize=address,undefined", "-fno-sanitize-recover=all", "-Wno-unknown-attributes",
              "-Wno-unused-function", "-Wno-array-compare"]
     objs, procs = [], []
