@@ -47,7 +47,9 @@ LR, MOMENTUM = 1.0, 0.9
 # by what the same counter reads for a copy kernel of known size.  Offline profile values, not
 # measured in this run; every entry names the summary it comes from.
 PROFILED_TRAFFIC = {
-    "c2": {"bytes": 308.61e6, "profile": "profiles/bench_c2_hbm_traffic.txt"},
+    "c5": {"bytes": 12068.64e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
+    "c2": {"bytes": 308.62e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
+    "c3": {"bytes": 207.74e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
 }
 
 

@@ -25,7 +25,7 @@ size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
     size_t tile_desc, tdesc, plans, tau, hint2, tprev, ghist, tile_cnt, heads, slots, ord, stats, flag;
-    size_t segtab, grptab, grpcnt, segcnt, segG1, segOut, segstate, pfxlist, total;
+    size_t segtab, grptab, grpcnt, segstart, segcnt, segG1, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -95,6 +95,7 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
     L.grptab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));      // groups <= parts
     L.grpcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
+    L.segstart = o;  o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segG1 = o;     o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
     L.segOut = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint2));
@@ -160,7 +161,7 @@ struct dgs_ctx {
     uint32_t *flag = nullptr;
     SegDesc *segtab = nullptr;
     SegDesc *grptab = nullptr;
-    uint32_t *grpcnt = nullptr;
+    uint32_t *grpcnt = nullptr, *segstart = nullptr;
     uint32_t ngroups = 0, gparts = 1;  // join groups; parts per group
     uint32_t bgroup = 8;               // parts per re-collecting workgroup (about 2048 tiles)
     uint32_t *segcnt = nullptr, *segG1 = nullptr;
@@ -431,6 +432,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     se.segtab = c->segtab;
     se.grptab = c->grptab;
     se.grpcnt = c->grpcnt;
+    se.segstart = c->segstart;
     se.ngroups = c->ngroups;
     se.gparts = c->gparts;
     se.bgroup = c->bgroup;
@@ -498,6 +500,7 @@ void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
     c->segtab = (SegDesc *)(c->ws + L.segtab);
     c->grptab = (SegDesc *)(c->ws + L.grptab);
     c->grpcnt = (uint32_t *)(c->ws + L.grpcnt);
+    c->segstart = (uint32_t *)(c->ws + L.segstart);
     c->segcnt = (uint32_t *)(c->ws + L.segcnt);
     c->segG1 = (uint32_t *)(c->ws + L.segG1);
     c->segOut = (uint2 *)(c->ws + L.segOut);
@@ -536,7 +539,9 @@ void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, Seg
     }
     for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)c->offsets[j];
     c->nseg_total = nsegs;
-    c->bgroup = scale >= 8 ? 1u : 8u / scale;
+    // re-collecting workgroups: about 112 per role, so that both roles fit the chip beside each
+    // other, each looking after at most 8 consecutive parts
+    c->bgroup = std::min<uint32_t>(8u, std::max<uint32_t>(1u, (nsegs + 111u) / 112u));
     // Join groups: runs of `gparts` consecutive parts (about GROUP_TILES tiles).  The launch takes
     // the groups of the tensors with several groups first: those tensors end with a gather and
     // a selection by the last group to arrive, the critical path of the launch.

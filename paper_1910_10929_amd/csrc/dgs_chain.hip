@@ -34,7 +34,7 @@ __device__ __forceinline__ PartSource part_source(const SelectArgs &A, const Ten
                                                   uint32_t part, bool dense)
 {
     PartSource S;
-    S.list = A.ord + (size_t)(sd.tile0 + sd.j) * CAPT;
+    S.list = A.ord + (dense ? 0u : A.segstart[part]);
     S.state = A.state;
     S.model = A.model;
     S.dense = dense;

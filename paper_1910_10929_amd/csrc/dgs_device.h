@@ -34,7 +34,7 @@ constexpr uint32_t HSHIFT = 31 - HBITS;
 // Selection workgroup.
 constexpr uint32_t SEL_THREADS = 1024;
 constexpr uint32_t SEL_WAVES = SEL_THREADS / 64;
-constexpr uint32_t SEL_LDS_LIST = 12288;           // candidates kept in LDS (96 KB); longer lists continue in global scratch
+constexpr uint32_t SEL_LDS_LIST = 16384;           // candidates kept in LDS (128 KB); longer lists continue in global scratch
 constexpr uint32_t SEL_LIST_MAX = 24576;           // longest candidate list one workgroup is planned for
 constexpr uint32_t SEL_LIST_HARD = 65536;          // longest it accepts when a tail has grown beyond the plan
 // Above this density candidates stop paying off; such requests select densely.
@@ -62,7 +62,7 @@ constexpr uint32_t SEG_LOWBITS = 12;               // key bits resolved by the s
 constexpr uint32_t SEG_WBINS = 2048;               // window of key >> SEG_LOWBITS above the threshold
 constexpr uint32_t SEG_LBINS = 1u << SEG_LOWBITS;
 constexpr uint32_t PFX_CAP = 8192;                 // candidates sharing the k-th key's prefix, per tensor
-constexpr uint32_t SEG_MAX_PER_TENSOR = 1024;      // parts per tensor whose list positions fit the selection's LDS
+constexpr uint32_t SEG_MAX_PER_TENSOR = 512;       // parts per tensor whose list positions fit the selection's LDS
 // Status of a tensor inside one selection call.
 //   SEG_IDLE      nothing decided yet
 //   SEG_DONE      selected and emitted
@@ -166,6 +166,7 @@ struct SelectArgs {
     SegState *segstate;
     uint32_t *segcnt;             // per part: candidates (bit 31: a tile of the part overflowed)
     uint32_t *grpcnt;             // per join group: the same, for the lists joined by groups
+    uint32_t *segstart;           // per part of a tensor that takes the chain: where its list starts in ord
     uint32_t *segG1;              // per part: candidates with a larger key prefix than the k-th
     uint2 *segOut;                // per part: (output position within the tensor, ties to take)
     uint4 *pfxlist;               // per tensor PFX_CAP x (index, value bits, part, 0)

@@ -65,6 +65,15 @@ struct SrcList {           // ordered candidates (index, value bits)
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return list[p].x; }
 };
 
+struct SrcSplit {          // a list whose first SEL_LDS_LIST entries are in LDS, the rest in global scratch
+    static constexpr bool AGG = true;
+    const uint2 *llist;
+    const uint2 *glist;
+    __device__ __forceinline__ uint2 get(uint32_t p) const { return (p < SEL_LDS_LIST) ? llist[p] : glist[p]; }
+    __device__ __forceinline__ uint32_t bits(uint32_t p) const { return get(p).y; }
+    __device__ __forceinline__ uint32_t index(uint32_t p) const { return get(p).x; }
+};
+
 struct SelShared {
     uint32_t h[2048];
     uint32_t wsum[SEL_WAVES];
@@ -477,16 +486,15 @@ __device__ __forceinline__ uint32_t wave_min_to_last(uint32_t v)
     return (uint32_t)x;
 }
 
-// Ordered-list entry: LDS while it fits, global scratch beyond.  The global lists are only ever
-// written through to memory (st_dev): a cached store by this workgroup would sit in its L2
-// and shadow what a workgroup elsewhere on the chip writes to the same place later in the
-// launch, when the tensor is collected again.
+// Ordered-list entry: LDS while it fits, global scratch beyond (an ordinary cached store: the
+// list is read back by this workgroup; see release_dev() for the one case where another
+// workgroup writes to the same place later in the launch).
 __device__ __forceinline__ void put_entry(uint2 *llist, uint2 *glist, uint32_t pos, uint2 e)
 {
     if (pos < SEL_LDS_LIST) {
         llist[pos] = e;
     } else {
-        st_dev(&glist[pos], e);
+        glist[pos] = e;
         // keeps the two stores apart: merged into one store through a generic pointer they
         // would take the slow flat path into LDS
         asm volatile("" ::: "memory");

@@ -103,9 +103,9 @@ struct PartShared {
     uint32_t wtot[SEL_WAVES];
     uint32_t vbuf[B_GROUP_MAX];               // verdicts of the tensors of a re-collecting workgroup's parts
     uint32_t tile_pos[SEL_THREADS];           // JOIN: list position and count of every tile of the round
-    uint32_t tile_n[SEL_THREADS];
-    uint32_t crowd_tile[SEL_THREADS];         // JOIN: tiles of the round that take the per-entry loop,
-    uint32_t crowd_pos[SEL_THREADS];          //       their list positions
+    uint32_t tile_n[SEL_THREADS];             //       (bit 31: the tile's entries are fetched one by one)
+    uint32_t start0;                          //       entries of the previous tensor in a shared first tile
+    uint32_t crowd_slot[SEL_THREADS];         //       the round's crowded tiles (which lane has them)
     uint32_t bc;
 };
 
@@ -146,9 +146,14 @@ __device__ __forceinline__ void tile_counts(uint32_t w, uint32_t t, uint32_t tlo
 // four lines per lane -- and put in place with the positions read back from LDS; crowded tiles
 // and a first tile shared with the previous tensor go to a worklist that the wavefronts then
 // copy entry by entry.
-template <class Put>
+struct NoTileHook {
+    __device__ __forceinline__ void operator()(uint32_t, uint32_t) const {}
+};
+
+// (`at_tile(tile index within the run, list position)` is called once for every tile.)
+template <class Put, class AtTile = NoTileHook>
 __device__ __forceinline__ uint32_t join_part(const SelectArgs &A, const TensorDesc &td, const SegDesc &sd,
-                                              PartShared &P, bool &ovf_out, Put put)
+                                              PartShared &P, bool &ovf_out, Put put, AtTile at_tile = AtTile())
 {
     const uint32_t tid = threadIdx.x, wave = tid >> 6, lane = tid & 63u;
     const uint32_t tlo = td.off / TILE;
@@ -168,38 +173,72 @@ __device__ __forceinline__ uint32_t join_part(const SelectArgs &A, const TensorD
         const uint32_t w = (r0 + tid < sd.ntiles) ? A.tile_cnt[t] : 0u;
         uint32_t n_t, start;
         tile_counts(w, t, tlo, head_shared, n_t, start, ovf);
-        // one scan for both: list positions (low 19 bits: at most 2^18 candidates a round) and
-        // worklist slots of the crowded tiles (the bits above)
+        // one scan for both: list positions (low 19 bits: at most 2^18 candidates a round) and the
+        // number of crowded tiles (the bits above)
         const bool crowded = n_t != 0 && (start != 0 || n_t > HEAD);
         uint32_t total;
         const uint32_t excl = block_excl_scan<SEL_WAVES>(n_t | (crowded ? 1u << 19 : 0u), P.S.wsum, total);
         const uint32_t pos = base + (excl & 0x7FFFFu);
-        const uint32_t nc = total >> 19;
-        base += total & 0x7FFFFu;
+        const uint32_t nc = total >> 19, round_n = total & 0x7FFFFu;
         P.tile_pos[tid] = pos;
-        P.tile_n[tid] = crowded ? 0u : n_t;
-        if (crowded) {
-            P.crowd_tile[excl >> 19] = t;
-            P.crowd_pos[excl >> 19] = pos;
-        }
+        P.tile_n[tid] = n_t | (crowded ? 0x80000000u : 0u);
+        if (crowded) P.crowd_slot[excl >> 19] = tid;
+        if (head_shared && t == tlo) P.start0 = start;      // (the tensor's first tile, shared with the one before)
+        if (r0 + tid < sd.ntiles) at_tile(r0 + tid, pos);
         __syncthreads();
 #pragma unroll
         for (uint32_t v = 0; v < 4; ++v) {
             const uint32_t slot = wave * 64u + v * 16u + (lane >> 2);
-            const uint32_t n = P.tile_n[slot], p = P.tile_pos[slot], e0 = 2u * (lane & 3u);
+            const uint32_t nv = P.tile_n[slot], p = P.tile_pos[slot], e0 = 2u * (lane & 3u);
+            const uint32_t n = (nv >> 31) ? 0u : nv;
             if (e0 < n) put(p + e0, make_uint2(pf[v].x, pf[v].y));
             if (e0 + 1 < n) put(p + e0 + 1, make_uint2(pf[v].z, pf[v].w));
         }
-        for (uint32_t q = wave; q < nc; q += SEL_WAVES) {
-            const uint32_t tc = P.crowd_tile[q], pc = P.crowd_pos[q];
-            uint32_t n_c, start_c;
-            int o = 0;
-            tile_counts(A.tile_cnt[tc], tc, tlo, head_shared, n_c, start_c, o);
-            const uint2 *hd = A.heads + (size_t)tc * HEAD;
-            const uint2 *sl = A.slots + (size_t)tc * CAPT;
-            for (uint32_t i = lane; i < n_c; i += 64) put(pc + i, tile_entry(hd, sl, start_c + i));
+        if (nc != 0 && nc <= 2 * SEL_WAVES) {
+            // a few crowded tiles: a wavefront copies one at a time
+            for (uint32_t q = wave; q < nc; q += SEL_WAVES) {
+                const uint32_t slot = P.crowd_slot[q], tc = sd.tile0 + r0 + slot;
+                const uint32_t n_c = P.tile_n[slot] & 0x7FFFFFFFu, pc = P.tile_pos[slot];
+                const uint32_t st0 = (head_shared && tc == tlo) ? P.start0 : 0u;
+                const uint2 *hd = A.heads + (size_t)tc * HEAD;
+                const uint2 *sl = A.slots + (size_t)tc * CAPT;
+                for (uint32_t i = lane; i < n_c; i += 64) put(pc + i, tile_entry(hd, sl, st0 + i));
+            }
+        } else if (nc != 0) {
+            // many crowded tiles: every list position of the round finds its tile (the last one
+            // that starts at or before it) and, if that tile is crowded, fetches its own entry
+            constexpr uint32_t CU = 4;      // entries per thread in flight
+            for (uint32_t q0 = 0; q0 < round_n; q0 += CU * SEL_THREADS) {
+                uint2 e[CU];
+                bool take[CU];
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u) {
+                    const uint32_t q = base + q0 + u * SEL_THREADS + tid;
+                    take[u] = false;
+                    e[u] = make_uint2(0, 0);
+                    if (q0 + u * SEL_THREADS + tid < round_n) {
+                        uint32_t lo = 0, hi = SEL_THREADS;
+                        while (hi - lo > 1) {
+                            const uint32_t mid = (lo + hi) >> 1;
+                            if (P.tile_pos[mid] <= q) lo = mid;
+                            else hi = mid;
+                        }
+                        if (P.tile_n[lo] >> 31) {
+                            const uint32_t tc = sd.tile0 + r0 + lo;
+                            const uint32_t st0 = (head_shared && tc == tlo) ? P.start0 : 0u;
+                            take[u] = true;
+                            e[u] = tile_entry(A.heads + (size_t)tc * HEAD, A.slots + (size_t)tc * CAPT,
+                                              st0 + (q - P.tile_pos[lo]));
+                        }
+                    }
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < CU; ++u)
+                    if (take[u]) put(base + q0 + u * SEL_THREADS + tid, e[u]);
+            }
         }
-        // (the next round rewrites positions and worklist behind the two barriers of its scan)
+        base += round_n;
+        // (the next round rewrites the positions behind the two barriers of its scan)
     }
     ovf_out = __syncthreads_or(ovf) != 0;
     return base;
@@ -225,6 +264,39 @@ __device__ __forceinline__ DenseRun dense_run(const TensorDesc &td, const SegDes
     return r;
 }
 
+// The four consecutive elements e0 .. e0 + 3 (e0 a multiple of 4) of the ranked row as bit
+// patterns, and which of them belong to the tensor [lo, hi): one 16-byte load per buffer where
+// the quad lies inside the tensor and the buffers are 16-byte aligned (`vec`), element by
+// element at a tensor border or off alignment.
+template <int OP>
+__device__ __forceinline__ uint32_t quad_bits(const SelectArgs &A, uint32_t e0, uint32_t lo, uint32_t hi, bool vec,
+                                              uint32_t (&bits)[4])
+{
+    if (vec && e0 >= lo && e0 + 3u < hi) {
+        f32x4 v = *(const f32x4 *)(A.state + e0);
+        if (OP == SEL_PULL_V) v = *(const f32x4 *)(A.model + e0) - v;      // one fp32 subtraction per element
+        bits[0] = __float_as_uint(v.x);
+        bits[1] = __float_as_uint(v.y);
+        bits[2] = __float_as_uint(v.z);
+        bits[3] = __float_as_uint(v.w);
+        return 0xFu;
+    }
+    uint32_t in = 0;
+#pragma unroll
+    for (int x = 0; x < 4; ++x) {
+        const uint32_t e = e0 + x;
+        const bool ok = e >= lo && e < hi;
+        bits[x] = ok ? __float_as_uint(row_value<OP>(A.state, A.model, e)) : 0u;
+        in |= ok ? (1u << x) : 0u;
+    }
+    return in;
+}
+
+__device__ __forceinline__ bool rows_aligned(const SelectArgs &A)
+{
+    return (((uintptr_t)A.state | (uintptr_t)A.model) & 15u) == 0;   // (a null model counts as aligned)
+}
+
 // RE-HISTOGRAM of one part: key bits [30:19] of the tensor's nonzero elements in the part,
 // into lh (HBINS counters in LDS, zeroed here).  Ends with a barrier.
 template <int OP>
@@ -234,21 +306,18 @@ __device__ __forceinline__ void dense_hist(const SelectArgs &A, const TensorDesc
     __syncthreads();
     const DenseRun r = dense_run(td, sd);
     const uint32_t lane = lane_id();
+    const bool vec = rows_aligned(A);
     for (uint32_t t = r.t0; t < r.t1; ++t) {
+        uint32_t bits[4][4];     // the whole tile is fetched before the first counter is touched
 #pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            const uint32_t e0 = t * TILE + row * 256 + lane * 4;
-            uint32_t key[4];
+        for (int row = 0; row < 4; ++row) quad_bits<OP>(A, t * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, bits[row]);
+#pragma unroll
+        for (int row = 0; row < 4; ++row)
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const uint32_t e = e0 + x;
-                key[x] = (e >= r.lo && e < r.hi) ? (__float_as_uint(row_value<OP>(A.state, A.model, e)) & 0x7FFFFFFFu)
-                                                : 0u;
+                const uint32_t key = bits[row][x] & 0x7FFFFFFFu;      // elements outside the tensor read as 0
+                if (key != 0) atomicAdd(&lh[key >> HSHIFT], 1u);
             }
-#pragma unroll
-            for (int x = 0; x < 4; ++x)
-                if (key[x] != 0) atomicAdd(&lh[key[x] >> HSHIFT], 1u);
-        }
     }
     __syncthreads();
 }
@@ -262,19 +331,17 @@ __device__ __forceinline__ uint32_t dense_compact(const SelectArgs &A, const Ten
 {
     const DenseRun r = dense_run(td, sd);
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
+    const bool vec = rows_aligned(A);
     uint32_t mine = 0;
     for (uint32_t t = r.t0; t < r.t1; ++t) {
+        uint32_t bits[4][4], in[4];
 #pragma unroll
-        for (int row = 0; row < 4; ++row) {
-            const uint32_t e0 = t * TILE + row * 256 + lane * 4;
+        for (int row = 0; row < 4; ++row) in[row] = quad_bits<OP>(A, t * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, bits[row]);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const uint32_t e = e0 + x;
-                if (e >= r.lo && e < r.hi &&
-                    (__float_as_uint(row_value<OP>(A.state, A.model, e)) & 0x7FFFFFFFu) >= tau)
-                    ++mine;
-            }
-        }
+        for (int row = 0; row < 4; ++row)
+#pragma unroll
+            for (int x = 0; x < 4; ++x)
+                if (((in[row] >> x) & 1u) && (bits[row][x] & 0x7FFFFFFFu) >= tau) ++mine;
     }
     const uint32_t wsum_ = wave_sum(mine);
     __syncthreads();
@@ -290,18 +357,19 @@ __device__ __forceinline__ uint32_t dense_compact(const SelectArgs &A, const Ten
     if (total > cap) return total;
     uint32_t run = before;
     for (uint32_t t = r.t0; t < r.t1; ++t) {
+        uint32_t tbits[4][4], tin[4];
+#pragma unroll
+        for (int row = 0; row < 4; ++row) tin[row] = quad_bits<OP>(A, t * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, tbits[row]);
 #pragma unroll
         for (int row = 0; row < 4; ++row) {
             const uint32_t e0 = t * TILE + row * 256 + lane * 4;
-            uint32_t bits[4];
+            const uint32_t (&bits)[4] = tbits[row];
             bool f[4];
             uint64_t mk[4];
+            const uint32_t in = tin[row];
 #pragma unroll
             for (int x = 0; x < 4; ++x) {
-                const uint32_t e = e0 + x;
-                const bool in = e >= r.lo && e < r.hi;
-                bits[x] = in ? __float_as_uint(row_value<OP>(A.state, A.model, e)) : 0u;
-                f[x] = in && (bits[x] & 0x7FFFFFFFu) >= tau;
+                f[x] = ((in >> x) & 1u) && (bits[x] & 0x7FFFFFFFu) >= tau;
                 mk[x] = ballot64(f[x]);
             }
             if ((mk[0] | mk[1] | mk[2] | mk[3]) != 0) {
@@ -477,11 +545,6 @@ __device__ __forceinline__ void list_select(const SelectArgs &A, const TensorDes
                                             uint2 *llist, uint2 *glist)
 {
     const uint32_t tid = threadIdx.x;
-    if (c > SEL_LDS_LIST) {
-        // the list outgrew LDS: complete the global copy
-        for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) st_dev(&glist[p], llist[p]);
-        __syncthreads();
-    }
     uint32_t R = 0, Eq = 0;
     if (A.write_hint) R = hint_rank<OP>(td, pe, !exact_mode, c, hint2_cur, A.m, &Eq);
     uint32_t tau_next = 0, expect = 0, q_e = 0, t_k = 0;
@@ -496,7 +559,7 @@ __device__ __forceinline__ void list_select(const SelectArgs &A, const TensorDes
         select_emit<OP, 4>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, P.S, A, pe.outoff,
                            &tau_next, &expect, &q_e, &t_k);
     } else {
-        SrcList src{glist};
+        SrcSplit src{llist, glist};     // the list outgrew LDS: its tail is read from global scratch
         select_emit<OP, 8>(src, c, pe.k, R, Eq, win_base, win_min, win_ready, kmin, P.S, A, pe.outoff,
                            &tau_next, &expect, &q_e, &t_k);
     }
@@ -586,7 +649,9 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
             const uint32_t ex = block_excl_scan<SEL_WAVES>(cnt, P.S.wsum, tot);
             if (s < nunits && have_pbase) {
                 P.pbase[s] = c + ex;
-                P.pofs[s] = (units[s].tile0 + j) * CAPT;   // below 2^32: n < 2^32
+                // (a part of a tensor that takes the chain lies where its group's join put it)
+                P.pofs[s] = (by_parts && pe.seg) ? ld_dev(&A.segstart[td.seg_first + s])
+                                                 : (units[s].tile0 + j) * CAPT;   // below 2^32: n < 2^32
             }
             c += tot;
         }
@@ -607,10 +672,7 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
         } else if (pe.seg) {
             zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
         } else if (c > SEL_LDS_LIST) {
-            for (uint32_t p = tid; p < SEL_LDS_LIST; p += SEL_THREADS) st_dev(&glist[p], llist[p]);
-            wait_mem();
-            __syncthreads();
-            zero_fill_emit<OP>(SrcList{glist}, c, td, pe, A, P.S.wsum);
+            zero_fill_emit<OP>(SrcSplit{llist, glist}, c, td, pe, A, P.S.wsum);
         } else {
             zero_fill_emit<OP>(SrcList{llist}, c, td, pe, A, P.S.wsum);
         }
@@ -677,7 +739,13 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
     if (verdict && !early) {
         wait_mem();
         __syncthreads();
-        if (tid == 0) st_dev(verdict, 0x100u | status);
+        if (tid < 64) {
+            // A rejected join may have spilled list entries with cached stores into the very
+            // lists that other workgroups now fill again: written back before they start, so
+            // that no older copy in this L2 shadows theirs.
+            if (status == SEG_PENDING) release_dev();
+            if (tid == 0) st_dev(verdict, 0x100u | status);
+        }
     }
     return status;
 }
@@ -752,7 +820,10 @@ __device__ __forceinline__ void recollect_part(const SelectArgs &A, uint32_t rol
     } else {
         c2 = dense_compact<OP>(A, td, sd, tau_new, part_cap, P, [&](uint32_t pos, uint2 e) { st_dev(&plist[pos], e); });
     }
-    if (tid == 0) st_dev(&A.segcnt[part], min(c2, 0x7FFFFFFFu) | (c2 > part_cap ? 0x80000000u : 0u));
+    if (tid == 0) {
+        st_dev(&A.segcnt[part], min(c2, 0x7FFFFFFFu) | (c2 > part_cap ? 0x80000000u : 0u));
+        if (pe.seg) st_dev(&A.segstart[part], (sd.tile0 + j) * CAPT);      // the part's own place again
+    }
     if (!arrive_last(&st->arrive[2], td.nseg, &P.bc)) return;
     tensor_select<OP>(A, td, pe, j, 1, true, true, 0u, false, 0xFFFFFFFFu, tau_new, tprev_new, 0xFFFFFFFFu, false,
                       nullptr, P, llist);
@@ -830,35 +901,52 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
         uint32_t *verdict = (has_parts && A.repair) ? &st->verdict : nullptr;
         uint32_t status;
         if (pe.seg) {
-            // a tensor that takes the chain: lists, counts and window histogram part by part
+            // a tensor that takes the chain: the group's candidates in one list, with every part's
+            // start and count noted for the chain kernels, and the group's window histogram
             const uint32_t p0 = td.seg_first + sd.sidx * A.gparts;
             const uint32_t p1 = min(p0 + A.gparts, td.seg_first + td.nseg);
             uint32_t *gh = A.ghist + (size_t)j * HBINS;
-            for (uint32_t p = p0; p < p1; ++p) {
-                const SegDesc ps = A.segtab[p];
-                uint2 *pl = A.ord + (size_t)(ps.tile0 + j) * CAPT;
+            if (chain_dense) {
+                for (uint32_t p = p0; p < p1; ++p) {       // no lists: the parts' elements are counted
+                    const SegDesc ps = A.segtab[p];
+                    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+                    __syncthreads();
+                    const uint32_t cp = dense_window_count<OP>(A, td, ps, tau_cur, win_seg, P.S.h, P.S.wsum);
+                    __syncthreads();
+                    for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
+                        const uint32_t v = P.S.h[b];
+                        if (v) atomicAdd(&gh[b], v);
+                    }
+                    if (tid == 0) st_dev(&A.segcnt[p], cp);
+                    cs += cp;
+                    __syncthreads();
+                }
+            } else {
                 for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
                 __syncthreads();
-                bool o = false;
-                uint32_t cp;
-                if (chain_dense) {
-                    cp = dense_window_count<OP>(A, td, ps, tau_cur, win_seg, P.S.h, P.S.wsum);
-                } else {
-                    cp = join_part(A, td, ps, P, o, [&](uint32_t pos, uint2 e) {
-                        st_dev(&pl[pos], e);          // read by the chain kernels, and by a zero fill
+                const uint32_t ptiles = A.segtab[p0].ntiles;         // tiles per part (the tensor's last part may have fewer)
+                const uint32_t gbase = (sd.tile0 + j) * CAPT;        // below 2^32: n < 2^32
+                cs = join_part(
+                    A, td, sd, P, ovf,
+                    [&](uint32_t pos, uint2 e) {
+                        st_dev(&plist[pos], e);          // read by the chain kernels, and by a zero fill
                         const uint32_t hi12 = (e.y & 0x7FFFFFFFu) >> SEG_LOWBITS;
                         const uint32_t w = (hi12 > win_seg) ? (hi12 - win_seg) : 0u;
                         atomicAdd(&P.S.h[min(w, SEG_WBINS - 1u)], 1u);
+                    },
+                    [&](uint32_t tl, uint32_t pos) {
+                        if (tl % ptiles == 0) P.pbase[tl / ptiles] = pos;
                     });
-                }
-                __syncthreads();
                 for (uint32_t b = tid; b < SEG_WBINS; b += SEL_THREADS) {
                     const uint32_t v = P.S.h[b];
                     if (v) atomicAdd(&gh[b], v);
                 }
-                if (tid == 0) st_dev(&A.segcnt[p], cp | (o ? 0x80000000u : 0u));
-                cs += cp;
-                ovf = ovf || o;
+                const uint32_t np = p1 - p0;
+                if (tid < np) {
+                    const uint32_t start = P.pbase[tid], end = (tid + 1 < np) ? P.pbase[tid + 1] : cs;
+                    st_dev(&A.segstart[p0 + tid], gbase + start);
+                    st_dev(&A.segcnt[p0 + tid], (end - start) | (ovf ? 0x80000000u : 0u));
+                }
                 __syncthreads();
             }
             if (multi) {
@@ -926,7 +1014,7 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
                     const uint32_t v = P.S.h[b];
                     if (v) atomicAdd(&gh[b], v);
                 }
-                if (tid == 0) A.segcnt[part] = c2;
+                if (tid == 0) st_dev(&A.segcnt[part], c2);
             }
         } else {
             uint2 *glist = plist;

@@ -82,6 +82,14 @@ __device__ __forceinline__ void wait_mem() {}
 __device__ __forceinline__ void wait_mem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 #endif
 
+// Everything this compute-unit group's L2 holds dirty goes to memory (device-scope release).
+// Expensive -- the whole L2 is walked -- and therefore only used where a prediction has failed.
+#ifdef DGS_HOST_EMULATION
+__device__ __forceinline__ void release_dev() {}
+#else
+__device__ __forceinline__ void release_dev() { __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent"); }
+#endif
+
 // The workgroup has finished its share of a per-tensor phase: after every wavefront's stores
 // are acknowledged, one device-scope atomic counts it in.  Returns true in every thread of the
 // workgroup that arrives last of `expected` (it then also clears the counter for the next

@@ -74,6 +74,54 @@ def test_step_replayed_from_a_graph(oracle):
     ctx.close()
 
 
+def test_an_unplanned_density_is_refused_during_capture(oracle):
+    """Planning a density copies its tables to the device, which a stream capture must not contain:
+    a call with a density that has no cached plan returns DGS_ENOTSUP while the stream is being
+    captured, and nothing of it is recorded.  The plan that WAS used during a capture survives any
+    number of other densities afterwards: the replay keeps giving the oracle's result."""
+    import torch
+    sizes = [200_000, 64, 9408]
+    off = synth.offsets_from_sizes(sizes)
+    n = int(off[-1])
+    rho = 0.004
+    lr, m = np.float32(1.0), np.float32(0.0)
+    dev = "cuda:0"
+    s = torch.cuda.Stream(device=dev)
+    ctx = dgs.Context(off, W=0, device=dev, stream=s)
+    K = ctx.nnz(rho)
+    rng = np.random.default_rng(82)
+    grads = [synth.gaussian(n, rng) for _ in range(4)]
+    with torch.cuda.stream(s):
+        g_static = torch.zeros(n, device=dev)
+        state = torch.zeros(n, device=dev)
+        idx = torch.zeros(2 * K, dtype=torch.int32, device=dev)
+        val = torch.zeros(2 * K, device=dev)
+        s_ref = np.zeros(n, np.float32)
+        for t in range(2):
+            g_static.copy_(torch.from_numpy(grads[t]))
+            ctx.worker_step(g_static, state, float(lr), float(m), rho, idx, val, residual_mode=True)
+            oracle.worker_step(grads[t], s_ref, off, lr, m, rho)
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=s):
+            with pytest.raises(dgs.DgsError) as e:
+                ctx.worker_step(g_static, state, float(lr), float(m), 0.0071, idx, val, residual_mode=True)
+            assert e.value.code == dgs.DGS_ENOTSUP
+            ctx.worker_step(g_static, state, float(lr), float(m), rho, idx, val, residual_mode=True)
+        # nine other densities, eagerly: more than the cache holds
+        scratch = torch.zeros(n, device=dev)
+        for i in range(9):
+            ctx.worker_step(g_static, scratch, float(lr), float(m), 0.001 + 0.0005 * i, idx, val, residual_mode=True)
+        for t in range(2, 4):
+            g_static.copy_(torch.from_numpy(grads[t]))
+            graph.replay()
+            wi, wv = oracle.worker_step(grads[t], s_ref, off, lr, m, rho)
+            s.synchronize()
+            assert_pairs_match(to_host_u32(idx)[:K], val.cpu().numpy()[:K], wi, wv, f"replay {t}")
+            assert_state_match(state.cpu().numpy(), s_ref, f"replay {t}: state")
+    assert ctx.stats().internal_errors == 0
+    ctx.close()
+
+
 def test_worker_and_server_on_two_streams(oracle):
     """Two contexts on two streams of default priority: the worker's step t+1 is enqueued while
     the server still handles push / pull t; messages are double-buffered and ordered with
