@@ -25,7 +25,8 @@
 #define __global__
 #define __device__
 #define __host__
-#define __forceinline__ inline __attribute__((always_inline))
+// (plain inline: forcing everything into the three kernel bodies made the sanitizer build take minutes)
+#define __forceinline__ inline
 // LDS: static storage in a section of its own, so that the scheduler can fill all of it with
 // garbage before every workgroup starts (the hardware gives a workgroup uninitialised LDS).
 #define __shared__ static __attribute__((section("emu_lds")))
