@@ -449,6 +449,105 @@ int dgs_oracle_encode(const uint64_t *offsets, uint32_t J, double density, const
     return ORACLE_OK;
 }
 
+/*
+ * The same wire form with 16-bit values (PARITY UNPINNED with respect to the paper, which names
+ * the combination with quantisation as future work, Section 6; pinned to this statement of it).
+ * Every value travels as a bfloat16: the binary32 number cut to its upper 16 bits (sign, 8
+ * exponent bits, 7 fraction bits), rounded to the nearest such number, halfway cases to the one
+ * whose last kept bit is 0; a value beyond the largest finite bfloat16 becomes infinity; a NaN
+ * stays a NaN (quiet).  Layout: K values of 2 bytes (little endian), padded with zero bytes to
+ * a multiple of 4, then the index blocks exactly as in the 32-bit form.
+ */
+static uint16_t bf16_nearest_even(float x)
+{
+    uint32_t bits, kept, rest;
+    memcpy(&bits, &x, sizeof bits);
+    if ((bits & 0x7FFFFFFFu) > 0x7F800000u) return (uint16_t)((bits >> 16) | 0x0040u);   /* NaN, made quiet */
+    kept = bits >> 16;                 /* candidate below (in magnitude) */
+    rest = bits & 0xFFFFu;             /* what is cut off, in units of 2^-16 of the kept step */
+    if (rest > 0x8000u) kept += 1;                       /* nearer to the candidate above */
+    else if (rest == 0x8000u && (kept & 1u)) kept += 1;  /* halfway: to the even one */
+    return (uint16_t)kept;             /* a carry out of the fraction moves to the next exponent, up to infinity */
+}
+
+int dgs_oracle_wire_bytes16(const uint64_t *offsets, uint32_t J, double density, uint64_t *bytes_out)
+{
+    uint32_t j;
+    uint64_t K = 0, bytes = 0;
+    if (!(density > 0.0) || density > 1.0) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        K += kj;
+        bytes += 4 * ((kj * index_bits(nj) + 31) / 32);
+    }
+    *bytes_out = 4 * ((2 * K + 3) / 4) + bytes;
+    return ORACLE_OK;
+}
+
+int dgs_oracle_encode16(const uint64_t *offsets, uint32_t J, double density, const uint32_t *idx,
+                        const float *val, uint8_t *wire)
+{
+    uint32_t j, t;
+    uint64_t K = 0, e, o = 0, base, total;
+    if (dgs_oracle_wire_bytes16(offsets, J, density, &total) != ORACLE_OK) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) K += dgs_oracle_k(density, offsets[j + 1] - offsets[j]);
+    memset(wire, 0, total);
+    for (e = 0; e < K; ++e) {
+        uint16_t h = bf16_nearest_even(val[e]);
+        wire[2 * e] = (uint8_t)(h & 0xFFu);
+        wire[2 * e + 1] = (uint8_t)(h >> 8);
+    }
+    base = 4 * ((2 * K + 3) / 4);
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        uint32_t b = index_bits(nj);
+        for (e = 0; e < kj; ++e, ++o) {
+            uint64_t local;
+            if (idx[o] < offsets[j] || idx[o] >= offsets[j + 1]) return ORACLE_EINVAL;
+            if (e > 0 && idx[o] <= idx[o - 1]) return ORACLE_EINVAL;
+            local = idx[o] - offsets[j];
+            for (t = 0; t < b; ++t) {
+                uint64_t pos = e * b + t;
+                if ((local >> t) & 1u) wire[base + pos / 8] |= (uint8_t)(1u << (pos % 8));
+            }
+        }
+        base += 4 * ((kj * b + 31) / 32);
+    }
+    return ORACLE_OK;
+}
+
+int dgs_oracle_decode16(const uint64_t *offsets, uint32_t J, double density, const uint8_t *wire,
+                        uint32_t *idx, float *val)
+{
+    uint32_t j, t;
+    uint64_t K = 0, e, o = 0, base;
+    if (!(density > 0.0) || density > 1.0) return ORACLE_EINVAL;
+    for (j = 0; j < J; ++j) K += dgs_oracle_k(density, offsets[j + 1] - offsets[j]);
+    for (e = 0; e < K; ++e) {          /* a bfloat16 is the upper half of a binary32: exact */
+        uint32_t bits = ((uint32_t)wire[2 * e] | ((uint32_t)wire[2 * e + 1] << 8)) << 16;
+        memcpy(&val[e], &bits, sizeof bits);
+    }
+    base = 4 * ((2 * K + 3) / 4);
+    for (j = 0; j < J; ++j) {
+        uint64_t nj = offsets[j + 1] - offsets[j];
+        uint64_t kj = dgs_oracle_k(density, nj);
+        uint32_t b = index_bits(nj);
+        for (e = 0; e < kj; ++e, ++o) {
+            uint64_t local = 0;
+            for (t = 0; t < b; ++t) {
+                uint64_t pos = e * b + t;
+                if ((wire[base + pos / 8] >> (pos % 8)) & 1u) local |= (uint64_t)1 << t;
+            }
+            if (local >= nj) return ORACLE_EINVAL;
+            idx[o] = (uint32_t)(offsets[j] + local);
+        }
+        base += 4 * ((kj * b + 31) / 32);
+    }
+    return ORACLE_OK;
+}
+
 int dgs_oracle_decode(const uint64_t *offsets, uint32_t J, double density, const uint8_t *wire,
                       uint32_t *idx, float *val)
 {

@@ -72,6 +72,9 @@ def lib():
         L.dgs_oracle_wire_bytes.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u64p]
         L.dgs_oracle_encode.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u32p, _c_f32p, _c_u8p]
         L.dgs_oracle_decode.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u8p, _c_u32p, _c_f32p]
+        L.dgs_oracle_wire_bytes16.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u64p]
+        L.dgs_oracle_encode16.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u32p, _c_f32p, _c_u8p]
+        L.dgs_oracle_decode16.argtypes = [_c_u64p, ctypes.c_uint32, ctypes.c_double, _c_u8p, _c_u32p, _c_f32p]
         _lib = L
     return _lib
 
@@ -224,6 +227,34 @@ def encode(offsets: np.ndarray, density: float, idx: np.ndarray, val: np.ndarray
     _check(lib().dgs_oracle_encode(_u64(offsets), len(offsets) - 1, float(density), _u32(idx), _f32(val),
                                    wire.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "encode")
     return wire
+
+
+def wire_bytes16(offsets: np.ndarray, density: float) -> int:
+    out = ctypes.c_uint64(0)
+    _check(lib().dgs_oracle_wire_bytes16(_u64(offsets), len(offsets) - 1, float(density), ctypes.byref(out)),
+           "wire_bytes16")
+    return int(out.value)
+
+
+def encode16(offsets: np.ndarray, density: float, idx: np.ndarray, val: np.ndarray) -> np.ndarray:
+    """The wire form with bfloat16 values (uint8 array)."""
+    _, K = nnz(offsets, density)
+    assert idx.size == K and val.size == K
+    wire = np.zeros(wire_bytes16(offsets, density), dtype=np.uint8)
+    _check(lib().dgs_oracle_encode16(_u64(offsets), len(offsets) - 1, float(density), _u32(idx), _f32(val),
+                                     wire.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))), "encode16")
+    return wire
+
+
+def decode16(offsets: np.ndarray, density: float, wire: np.ndarray):
+    _, K = nnz(offsets, density)
+    assert wire.dtype == np.uint8 and wire.flags.c_contiguous and wire.size == wire_bytes16(offsets, density)
+    idx = np.zeros(K, dtype=np.uint32)
+    val = np.zeros(K, dtype=np.float32)
+    _check(lib().dgs_oracle_decode16(_u64(offsets), len(offsets) - 1, float(density),
+                                     wire.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)), _u32(idx), _f32(val)),
+           "decode16")
+    return idx, val
 
 
 def decode(offsets: np.ndarray, density: float, wire: np.ndarray):

@@ -692,6 +692,86 @@ def test_wire_form_against_big_integer_construction(oracle):
         assert np.array_equal(di, idx) and np.array_equal(bits(dv), bits(val))
 
 
+def bf16_by_rationals(b32: int) -> int:
+    """Nearest bfloat16 of a finite binary32, by exact rational arithmetic: the two bfloat16
+    neighbours (bit patterns with the low half cleared, as integers on the ordered line of
+    magnitudes) and the distances to them as Fractions."""
+    from fractions import Fraction
+    sign = b32 >> 31
+    mag = b32 & 0x7FFFFFFF
+
+    def value(m):          # magnitude of the binary32 with bit pattern m (finite or the 2^128 that "inf" stands for)
+        e, f = m >> 23, m & 0x7FFFFF
+        if e == 0:
+            return Fraction(f, 1 << 149)
+        return Fraction((1 << 23) + f, 1 << 23) * (Fraction(2) ** (e - 127))
+    lo = mag & 0x7FFF0000
+    hi = lo + 0x10000
+    v, vl, vh = value(mag), value(lo), value(hi)
+    if v - vl < vh - v:
+        pick = lo
+    elif v - vl > vh - v:
+        pick = hi
+    else:
+        pick = lo if ((lo >> 16) & 1) == 0 else hi
+    return (sign << 15) | (pick >> 16)
+
+
+def test_wire16_rounding_table_and_hand_example(oracle):
+    with open(os.path.join(HERE, "golden", "x3_wire16_example.json")) as f:
+        ex = json.load(f)
+    off1 = synth.offsets_from_sizes([1])
+    for src, want in ex["rounding"]:
+        val = np.array([int(src, 16)], np.uint32).view(np.float32)
+        wire = oracle.encode16(off1, 1.0, np.array([0], np.uint32), val)
+        got = int(wire[0]) | (int(wire[1]) << 8)
+        assert got == int(want, 16), f"{src}: {got:04X} != {want}"
+        _, back = oracle.decode16(off1, 1.0, wire)
+        assert int(bits(back)[0]) == int(want, 16) << 16
+    m = ex["message"]
+    off = synth.offsets_from_sizes(m["sizes"])
+    kj, K = oracle.nnz(off, m["density"])
+    assert list(kj) == m["k"]
+    idx = np.array(m["idx"], np.uint32)
+    val = np.array([int(h, 16) for h in m["val_bits_hex"]], np.uint32).view(np.float32)
+    want = bytes.fromhex(m["wire_hex"].replace(" ", ""))
+    assert oracle.wire_bytes16(off, m["density"]) == len(want) == 16
+    assert oracle.encode16(off, m["density"], idx, val).tobytes() == want
+    di, dv = oracle.decode16(off, m["density"], np.frombuffer(want, np.uint8).copy())
+    assert np.array_equal(di, idx)
+    assert [f"{int(b):08X}" for b in bits(dv)] == m["decoded_bits_hex"]
+
+
+def test_wire16_against_rational_rounding_and_the_32_bit_index_blocks(oracle):
+    """Random finite values (every exponent, also subnormals and halfway patterns): the value
+    area against exact rational rounding, the index area byte for byte equal to the 32-bit
+    form's (pinned above), the decoded value never further from the original than half a
+    bfloat16 step."""
+    rng = np.random.default_rng(78)
+    for trial in range(20):
+        sizes = [int(x) for x in rng.integers(1, 5000, size=int(rng.integers(1, 6)))]
+        off = synth.offsets_from_sizes(sizes)
+        rho = float(rng.choice([0.01, 0.1, 0.5, 1.0]))
+        kj, K = oracle.nnz(off, rho)
+        idx = np.concatenate([off[j] + np.sort(rng.choice(sizes[j], size=int(kj[j]), replace=False))
+                              for j in range(len(sizes))]).astype(np.uint32)
+        b32 = rng.integers(0, 1 << 32, size=K, dtype=np.uint64).astype(np.uint32)
+        b32[(b32 & 0x7F800000) == 0x7F800000] &= np.uint32(0x807FFFFF)     # keep them finite
+        if K > 4:
+            b32[:4] = [0x3F808000, 0x3F818000, 0x00018000, 0x7F7FFFFF]
+        val = b32.view(np.float32)
+        wire = oracle.encode16(off, rho, idx, val)
+        va = 4 * ((2 * K + 3) // 4)
+        got = wire[:2 * K].view("<u2")
+        want = np.array([bf16_by_rationals(int(b)) for b in b32], np.uint16)
+        assert np.array_equal(got, want), f"trial {trial}"
+        assert not wire[2 * K:va].any()
+        assert wire[va:].tobytes() == oracle.encode(off, rho, idx, val)[4 * K:].tobytes()
+        di, dv = oracle.decode16(off, rho, wire)
+        assert np.array_equal(di, idx)
+        assert np.array_equal(bits(dv), want.astype(np.uint32) << 16)
+
+
 def test_wire_form_rejects_entries_outside_their_tensor(oracle):
     off = synth.offsets_from_sizes([10, 10])
     val = np.ones(2, np.float32)
