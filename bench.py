@@ -298,6 +298,9 @@ def run_worker_server(torch, dgs, name, wl, steps, warmup, dev, *, cpu=True, exa
     for kname, kind in (("encode_us", dgs.PROF_ENCODE), ("decode_us", dgs.PROF_DECODE)):
         cnt, ms = ws.ctx.profile_read(kind)
         wire_info[kname] = round(ms / cnt * 1e3, 2) if cnt else None
+    ws.ctx.set_option(dgs.OPT_WIRE_VALUE_BITS, 16)
+    wire_info["bytes_bf16_values"] = int(ws.ctx.wire_bytes(rho))      # the lossy variant: size only
+    ws.ctx.set_option(dgs.OPT_WIRE_VALUE_BITS, 32)
     ws.ctx.set_option(dgs.OPT_PROFILE, 0)
     del wire, didx, dval
 

@@ -61,6 +61,13 @@ enum {
                                 failed (they wait inside the launch and return at once when their
                                 tensor is fine); 0: such tensors are selected from the state buffer
                                 by one workgroup (slow on large tensors) */
+    DGS_OPT_WIRE_VALUE_BITS = 9, /* 32 (default): the wire form carries fp32 values and is lossless; 16: every
+                                value travels as a bfloat16 (the upper half of the fp32, rounded to nearest,
+                                halfway cases to even, NaN kept) -- what dgs_decode returns then differs
+                                from what was encoded by up to 2^-9 relative.  Applies to dgs_wire_bytes,
+                                dgs_encode and dgs_decode.  Not part of the paper's method (its Section 6
+                                leaves quantisation to future work): the caller decides what to do with
+                                the rounding error */
     DGS_OPT_SPIN_LIMIT = 8   /* polls after which a waiting workgroup of the selection gives up
                                 (default 2^20, far beyond any wait that ends); it is then counted
                                 in dgs_stats.internal_errors.  A tensor whose prediction failed in
@@ -300,6 +307,9 @@ int dgs_apply_sparse(dgs_ctx *ctx, float *dst, const uint32_t *idx, const float 
  *   (b_j = number of bits of n_j - 1, at least 1), entry e in bits [e b_j, (e + 1) b_j) of
  *   the tensor's block, least significant bit first, bit i of a block in bit i mod 8 of its
  *   byte i / 8, each block padded with zero bits to a multiple of 4 bytes.
+ * With DGS_OPT_WIRE_VALUE_BITS = 16 the value area is instead K bfloat16 values of 2 bytes,
+ * little-endian, padded with zero bytes to a multiple of 4 (lossy: see the option); the index
+ * blocks are the same.
  * Both ends derive k_j, b_j and every offset from the layout and the density: no header.
  * A message is what dgs_worker_step, dgs_server_pull or dgs_server_pull_sent returned for
  * `density`: exactly k_j ascending entries per tensor (not dgs_server_pull_all's).

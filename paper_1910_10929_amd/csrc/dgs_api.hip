@@ -186,6 +186,7 @@ struct dgs_ctx {
     bool repair_round = true;
     uint32_t spin_limit = 1u << 20;    // polls before a waiting workgroup of the selection gives up
     uint32_t stream_quads = 0;         // 0 = automatic
+    uint32_t wire_value_bits = 32;     // wire form: fp32 values, or 16 = bfloat16
     // host counters
     uint64_t calls_worker = 0, calls_pull = 0, calls_push = 0, exact_calls = 0;
     ProfClass prof[DGS_PROF_KINDS];
@@ -969,7 +970,8 @@ int dgs_wire_bytes(dgs_ctx *c, double density, uint64_t *bytes_out)
     uint64_t K;
     const int rc = get_plan(c, density, &slot, &K);
     if (rc != DGS_OK) return rc;
-    *bytes_out = 4ull * (K + c->plan_slot[slot].wire_words);
+    const uint64_t vw = (c->wire_value_bits == 16) ? (K + 1) / 2 : K;
+    *bytes_out = 4ull * (vw + c->plan_slot[slot].wire_words);
     return DGS_OK;
 }
 
@@ -995,11 +997,11 @@ int dgs_encode(dgs_ctx *c, double density, const uint32_t *idx, const float *val
     const int rc = get_plan(c, density, &slot, &K);
     if (rc != DGS_OK) return rc;
     const uint64_t words = c->plan_slot[slot].wire_words;
-    if (K + words >= (1ull << 32)) return DGS_EINVAL;
+    if (K + words >= (1ull << 32)) return DGS_EINVAL;      // (the value area is at most K words)
     if (c->validate) launch_fill_u32(c->flag, 0u, 1, c->stream);
     ProfSlot ps(c, DGS_PROF_ENCODE);
-    launch_wire_pack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, (uint32_t)words, idx, val,
-                     (uint32_t *)wire, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
+    launch_wire_pack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, (uint32_t)words,
+                     c->wire_value_bits, idx, val, (uint32_t *)wire, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
     ps.launched();
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     if (c->validate) {
@@ -1021,8 +1023,8 @@ int dgs_decode(dgs_ctx *c, double density, const void *wire, uint32_t *idx_out, 
     if (rc != DGS_OK) return rc;
     if (c->validate) launch_fill_u32(c->flag, 0u, 1, c->stream);
     ProfSlot ps(c, DGS_PROF_DECODE);
-    launch_wire_unpack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, (const uint32_t *)wire,
-                       idx_out, val_out, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
+    launch_wire_unpack(c->tdesc, c->plans + (size_t)slot * c->J, c->J, (uint32_t)K, c->wire_value_bits,
+                       (const uint32_t *)wire, idx_out, val_out, c->validate ? c->flag : nullptr, c->stream, ps.ev0, ps.ev1);
     ps.launched();
     if (hipGetLastError() != hipSuccess) return DGS_EHIP;
     if (c->validate) {
@@ -1050,6 +1052,10 @@ int dgs_set_option(dgs_ctx *c, int option, int64_t value)
         c->seg_mode = (int)value;
         return DGS_OK;
     case DGS_OPT_REPAIR_ROUND: c->repair_round = value != 0; return DGS_OK;
+    case DGS_OPT_WIRE_VALUE_BITS:
+        if (value != 32 && value != 16) return DGS_EINVAL;
+        c->wire_value_bits = (uint32_t)value;
+        return DGS_OK;
     case DGS_OPT_SPIN_LIMIT:
         if (value < 1 || value > (1ll << 30)) return DGS_EINVAL;
         c->spin_limit = (uint32_t)value;

@@ -201,11 +201,11 @@ void launch_push(float *model, float *diff, uint32_t W, uint32_t n, const uint32
                  const float *val, uint32_t nnz, void *stream, void *ev0, void *ev1);
 void launch_validate_idx(const uint32_t *idx, uint32_t nnz, uint32_t n, uint32_t *flag, void *stream);
 void launch_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K, uint32_t words,
-                      const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag, void *stream,
-                      void *ev0, void *ev1);
+                      uint32_t value_bits, const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag,
+                      void *stream, void *ev0, void *ev1);
 void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K,
-                        const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag, void *stream,
-                        void *ev0, void *ev1);
+                        uint32_t value_bits, const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag,
+                        void *stream, void *ev0, void *ev1);
 void launch_apply(float *dst, uint32_t n, const uint32_t *idx, const float *val, uint32_t nnz, float sign,
                   void *stream);
 void launch_fill_u32(uint32_t *p, uint32_t v, size_t count, void *stream);

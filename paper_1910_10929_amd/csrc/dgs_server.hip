@@ -93,20 +93,43 @@ __device__ __forceinline__ uint32_t plan_search(const PlanEntry *plan, uint32_t 
     return lo;                               // offsets increase strictly: every tensor has k_j >= 1
 }
 
-// One thread per value (copied) and per 32-bit word of the index area: the word gathers the
-// pieces of the entries that overlap it (entry e of tensor j covers bits [e b_j, (e + 1) b_j)
-// of the tensor's block).  Out-of-tensor indices are masked to b_j bits and, with `flag`, reported.
+// binary32 -> bfloat16 (its upper half), to nearest, halfway cases to the even one; beyond the
+// largest finite bfloat16 the carry runs into the exponent and gives infinity; NaN stays NaN.
+__device__ __forceinline__ uint32_t to_bf16(float x)
+{
+    const uint32_t b = __float_as_uint(x);
+    if ((b << 1) > 0xFF000000u) return (b >> 16) | 0x40u;
+    return (b + 0x7FFFu + ((b >> 16) & 1u)) >> 16;
+}
+
+// Words of the value area: one per fp32 value, or one per two bfloat16 values.
+__host__ __device__ __forceinline__ uint32_t wire_value_words(uint32_t K, uint32_t value_bits)
+{
+    return value_bits == 16u ? (K + 1u) / 2u : K;
+}
+
+// One thread per word of the value area (a copied fp32 value, or two values rounded to bfloat16)
+// and per 32-bit word of the index area: the word gathers the pieces of the entries that overlap
+// it (entry e of tensor j covers bits [e b_j, (e + 1) b_j) of the tensor's block).  Out-of-tensor
+// indices are masked to b_j bits and, with `flag`, reported.
 __global__ __launch_bounds__(256) void k_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J,
-                                                   uint32_t K, uint32_t words, const uint32_t *idx,
-                                                   const float *val, uint32_t *wire, uint32_t *flag)
+                                                   uint32_t K, uint32_t words, uint32_t value_bits,
+                                                   const uint32_t *idx, const float *val, uint32_t *wire,
+                                                   uint32_t *flag)
 {
     const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
-    if (t < K) {
-        wire[t] = __float_as_uint(val[t]);
+    const uint32_t vw = wire_value_words(K, value_bits);
+    if (t < vw) {
+        if (value_bits == 16u) {
+            const uint32_t e = 2u * (uint32_t)t;
+            wire[t] = to_bf16(val[e]) | ((e + 1u < K) ? (to_bf16(val[e + 1u]) << 16) : 0u);
+        } else {
+            wire[t] = __float_as_uint(val[t]);
+        }
         return;
     }
-    if (t >= (uint64_t)K + words) return;
-    const uint32_t w = (uint32_t)(t - K);
+    if (t >= (uint64_t)vw + words) return;
+    const uint32_t w = (uint32_t)(t - vw);
     const uint32_t j = plan_search<&PlanEntry::wire_off>(plan, J, w);
     const PlanEntry pe = plan[j];
     const TensorDesc td = tdesc[j];
@@ -129,20 +152,26 @@ __global__ __launch_bounds__(256) void k_wire_pack(const TensorDesc *tdesc, cons
     if (bad && flag) atomicOr(flag, 1u);
 }
 
-// One thread per entry: value copied, local index cut out of one or two words of its block.
+// One thread per entry: value copied (a bfloat16 widened), local index cut out of one or two
+// words of its block.
 __global__ __launch_bounds__(256) void k_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J,
-                                                     uint32_t K, const uint32_t *wire, uint32_t *idx,
-                                                     float *val, uint32_t *flag)
+                                                     uint32_t K, uint32_t value_bits, const uint32_t *wire,
+                                                     uint32_t *idx, float *val, uint32_t *flag)
 {
     const uint64_t t = (uint64_t)blockIdx.x * 256 + threadIdx.x;
     if (t >= K) return;
-    val[t] = __uint_as_float(wire[t]);
+    if (value_bits == 16u) {
+        const uint32_t w2 = wire[t >> 1];
+        val[t] = __uint_as_float((t & 1u) ? (w2 & 0xFFFF0000u) : (w2 << 16));
+    } else {
+        val[t] = __uint_as_float(wire[t]);
+    }
     const uint32_t j = plan_search<&PlanEntry::outoff>(plan, J, (uint32_t)t);
     const PlanEntry pe = plan[j];
     const TensorDesc td = tdesc[j];
     const uint32_t b = pe.wire_bits;
     const uint64_t pos = (uint64_t)((uint32_t)t - pe.outoff) * b;
-    const uint32_t *block = wire + K + pe.wire_off;
+    const uint32_t *block = wire + wire_value_words(K, value_bits) + pe.wire_off;
     const uint32_t w = (uint32_t)(pos >> 5), sh = (uint32_t)(pos & 31u);
     uint64_t x = block[w];
     if (sh + b > 32u) x |= (uint64_t)block[w + 1] << 32;              // an entry that crosses ends inside the block
@@ -153,22 +182,22 @@ __global__ __launch_bounds__(256) void k_wire_unpack(const TensorDesc *tdesc, co
 }
 
 void launch_wire_pack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K, uint32_t words,
-                      const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag, void *stream,
-                      void *ev0, void *ev1)
+                      uint32_t value_bits, const uint32_t *idx, const float *val, uint32_t *wire, uint32_t *flag,
+                      void *stream, void *ev0, void *ev1)
 {
-    const uint64_t threads = (uint64_t)K + words;
+    const uint64_t threads = (uint64_t)wire_value_words(K, value_bits) + words;
     if (threads == 0) return;
     launch_k(k_wire_pack, dim3((uint32_t)((threads + 255) / 256)), dim3(256), (hipStream_t)stream, ev0, ev1,
-             tdesc, plan, J, K, words, idx, val, wire, flag);
+             tdesc, plan, J, K, words, value_bits, idx, val, wire, flag);
 }
 
 void launch_wire_unpack(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t J, uint32_t K,
-                        const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag, void *stream,
-                        void *ev0, void *ev1)
+                        uint32_t value_bits, const uint32_t *wire, uint32_t *idx, float *val, uint32_t *flag,
+                        void *stream, void *ev0, void *ev1)
 {
     if (K == 0) return;
     launch_k(k_wire_unpack, dim3((K + 255) / 256), dim3(256), (hipStream_t)stream, ev0, ev1, tdesc, plan, J, K,
-             wire, idx, val, flag);
+             value_bits, wire, idx, val, flag);
 }
 
 __global__ __launch_bounds__(256) void k_fill_u32(uint32_t *p, uint32_t v, size_t count)

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libdgs.so")
 
 DGS_OK = 0
 DGS_EINVAL, DGS_ENOMEM, DGS_ENOTSUP, DGS_ECAPACITY, DGS_EHIP = -1, -2, -3, -4, -5
-OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS, OPT_SEGMENTED, OPT_REPAIR_ROUND, OPT_SPIN_LIMIT = 1, 2, 3, 4, 5, 6, 7, 8
+OPT_FORCE_EXACT, OPT_PROFILE, OPT_VALIDATE, OPT_MARGIN_PCT, OPT_STREAM_QUADS, OPT_SEGMENTED, OPT_REPAIR_ROUND, OPT_SPIN_LIMIT, OPT_WIRE_VALUE_BITS = 1, 2, 3, 4, 5, 6, 7, 8, 9
 SEG_AUTO, SEG_ALWAYS, SEG_NEVER = 0, 1, 2
 (PROF_WORKER_STREAM, PROF_WORKER_SELECT, PROF_PULL_STREAM, PROF_PULL_SELECT, PROF_PUSH, PROF_EXACT_EXTRA,
  PROF_WORKER_SEGMENTED, PROF_PULL_SEGMENTED, PROF_ENCODE, PROF_DECODE) = range(10)

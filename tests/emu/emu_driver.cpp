@@ -30,6 +30,9 @@ int dgs_oracle_server_pull_all(float *, uint64_t, uint32_t *, float *, uint64_t,
 int dgs_oracle_apply_sparse(float *, uint64_t, const uint32_t *, const float *, uint64_t, float);
 int dgs_oracle_wire_bytes(const uint64_t *, uint32_t, double, uint64_t *);
 int dgs_oracle_encode(const uint64_t *, uint32_t, double, const uint32_t *, const float *, uint8_t *);
+int dgs_oracle_wire_bytes16(const uint64_t *, uint32_t, double, uint64_t *);
+int dgs_oracle_encode16(const uint64_t *, uint32_t, double, const uint32_t *, const float *, uint8_t *);
+int dgs_oracle_decode16(const uint64_t *, uint32_t, double, const uint8_t *, uint32_t *, float *);
 }
 
 #define CHECK(c)                                                                             \
@@ -280,6 +283,22 @@ static void helpers_and_static(uint64_t seed)
     CHECK(memcmp(wire.p, wire_ref.p, wb) == 0);
     CHECK(dgs_decode(c.c, rho, wire.p, di.p, dv.p) == DGS_OK);
     expect_same(di.p, dv.p, wi.p, wv.p, K);
+    {   // the same with bfloat16 values (exact-size buffers: the value area is half as long)
+        uint64_t hb = 0, hb2 = 0;
+        CHECK(dgs_set_option(c.c, DGS_OPT_WIRE_VALUE_BITS, 16) == DGS_OK);
+        CHECK(dgs_wire_bytes(c.c, rho, &hb) == DGS_OK);
+        CHECK(dgs_oracle_wire_bytes16(L.off.data(), L.J, rho, &hb2) == 0 && hb == hb2 && hb < wb);
+        Buf<uint8_t> h(hb), h_ref(hb);
+        Buf<uint32_t> qi(K), ri(K);
+        Buf<float> qv(K), rv(K);
+        CHECK(dgs_oracle_encode16(L.off.data(), L.J, rho, wi.p, wv.p, h_ref.p) == 0);
+        CHECK(dgs_encode(c.c, rho, wi.p, wv.p, h.p) == DGS_OK);
+        CHECK(memcmp(h.p, h_ref.p, hb) == 0);
+        CHECK(dgs_oracle_decode16(L.off.data(), L.J, rho, h_ref.p, ri.p, rv.p) == 0);
+        CHECK(dgs_decode(c.c, rho, h.p, qi.p, qv.p) == DGS_OK);
+        expect_same(qi.p, qv.p, ri.p, rv.p, K);
+        CHECK(dgs_set_option(c.c, DGS_OPT_WIRE_VALUE_BITS, 32) == DGS_OK);
+    }
     // apply with a sign, an out-of-range index is skipped
     for (uint64_t i = 0; i < L.n; ++i) theta.p[i] = theta_ref.p[i] = r.gauss();
     CHECK(dgs_oracle_apply_sparse(theta_ref.p, L.n, wi.p, wv.p, K - 1, -1.0f) == 0);

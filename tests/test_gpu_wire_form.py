@@ -53,6 +53,52 @@ def test_wire_form_ragged_layout(oracle, rho):
     ctx.close()
 
 
+def check_both_ways16(oracle, ctx, off, rho, idx, val):
+    """The same with bfloat16 values: wire bytes against the oracle's, decoded values against the
+    oracle's decoding (the rounded values widened again, bit for bit)."""
+    import torch
+    K = idx.size
+    want = oracle.encode16(off, rho, idx, val)
+    assert ctx.wire_bytes(rho) == want.size == oracle.wire_bytes16(off, rho)
+    wire = torch.full((want.size,), 0xA5, dtype=torch.uint8, device=ctx.device)
+    ctx.encode(rho, to_dev(idx, ctx.device), to_dev(val, ctx.device), wire)
+    torch.cuda.synchronize()
+    got = wire.cpu().numpy()
+    if not np.array_equal(got, want):
+        bad = np.nonzero(got != want)[0]
+        raise AssertionError(f"{bad.size} wire bytes differ, first at {bad[0]} of {want.size} (values end at {2 * K})")
+    wi, wv = oracle.decode16(off, rho, want)
+    di = torch.zeros(K, dtype=torch.int32, device=ctx.device)
+    dv = torch.zeros(K, dtype=torch.float32, device=ctx.device)
+    ctx.decode(rho, to_dev(want, ctx.device), di, dv)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host_u32(di), idx) and np.array_equal(wi, idx)
+    assert np.array_equal(dv.cpu().numpy().view(np.uint32), wv.view(np.uint32))
+
+
+@pytest.mark.parametrize("rho", [1e-6, 1e-3, 0.01, 0.3, 1.0])
+def test_wire_form_with_bfloat16_values(oracle, rho):
+    """DGS_OPT_WIRE_VALUE_BITS = 16: any bit pattern as a value (NaNs, infinities, subnormals,
+    halfway cases planted), odd and even K, and back to 32 bits on the same context."""
+    off = synth.offsets_from_sizes(SIZES)
+    rng = np.random.default_rng(91)
+    ctx = dgs.Context(off, W=0)
+    ctx.set_option(dgs.OPT_WIRE_VALUE_BITS, 16)
+    for _ in range(2):
+        idx, val = random_message(oracle, off, rho, rng)
+        planted = np.array([0x3F808000, 0x3F818000, 0x00018000, 0x7F7FFFFF, 0x7F800001, 0xFF7FFFFF, 0x007F8000],
+                           np.uint32)
+        m = min(planted.size, val.size)
+        val.view(np.uint32)[:m] = planted[:m]
+        check_both_ways16(oracle, ctx, off, rho, idx, val)
+    ctx.set_option(dgs.OPT_WIRE_VALUE_BITS, 32)
+    idx, val = random_message(oracle, off, rho, rng)
+    check_both_ways(oracle, ctx, off, rho, idx, val)
+    with pytest.raises(dgs.DgsError):
+        ctx.set_option(dgs.OPT_WIRE_VALUE_BITS, 8)
+    ctx.close()
+
+
 def test_wire_form_of_a_worker_message_resnet50_shapes(oracle):
     """25,557,032 parameters, density 1e-3: the message dgs_worker_step returns, encoded on the
     device, decoded, pushed; bytes against the oracle's encoding of the oracle's message."""
