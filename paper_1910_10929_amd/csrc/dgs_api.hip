@@ -540,9 +540,12 @@ void fill_tables(dgs_ctx *c, TensorDesc *td, uint32_t *tau0, uint32_t *toff, Seg
     }
     for (uint32_t j = 0; j <= J; ++j) toff[j] = (uint32_t)c->offsets[j];
     c->nseg_total = nsegs;
-    // re-collecting workgroups: about 112 per role, so that both roles fit the chip beside each
-    // other, each looking after at most 8 consecutive parts
-    c->bgroup = std::min<uint32_t>(8u, std::max<uint32_t>(1u, (nsegs + 111u) / 112u));
+    // re-collecting workgroups: both roles together about as many as the compute units that the
+    // tensors' selecting workgroups (at most one per tensor) leave free, each looking after at
+    // most 8 consecutive parts
+    const uint32_t busy = std::min<uint32_t>(J, (uint32_t)c->cus / 2u);
+    const uint32_t per_role = std::max<uint32_t>(16u, ((uint32_t)c->cus - busy) / 2u);
+    c->bgroup = std::min<uint32_t>(8u, std::max<uint32_t>(1u, (nsegs + per_role - 1u) / per_role));
     // Join groups: runs of `gparts` consecutive parts (about GROUP_TILES tiles).  The launch takes
     // the groups of the tensors with several groups first: those tensors end with a gather and
     // a selection by the last group to arrive, the critical path of the launch.
