@@ -9,7 +9,8 @@ Default workload (`--workload c5`, the largest single-GPU configuration): 1e9 fp
 parameters in 64 equal tensors, Gaussian gradients with per-tensor log-uniform scale,
 density 1e-4.  The same JSON line carries, as extra objects, the 25.6M-parameter
 ResNet-50-shaped workload (`also_c2`: its step, kernels, roofline, a cold variant with
-rotating buffers), the non-predicted two-pass path (`forced_exact`) and the CPU oracle
+rotating buffers), calls without a prediction (`forced_exact`: two passes; `sampled_every_call`: thresholds
+from a sample) and the CPU oracle
 timed on a bounded sample of the same arrays (`cpu_baseline`), which doubles as a parity
 check of the last timed-regime steps.
 
@@ -153,7 +154,7 @@ class WorkerServer:
         self.rho = wl["density"]
         self.ctx = dgs.Context(off, W=1, device=dev)
         if force_exact:
-            self.ctx.set_option(dgs.OPT_FORCE_EXACT, 1)
+            self.ctx.set_option(dgs.OPT_FORCE_EXACT, int(force_exact))    # 1 (True): two passes; 2: sampled estimate
         self.K = self.ctx.nnz(self.rho)
         n, K = self.n, self.K
         self.g_dev = g_dev
@@ -326,9 +327,11 @@ def run_worker_server(torch, dgs, name, wl, steps, warmup, dev, *, cpu=True, exa
     gc.collect()
     torch.cuda.empty_cache()
 
-    if exact_steps:
-        # the non-predicted path: histogram pass, pick, read-only collecting pass, selection
-        we = WorkerServer(torch, dgs, wl, g_dev, dev, force_exact=True)
+    # calls without a prediction: `forced_exact` takes two passes on every call (full histogram,
+    # pick, read-only collecting pass, selection), `sampled_every_call` what a first call or a new
+    # density takes by default (histogram of a sixteenth of the data, pick, then the one pass)
+    for key, mode in (("forced_exact", 1), ("sampled_every_call", 2)) if exact_steps else ():
+        we = WorkerServer(torch, dgs, wl, g_dev, dev, force_exact=mode)
         dte, te = timed(torch, we.step, 0, 2, exact_steps)
         we.ctx.set_option(dgs.OPT_PROFILE, 1)
         for _ in range(exact_steps):
@@ -338,10 +341,11 @@ def run_worker_server(torch, dgs, name, wl, steps, warmup, dev, *, cpu=True, exa
         ku = read_kernel_us(dgs, we.ctx)
         ste = we.ctx.stats()
         assert ste.internal_errors == 0
-        out["forced_exact"] = {"ms_per_step": dte / exact_steps * 1e3, "steps": exact_steps,
-                               "params_per_s": n * exact_steps / dte,
-                               "step_algorithmic_frac": step_bytes / (dte / exact_steps) / 1e9 / HBM_PEAK_GBS,
-                               "kernel_us": ku, "exact_extra_us": ku["exact_extra"]}
+        out[key] = {"ms_per_step": dte / exact_steps * 1e3, "steps": exact_steps,
+                    "params_per_s": n * exact_steps / dte,
+                    "step_algorithmic_frac": step_bytes / (dte / exact_steps) / 1e9 / HBM_PEAK_GBS,
+                    "kernel_us": ku, "exact_extra_us": ku["exact_extra"],
+                    "repaired_tensors": ste.repaired_tensors}
         we.close()
         del we
         gc.collect()

@@ -48,7 +48,14 @@ enum {
 
 /* Options for dgs_set_option(). */
 enum {
-    DGS_OPT_FORCE_EXACT = 1, /* 1: never use the previous step's threshold as a prediction */
+    DGS_OPT_FORCE_EXACT = 1, /* How a call finds its candidate thresholds.  0 (default): from the previous
+                                call on the same state (one pass over the data); a call without a usable
+                                prediction -- the first one, a new density -- estimates them from a
+                                histogram of a sixteenth of the data and goes on in one pass.  1: every
+                                call takes two passes (full histogram, then collection).  2: every call
+                                estimates from the sample.  The results are the same in all three: a
+                                threshold that lets too few candidates through is repaired inside the
+                                call */
     DGS_OPT_PROFILE = 2,     /* 1: attach start/stop HIP events to the kernels of each call */
     DGS_OPT_VALIDATE = 3,    /* 1: dgs_server_push checks idx on the device (synchronises) */
     DGS_OPT_MARGIN_PCT = 4,  /* candidate over-provisioning in percent of k_j (default 50) */

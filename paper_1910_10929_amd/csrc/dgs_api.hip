@@ -25,7 +25,7 @@ size_t align_up(size_t x) { return (x + ALIGN - 1) / ALIGN * ALIGN; }
 
 struct Layout {          // byte offsets inside the workspace
     size_t tile_desc, tdesc, plans, tau, hint2, tprev, ghist, tile_cnt, heads, slots, ord, stats, flag;
-    size_t segtab, grptab, grpcnt, segstart, segcnt, segG1, segOut, segstate, pfxlist, total;
+    size_t qlist, segtab, grptab, grpcnt, segstart, segcnt, segG1, segOut, segstate, pfxlist, total;
 };
 
 bool check_offsets(const uint64_t *offsets, uint32_t J)
@@ -92,6 +92,7 @@ Layout make_layout(const uint64_t *offsets, uint32_t J, uint32_t W)
     L.ord = o;       o = align_up(o + (ntiles + J) * CAPT * sizeof(uint2));
     L.stats = o;     o = align_up(o + sizeof(DevStats));
     L.flag = o;      o = align_up(o + 64);
+    L.qlist = o;     o = align_up(o + (ntiles + 4) * sizeof(uint32_t));
     L.segtab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));
     L.grptab = o;    o = align_up(o + (nseg_total + 1) * sizeof(SegDesc));      // groups <= parts
     L.grpcnt = o;    o = align_up(o + (nseg_total + 1) * sizeof(uint32_t));
@@ -159,6 +160,8 @@ struct dgs_ctx {
     uint2 *ord = nullptr;
     DevStats *stats = nullptr;
     uint32_t *flag = nullptr;
+    uint32_t *qlist = nullptr;         // the tiles that a sampling pass visits
+    uint32_t nqlist = 0;               // 0: no sampling on this context
     SegDesc *segtab = nullptr;
     SegDesc *grptab = nullptr;
     uint32_t *grpcnt = nullptr, *segstart = nullptr;
@@ -181,6 +184,7 @@ struct dgs_ctx {
     bool no_alloc = false;             // tables go up as kernel arguments, nothing is allocated or copied
     // options
     bool force_exact = false, profile = false, validate = false;
+    bool force_sample = false;         // never predict, estimate from a sample on every call
     int margin_pct = 50;
     int seg_mode = SEG_MODE_AUTO;
     bool repair_round = true;
@@ -361,7 +365,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
     // repair round): the worker's are in `state` by then, a model - sent_k pull recomputes them
     const int op_again = (op_stream == OP_SUB) ? OP_SUB : OP_IDENT;
     const bool dense_req = density > DENSE_DENSITY;
-    const bool exact = !dense_req && (c->force_exact || c->hint_density[hint_set] != density);
+    const bool exact = !dense_req && (c->force_exact || c->force_sample || c->hint_density[hint_set] != density);
     uint32_t *tau = c->tau + (size_t)hint_set * c->J;
     const PlanEntry *plan = c->plans + (size_t)slot * c->J;
 
@@ -392,7 +396,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         const uint32_t blocks = stream_blocks(c, MODE_HIST, &sa.quads_per_block);
         launch_stream(op_stream, MODE_HIST, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
         ps.launched();
-        launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, c->stream);
+        launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, false, c->stream);
     } else if (dense_req) {
         if (op_stream == OP_FMA) {
             ProfSlot ps(c, prof_stream);
@@ -400,6 +404,27 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
             launch_stream(OP_FMA, MODE_PLAIN, vec, sa, blocks, c->stream, ps.ev0, ps.ev1);
             ps.launched();
         }
+    } else if (exact && !c->force_exact && c->nqlist != 0) {
+        // No usable prediction: a histogram of a sample of the buffer gives the thresholds (k_pick
+        // scales the ranks), and the call goes on as a predicted one; where the estimate lets too
+        // few candidates through, the selection launch collects that tensor again.
+        ++c->exact_calls;
+        ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
+        StreamArgs sb = sa;
+        sb.tile_list = c->qlist;
+        sb.nlist = c->nqlist;
+        sb.nquads = (c->nqlist + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
+        // about two workgroups per compute unit: every workgroup ends with a flush of its LDS
+        // histogram into the tensors' counters, and those atomics meet on a few hundred addresses
+        sb.quads_per_block = std::max<uint32_t>(1u, (sb.nquads + (uint32_t)c->cus * 2u - 1u) / ((uint32_t)c->cus * 2u));
+        launch_stream(op_stream, MODE_SAMPLE, vec, sb, (sb.nquads + sb.quads_per_block - 1u) / sb.quads_per_block,
+                      c->stream, ps.ev0, ps.ev1);
+        ps.launched();
+        launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, true, c->stream);
+        ProfSlot pc(c, prof_stream);
+        const uint32_t blocks = stream_blocks(c, MODE_COLLECT, &sa.quads_per_block);
+        launch_stream(op_stream, MODE_COLLECT, vec, sa, blocks, c->stream, pc.ev0, pc.ev1);
+        pc.launched();
     } else if (exact) {
         ++c->exact_calls;
         {
@@ -409,7 +434,7 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
             ps.launched();
         }
         {
-            launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, c->stream);
+            launch_pick(c->tdesc, plan, c->ghist, tau, tprev, c->stats, c->J, false, c->stream);
             ProfSlot ps(c, DGS_PROF_EXACT_EXTRA);
             StreamArgs sb = sa;
             if (op_again == OP_IDENT) sb.grad = nullptr;
@@ -498,6 +523,7 @@ void carve_workspace(dgs_ctx *c, void *workspace, const Layout &L)
     c->ord = (uint2 *)(c->ws + L.ord);
     c->stats = (DevStats *)(c->ws + L.stats);
     c->flag = (uint32_t *)(c->ws + L.flag);
+    c->qlist = (uint32_t *)(c->ws + L.qlist);
     c->segtab = (SegDesc *)(c->ws + L.segtab);
     c->grptab = (SegDesc *)(c->ws + L.grptab);
     c->grpcnt = (uint32_t *)(c->ws + L.grpcnt);
@@ -673,7 +699,24 @@ int dgs_create(dgs_ctx **out, const uint64_t *offsets, uint32_t J, uint32_t W, v
     c->nseg.assign(J, 0u);
     fill_tables(c, td.data(), tau0.data(), toff.data(), segs.data(), groups.data());
 
+    // What a sampling pass visits: every 16th tile of the buffer, and every tile of the tensors of
+    // at most 64 tiles, whose ranks are too small to estimate from a sixteenth.
+    std::vector<uint32_t> qlist;
+    {
+        std::vector<uint8_t> mark(c->ntiles, 0);
+        for (uint32_t t = 0; t < c->ntiles; t += 16) mark[t] = 1;
+        for (uint32_t j = 0; j < J; ++j) {
+            if (!td[j].big) continue;
+            const uint32_t tlo = td[j].off / TILE, thi = (td[j].off + td[j].n - 1) / TILE;
+            if (thi - tlo + 1 > 64) continue;
+            for (uint32_t t = tlo; t <= thi; ++t) mark[t] = 1;
+        }
+        for (uint32_t t = 0; t < c->ntiles; ++t)
+            if (mark[t]) qlist.push_back(t);
+    }
+    c->nqlist = (uint32_t)qlist.size();
     bool ok = true;
+    ok = ok && upload(c, c->qlist, qlist.data(), qlist.size() * sizeof(uint32_t)) == DGS_OK;
     ok = ok && hipHostMalloc((void **)&c->plan_stage, (size_t)NPLAN * J * sizeof(PlanEntry), hipHostMallocDefault) == hipSuccess;
     ok = ok && upload_tables(c, td.data(), tau0.data(), toff.data(), segs.data(), groups.data()) == DGS_OK;
     ok = ok && hipStreamSynchronize(c->stream) == hipSuccess;
@@ -1043,7 +1086,11 @@ int dgs_set_option(dgs_ctx *c, int option, int64_t value)
 {
     if (!c) return DGS_EINVAL;
     switch (option) {
-    case DGS_OPT_FORCE_EXACT: c->force_exact = value != 0; return DGS_OK;
+    case DGS_OPT_FORCE_EXACT:
+        if (value < 0 || value > 2) return DGS_EINVAL;
+        c->force_exact = value == 1;
+        c->force_sample = value == 2;
+        return DGS_OK;
     case DGS_OPT_PROFILE: c->profile = value != 0; return DGS_OK;
     case DGS_OPT_VALIDATE: c->validate = value != 0; return DGS_OK;
     case DGS_OPT_MARGIN_PCT:

@@ -128,7 +128,9 @@ struct DevStats {
 // OP_FMA: a = fmaf(lr, grad, state), state <- a (worker);  OP_IDENT: a = state (pull on a
 // difference row);  OP_SUB: a = grad - state, nothing stored (pull on model - sent_k).
 enum StreamOp { OP_FMA = 0, OP_IDENT = 1, OP_SUB = 2 };
-enum StreamMode { MODE_PLAIN = 0, MODE_COLLECT = 1, MODE_HIST = 2 };
+// MODE_SAMPLE: the histogram of a sample of the buffer (the tiles in tile_list, zero keys counted
+// too so that a tensor's counters add up to its sampled elements), nothing stored.
+enum StreamMode { MODE_PLAIN = 0, MODE_COLLECT = 1, MODE_HIST = 2, MODE_SAMPLE = 3 };
 enum StoreMode { STORE_PLAIN = 0, STORE_WT = 1, STORE_NT = 2 };
 // What happens to a sent entry: SEL_WORKER state <- m * val;  SEL_PULL state <- +0;
 // SEL_PULL_V state <- state + val (the values themselves are model - state).
@@ -144,6 +146,8 @@ struct StreamArgs {
     uint2 *slots;                 // per tile CAPT x (index, value bits): candidates HEAD .. CAPT-1
     uint32_t *ghist;              // per tensor HBINS counters
     uint32_t n, ntiles, nquads, quads_per_block, J;
+    const uint32_t *tile_list;    // MODE_SAMPLE: the tiles to visit, nlist of them, four per "quad"
+    uint32_t nlist;               //   (nquads = ceil(nlist / 4))
     float lr;
     uint32_t store_mode;          // OP_FMA: how the state is written back (StoreMode)
 };
@@ -191,7 +195,7 @@ struct SelectArgs {
 void launch_stream(int op, int mode, bool vec, const StreamArgs &a, uint32_t blocks, void *stream,
                    void *ev0, void *ev1);
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream);
+                 uint32_t *tprev, DevStats *stats, uint32_t J, bool sample, void *stream);
 // The selection: one launch for every tensor (join, exact k-th key, ordered emission, state
 // fix-up, next hint; failed predictions are collected again inside the same launch).
 void launch_select(int op, const SelectArgs &a, void *stream, void *ev0, void *ev1);

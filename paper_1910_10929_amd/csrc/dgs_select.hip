@@ -37,23 +37,61 @@ __device__ __forceinline__ void pick_from_hist(const uint32_t *h, const PlanEntr
     tprev_out = (b1 >= 0) ? (((uint32_t)b1 << HSHIFT) + (1u << (HSHIFT - 1))) : 0u;
 }
 
+// sample != 0: the histogram is that of a sample of the tensor, zero keys included (its total is
+// the number of sampled elements).  The ranks shrink with the sampled share; the candidate rank
+// aims at 2 k instead of the plan's and gets two standard deviations of slack on top, since a
+// threshold that lets too few through costs a second collection and one that lets a few more
+// through costs nothing.  A tensor that was sampled completely keeps the plan's ranks.
 __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const PlanEntry *plan,
                                               uint32_t *ghist, uint32_t *tau, uint32_t *tprev,
-                                              DevStats *stats)
+                                              DevStats *stats, uint32_t sample)
 {
     const uint32_t j = blockIdx.x;
     if (!tdesc[j].big) return;
     __shared__ uint32_t h[HBINS];
     __shared__ uint32_t rowsum[64];
     __shared__ int res[6];
+    __shared__ uint32_t wsum[4];
     uint32_t *g = ghist + (size_t)j * HBINS;
+    uint32_t mine = 0;
     for (uint32_t b = threadIdx.x; b < HBINS; b += 256) {
-        h[b] = g[b];
+        const uint32_t v = g[b];
+        h[b] = v;
+        mine += v;
         g[b] = 0;   // leave the histogram clean for the next use
     }
-    const PlanEntry pe = plan[j];
+    PlanEntry pe = plan[j];
+    if (sample) {
+        const uint32_t total = block_sum(mine, wsum, 4);
+        // from here on the histogram is that of the nonzero keys, as in a full pass (bucket 0 held
+        // the zeros; keys below 2^19, denormals of about 1e-39, go with them)
+        if (threadIdx.x == 0) h[0] = 0;
+        __syncthreads();
+        const uint32_t n = tdesc[j].n;
+        if (total < n) {
+            const double share = (double)total / (double)n;
+            const double want = share * (double)min(2u * pe.k, n);
+            const uint32_t k2s = (uint32_t)ceil(want + 2.0 * sqrt(want)) + 1u;
+            pe.k2 = max(1u, min(k2s, total));
+            pe.k = max(1u, min((uint32_t)ceil(share * (double)pe.k), pe.k2));
+        }
+    }
     uint32_t t, tp;
     pick_from_hist<4>(h, pe, rowsum, res, t, tp);
+    if (sample) {
+        // A sample that holds fewer nonzeros than the scaled k says nothing about where the k-th
+        // key lies, except that it cannot be far above the smallest nonzero seen: that bucket
+        // anchors the window histograms then (a full pass knows the bucket itself).
+        __shared__ uint32_t lowbin;
+        if (threadIdx.x == 0) lowbin = 0xFFFFFFFFu;
+        __syncthreads();
+        uint32_t mine_low = 0xFFFFFFFFu;
+        for (uint32_t b = 1 + threadIdx.x; b < HBINS; b += 256)
+            if (h[b] != 0) { mine_low = b; break; }
+        if (mine_low != 0xFFFFFFFFu) atomicMin(&lowbin, mine_low);
+        __syncthreads();
+        if (tp == 0 && lowbin != 0xFFFFFFFFu) tp = (lowbin << HSHIFT) + (1u << (HSHIFT - 1));
+    }
     if (threadIdx.x == 0) {
         tau[j] = t;
         tprev[j] = tp;
@@ -61,10 +99,10 @@ __global__ __launch_bounds__(256) void k_pick(const TensorDesc *tdesc, const Pla
 }
 
 void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist, uint32_t *tau,
-                 uint32_t *tprev, DevStats *stats, uint32_t J, void *stream)
+                 uint32_t *tprev, DevStats *stats, uint32_t J, bool sample, void *stream)
 {
     hipLaunchKernelGGL(k_pick, dim3(J), dim3(256), 0, (hipStream_t)stream, tdesc, plan, ghist, tau, tprev,
-                       stats);
+                       stats, sample ? 1u : 0u);
 }
 
 // ---------------------------------------------------------------------------

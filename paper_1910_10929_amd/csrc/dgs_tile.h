@@ -14,7 +14,7 @@ namespace dgs {
 template <int MODE>
 __device__ __forceinline__ void flush_hist(uint32_t *lhist, uint32_t *ghist, int cur)
 {
-    if (MODE != MODE_HIST) return;
+    if (MODE != MODE_HIST && MODE != MODE_SAMPLE) return;
     __syncthreads();
     if (cur >= 0) {
         for (uint32_t b = threadIdx.x; b < HBINS; b += STREAM_THREADS) {
@@ -145,8 +145,9 @@ __device__ __forceinline__ void tile_tail(const StreamArgs &A, const uint32_t *_
         if (!straddle) runA = run;
         if (lane == 0)
             A.tile_cnt[t] = (run > CAPT) ? CNT_OVERFLOW : (runA | ((run - runA) << 16));
-    } else {  // MODE_HIST
+    } else {  // MODE_HIST, MODE_SAMPLE
         const bool bigA = (d.x >> 31) != 0, bigB = (d.y >> 31) != 0;
+        uint32_t zeroA = 0, zeroB = 0;     // MODE_SAMPLE: zero keys of the two tensors, added once per tile
 #pragma unroll
         for (int r = 0; r < 4; ++r) {
 #pragma unroll
@@ -161,10 +162,32 @@ __device__ __forceinline__ void tile_tail(const StreamArgs &A, const uint32_t *_
                 }
                 if (tt < 0 || (only >= 0 && tt != only)) continue;
                 const uint32_t key = __float_as_uint(a[r][j]) & 0x7FFFFFFFu;
-                if (key == 0) continue;            // zeros (often the bulk of a difference row) are implied
+                if (key == 0) {
+                    // zeros (often the bulk of a difference row) are implied; a sample counts
+                    // them, so that the counters of a tensor add up to what was sampled of it
+                    if (MODE == MODE_SAMPLE) {
+                        if (e < endA) ++zeroA;
+                        else ++zeroB;
+                    }
+                    continue;
+                }
                 const uint32_t bin = key >> HSHIFT;
                 if (tt == cur) atomicAdd(&lhist[bin], 1u);
                 else atomicAdd(&A.ghist[(size_t)tt * HBINS + bin], 1u);
+            }
+        }
+        if (MODE == MODE_SAMPLE) {
+            zeroA = wave_sum(zeroA);
+            zeroB = wave_sum(zeroB);
+            if (lane == 0) {
+                if (zeroA) {
+                    if ((int)tA == cur) atomicAdd(&lhist[0], zeroA);
+                    else atomicAdd(&A.ghist[(size_t)tA * HBINS], zeroA);
+                }
+                if (zeroB) {
+                    if ((int)tB == cur) atomicAdd(&lhist[0], zeroB);
+                    else atomicAdd(&A.ghist[(size_t)tB * HBINS], zeroB);
+                }
             }
         }
     }
@@ -212,7 +235,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
         if (MODE != MODE_PLAIN) tile_tail<MODE>(A, tau, t, d, a, lhist, cur, stage, only);
         // The state goes out last: this wave never has to wait for the stores to be
         // acknowledged (the memory counter it would wait on also counts stores).
-        if (OP == OP_FMA) {
+        if (OP == OP_FMA && MODE != MODE_SAMPLE) {
             // How the state goes back (measured on the accumulate pass, 25.6M / 1e9 parameters):
             // plain write-back stores 47.3 / 2131 us; device-scope write-through 45.3 / 2035 us;
             // non-temporal 48.8 / 1951 us.  Write-through for buffers that fit the last-level
@@ -241,7 +264,7 @@ __device__ __forceinline__ void process_tile(const StreamArgs &A, const uint32_t
             if (e < A.n) {
                 if (OP == OP_FMA) {
                     v = __builtin_fmaf(A.lr, A.grad[e], A.state[e]);
-                    A.state[e] = v;
+                    if (MODE != MODE_SAMPLE) A.state[e] = v;
                 } else if (OP == OP_SUB) {
                     v = A.grad[e] - A.state[e];
                 } else {

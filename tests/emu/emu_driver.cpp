@@ -337,7 +337,10 @@ static void soak(uint64_t seed)
     static const double rhos[] = {0.0005, 0.001, 0.002, 0.004, 0.01, 0.03, 0.05, 0.3, 1.0};
     const double rho_up = rhos[r.u32() % 9], rho_down = rhos[r.u32() % 9];
     Opts o;
-    o.force_exact = (r.u32() % 5) == 0;
+    {
+        const uint32_t pick = r.u32() % 6;       // mostly predicted; two-pass and sampled now and then
+        o.force_exact = pick == 0 ? 1 : (pick == 1 ? 2 : 0);
+    }
     o.seg_mode = (int)(r.u32() % 3);
     o.repair = (r.u32() % 4) != 0;
     o.margin = (r.u32() % 3) == 0 ? (int)(r.u32() % 120) : -1;
@@ -397,6 +400,11 @@ int main(int argc, char **argv)
     worker_server("scale jumps, chain for every large tensor", two, 0.002, 0.002, 1.0f, 0.0f, true, jumps, 0, always, 3);
     if (!quick) {
         worker_server("ragged, exact path", ragged, 0.01, 0.002, 0.5f, 0.9f, false, {1, 1}, 0, exact, 4);
+        Opts sampled;
+        sampled.force_exact = 2;
+        worker_server("ragged, sampled estimate on every call", ragged, 0.004, 0.002, 0.5f, 0.9f, false, {1, 1, 1e3f, 1e-6f, 1}, 0,
+                      sampled, 30);
+        worker_server("mostly zeros, sampled estimate", two, 0.001, 0.02, 1.0f, 0.9f, false, steady, 2, sampled, 31);
         worker_server("scale jumps, no re-collecting roles", two, 0.002, 0.004, 1.0f, 0.0f, true, jumps, 0, norepair, 5);
         worker_server("massive ties", two, 0.003, 0.003, 1.0f, 0.9f, false, steady, 1, def, 6);
         worker_server("massive ties, chain", two, 0.003, 0.003, 1.0f, 0.9f, false, steady, 1, always, 7);

@@ -105,7 +105,7 @@ def run_worker_parity(oracle, off, grads, lr, m, rho, *, force_exact=False, resi
     from paper_1910_10929_amd import dgs
     ctx = dgs.Context(off, W=0)
     if force_exact:
-        ctx.set_option(dgs.OPT_FORCE_EXACT, 1)
+        ctx.set_option(dgs.OPT_FORCE_EXACT, int(force_exact))      # True: two passes; 2: sampled estimate
     if margin is not None:
         ctx.set_option(dgs.OPT_MARGIN_PCT, margin)
     if seg_mode is not None:

@@ -61,7 +61,7 @@ def test_c1_flat_one_million(oracle, torch_mod):
     ctx.close()
 
 
-@pytest.mark.parametrize("force_exact", [False, True], ids=["predicted", "exact"])
+@pytest.mark.parametrize("force_exact", [False, True, 2], ids=["predicted", "exact", "sampled"])
 @pytest.mark.parametrize("rho", [0.001, 0.01, 0.03])
 def test_ragged_multi_tensor(oracle, torch_mod, rho, force_exact):
     """Unaligned tensor borders, tiny and large tensors, a ragged tail tile."""
@@ -83,9 +83,9 @@ def test_predicted_and_exact_paths_agree_bytewise(oracle, torch_mod):
     rng = np.random.default_rng(23)
     grads = [synth.gaussian(int(off[-1]), rng) for _ in range(5)]
     outs = []
-    for force in (False, True, False):
+    for force in (0, 1, 0, 2):          # predicted, two passes, predicted again, sampled estimate on every call
         ctx = dgs.Context(off, W=0)
-        ctx.set_option(dgs.OPT_FORCE_EXACT, int(force))
+        ctx.set_option(dgs.OPT_FORCE_EXACT, force)
         w = Worker(ctx, density_max=0.005)
         run = []
         for g in grads:
@@ -93,7 +93,7 @@ def test_predicted_and_exact_paths_agree_bytewise(oracle, torch_mod):
             run.append((i.copy(), v.copy(), w.state_host()))
         outs.append(run)
         ctx.close()
-    for a, b in ((outs[0], outs[1]), (outs[0], outs[2])):
+    for a, b in ((outs[0], outs[1]), (outs[0], outs[2]), (outs[0], outs[3])):
         for (i1, v1, s1), (i2, v2, s2) in zip(a, b):
             assert np.array_equal(i1, i2)
             assert np.array_equal(v1.view(np.uint32), v2.view(np.uint32))

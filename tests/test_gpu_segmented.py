@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 SEG_SIZES = [100_003, 7, 1 << 18, 65_537, 300_001, 64, 70_001, 600_000, 9000, 65_536]
 
 
-@pytest.mark.parametrize("force_exact", [False, True], ids=["predicted", "exact"])
+@pytest.mark.parametrize("force_exact", [False, True, 2], ids=["predicted", "exact", "sampled"])
 @pytest.mark.parametrize("rho", [0.001, 0.01, 0.03])
 def test_segmented_ragged_multi_tensor(oracle, rho, force_exact):
     off = synth.offsets_from_sizes(SEG_SIZES)

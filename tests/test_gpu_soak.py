@@ -43,6 +43,7 @@ def run(oracle, seed):
     if rng.integers(0, 3) == 0: opts[dgs.OPT_MARGIN_PCT] = int(rng.choice([0, 10, 200]))
     if rng.integers(0, 4) == 0: opts[dgs.OPT_STREAM_QUADS] = int(rng.choice([2, 5]))
     if rng.integers(0, 4) == 0: opts[dgs.OPT_REPAIR_ROUND] = 0
+    if rng.integers(0, 5) == 0: opts[dgs.OPT_FORCE_EXACT] = 2          # sampled estimate on every call
     W = 2
     ctx = dgs.Context(off, W=W)
     for k, v in opts.items(): ctx.set_option(k, v)
