@@ -109,10 +109,12 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 // the selection kernel
 // ---------------------------------------------------------------------------
 //
-// Grid: block b < P is the JOIN of part b (1024 threads).  With the re-collecting roles
-// enabled, ceil(P / bgroup) RE-HISTOGRAM blocks follow, then as many RE-COLLECTION blocks,
-// each looking after `bgroup` consecutive parts in turn (they act on tensors of several parts
-// whose prediction failed, and pass over everything else).
+// Grid: block b < G is the JOIN of join group b (1024 threads; a group is a tensor, or up to
+// GROUP_TILES tiles of one).  With the re-collecting roles enabled, nb = ceil(P / bgroup)
+// RE-HISTOGRAM blocks follow (P: the number of parts), then as many RE-COLLECTION blocks; block
+// b of a role looks after parts b, b + nb, b + 2 nb, ... in turn, so the parts of one tensor
+// lie in different blocks.  These blocks act on tensors of several parts whose prediction
+// failed, and pass over everything else.
 //
 //   JOIN      compacts the candidates the streaming pass left in the part's tiles into one
 //             ordered list.  The workgroup that arrives last for a tensor (the only one, for a
@@ -345,17 +347,25 @@ __device__ __forceinline__ void dense_hist(const SelectArgs &A, const TensorDesc
     const DenseRun r = dense_run(td, sd);
     const uint32_t lane = lane_id();
     const bool vec = rows_aligned(A);
-    for (uint32_t t = r.t0; t < r.t1; ++t) {
-        uint32_t bits[4][4];     // the whole tile is fetched before the first counter is touched
+    // two tiles per turn, all of their loads issued before the first counter is touched (the odd
+    // last turn reads its one tile twice and counts it once)
+    for (uint32_t t = r.t0; t < r.t1; t += 2) {
+        const bool two = t + 1 < r.t1;
+        uint32_t bits[2][4][4];
 #pragma unroll
-        for (int row = 0; row < 4; ++row) quad_bits<OP>(A, t * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, bits[row]);
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int row = 0; row < 4; ++row)
+            for (int row = 0; row < 4; ++row)
+                quad_bits<OP>(A, (u && two ? t + 1 : t) * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, bits[u][row]);
 #pragma unroll
-            for (int x = 0; x < 4; ++x) {
-                const uint32_t key = bits[row][x] & 0x7FFFFFFFu;      // elements outside the tensor read as 0
-                if (key != 0) atomicAdd(&lh[key >> HSHIFT], 1u);
-            }
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int row = 0; row < 4; ++row)
+#pragma unroll
+                for (int x = 0; x < 4; ++x) {
+                    const uint32_t key = bits[u][row][x] & 0x7FFFFFFFu;      // elements outside the tensor read as 0
+                    if (key != 0 && (u == 0 || two)) atomicAdd(&lh[key >> HSHIFT], 1u);
+                }
     }
     __syncthreads();
 }
@@ -371,15 +381,22 @@ __device__ __forceinline__ uint32_t dense_compact(const SelectArgs &A, const Ten
     const uint32_t lane = lane_id(), wave = threadIdx.x >> 6;
     const bool vec = rows_aligned(A);
     uint32_t mine = 0;
-    for (uint32_t t = r.t0; t < r.t1; ++t) {
-        uint32_t bits[4][4], in[4];
+    for (uint32_t t = r.t0; t < r.t1; t += 2) {      // two tiles in flight, as in dense_hist
+        const bool two = t + 1 < r.t1;
+        uint32_t bits[2][4][4], in[2][4];
 #pragma unroll
-        for (int row = 0; row < 4; ++row) in[row] = quad_bits<OP>(A, t * TILE + row * 256 + lane * 4, r.lo, r.hi, vec, bits[row]);
+        for (int u = 0; u < 2; ++u)
 #pragma unroll
-        for (int row = 0; row < 4; ++row)
+            for (int row = 0; row < 4; ++row)
+                in[u][row] = quad_bits<OP>(A, (u && two ? t + 1 : t) * TILE + row * 256 + lane * 4, r.lo, r.hi, vec,
+                                           bits[u][row]);
 #pragma unroll
-            for (int x = 0; x < 4; ++x)
-                if (((in[row] >> x) & 1u) && (bits[row][x] & 0x7FFFFFFFu) >= tau) ++mine;
+        for (int u = 0; u < 2; ++u)
+#pragma unroll
+            for (int row = 0; row < 4; ++row)
+#pragma unroll
+                for (int x = 0; x < 4; ++x)
+                    if ((u == 0 || two) && ((in[u][row] >> x) & 1u) && (bits[u][row][x] & 0x7FFFFFFFu) >= tau) ++mine;
     }
     const uint32_t wsum_ = wave_sum(mine);
     __syncthreads();
@@ -874,24 +891,21 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
     __shared__ uint2 llist[SEL_LDS_LIST];
     const uint32_t tid = threadIdx.x;
     if (blockIdx.x >= A.ngroups) {
-        // RE-HISTOGRAM / RE-COLLECTION: this workgroup looks after B_GROUP consecutive parts
+        // RE-HISTOGRAM / RE-COLLECTION: this workgroup looks after up to B_GROUP parts, nb apart,
+        // so that the parts of one failed tensor are spread over as many workgroups as there are
         const uint32_t nb = (A.nparts + A.bgroup - 1) / A.bgroup;
         const uint32_t b = blockIdx.x - A.ngroups;
         const uint32_t role = (b < nb) ? 1u : 2u;
-        const uint32_t first = (role == 1 ? b : b - nb) * A.bgroup;
-        const uint32_t cnt = min(first + A.bgroup, A.nparts) - first;
-        // the verdicts of the tensors these parts belong to: lane i waits for part i's tensor if
-        // that part is the first of its tensor in the group (parts of a tensor are consecutive),
-        // and signs off for all of the tensor's parts in the group at once
+        const uint32_t first = (role == 1) ? b : b - nb;
+        // the verdicts of the tensors these parts belong to: lane i waits for part i's tensor and
+        // signs off for that part
         if (tid < B_GROUP_MAX) P.vbuf[tid] = 0;
         __syncthreads();
-        if (tid < cnt) {
-            const SegDesc sd = A.segtab[first + tid];
-            const bool head = (tid == 0) || (A.segtab[first + tid - 1].j != sd.j);
-            if (A.tdesc[sd.j].nseg > 1 && head) {
+        const uint32_t mypart = first + tid * nb;
+        if (tid < A.bgroup && mypart < A.nparts) {
+            const SegDesc sd = A.segtab[mypart];
+            if (A.tdesc[sd.j].nseg > 1) {
                 SegState *st = &A.segstate[sd.j];
-                uint32_t mine = 1;
-                while (tid + mine < cnt && A.segtab[first + tid + mine].j == sd.j) ++mine;
                 uint32_t v = 0;
                 for (uint32_t spin = 0; spin < A.spin_limit; ++spin) {
                     v = ld_dev(&st->verdict);
@@ -899,13 +913,13 @@ __global__ __launch_bounds__(SEL_THREADS) void k_select(const SelectArgs A)
                     __builtin_amdgcn_s_sleep(4);
                 }
                 if (v == 0) atomicAdd(&A.stats->internal_errors, 1ull);   // gave up waiting
-                reader_done(&st->seen[0], 2u * A.tdesc[sd.j].nseg, mine, &st->verdict);
-                for (uint32_t i = 0; i < mine; ++i) P.vbuf[tid + i] = v;
+                reader_done(&st->seen[0], 2u * A.tdesc[sd.j].nseg, 1u, &st->verdict);
+                P.vbuf[tid] = v;
             }
         }
         __syncthreads();
-        for (uint32_t i = 0; i < cnt; ++i)
-            if ((P.vbuf[i] & 0xFFu) == SEG_PENDING) recollect_part<OP>(A, role, first + i, P, llist);
+        for (uint32_t i = 0; i < A.bgroup; ++i)
+            if ((P.vbuf[i] & 0xFFu) == SEG_PENDING) recollect_part<OP>(A, role, first + i * nb, P, llist);
         return;
     }
     const SegDesc sd = A.grptab[blockIdx.x];      // this workgroup's join group
