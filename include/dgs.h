@@ -105,7 +105,8 @@ typedef struct dgs_stats {
     uint64_t candidates;       /* candidates collected by streaming passes */
     uint64_t internal_errors;  /* must stay 0 */
     uint64_t segmented_tensors; /* tensors resolved through the chain kernels */
-    uint64_t repaired_tensors;  /* tensors resolved after a second collection with a fresh threshold */
+    uint64_t repaired_tensors;  /* tensors whose prediction failed and that were resolved inside the call with
+                                   a fresh threshold: lists trimmed in place, or collected a second time */
 } dgs_stats;
 
 /*

@@ -120,10 +120,11 @@ void launch_pick(const TensorDesc *tdesc, const PlanEntry *plan, uint32_t *ghist
 //             ordered list.  The workgroup that arrives last for a tensor (the only one, for a
 //             tensor of one part) gathers the parts' lists and SELECTS: exact k-th key, ordered
 //             emission, state fix-up, next hint.  A tensor planned for the chain kernels only
-//             gets its key window resolved here.  If the prediction failed (fewer candidates
-//             than k, an overflowed tile, a list beyond one workgroup's reach) the tensor is
-//             left pending: a tensor of one part is collected again on the spot, for the others
-//             the verdict releases the waiting roles.
+//             gets its key window resolved here.  Lists that are complete but beyond one
+//             workgroup's reach are trimmed on the way (threshold from their own histogram).
+//             If the prediction failed otherwise (fewer candidates than k, an overflowed tile)
+//             the tensor is left pending: a tensor of one part is collected again on the spot,
+//             for the others the verdict releases the waiting roles.
 //   RE-HISTOGRAM  every part counts the keys of its own elements; the last one derives a fresh
 //             threshold and publishes it.
 //   RE-COLLECTION every part compacts its elements at or above that threshold straight from
@@ -778,6 +779,86 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
                         multi ? (win_join != 0xFFFFFFFFu) : win_counted, exact_mode, P, llist, glist);
         if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
         status = SEG_DONE;
+    }
+    if (status == 0 && multi && !pe.seg && !ovf && have_pbase && c >= pe.k && c > list_max) {
+        // TRIM.  Every candidate is in the lists, there are only too many of them for one
+        // workgroup (the threshold has fallen behind a scale that grew).  The lists' own key
+        // histogram gives the threshold that a fresh collection would use, and the lists are
+        // filtered against it while they are gathered: no second pass over the tensor.
+        uint32_t *lh = (uint32_t *)llist;        // (free until the gathered list is written)
+        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS) lh[b] = 0;
+        __syncthreads();
+        constexpr uint32_t GU = 8;      // entries per thread in flight
+        for (uint32_t s = 0; s < nunits; ++s) {
+            const uint2 *ul = A.ord + P.pofs[s];
+            const uint32_t cnt = P.pbase[s + 1] - P.pbase[s];
+            for (uint32_t e0 = 0; e0 < cnt; e0 += GU * SEL_THREADS) {
+                uint32_t key[GU];
+#pragma unroll
+                for (uint32_t u = 0; u < GU; ++u) {
+                    const uint32_t e = e0 + u * SEL_THREADS + tid;
+                    key[u] = (e < cnt) ? (ld_dev(&ul[e]).y & 0x7FFFFFFFu) : 0u;
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < GU; ++u)
+                    if (key[u] != 0) atomicAdd(&lh[key[u] >> HSHIFT], 1u);
+            }
+        }
+        __syncthreads();
+        uint32_t tau_new = 0, tprev_new = 0;
+        pick_from_hist<SEL_WAVES>(lh, pe, P.S.rowsum, P.S.res, tau_new, tprev_new);
+        if (tid == 0) P.bc = max(tau_new, tau_cur);       // (nothing below tau_cur is in the lists)
+        __syncthreads();
+        tau_new = P.bc;
+        uint32_t reach = 0;      // entries at or above the new threshold: whole buckets, by construction
+        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS)
+            if (b >= (tau_new >> HSHIFT)) reach += lh[b];
+        const uint32_t c2 = block_sum(reach, P.S.wsum, SEL_WAVES);
+        __syncthreads();
+        if (c2 >= pe.k && c2 <= list_max) {
+            early = true;
+            if (verdict && tid == 0) st_dev(verdict, 0x100u | (uint32_t)SEG_DONE);
+            // Gathered in list order, GU consecutive entries per thread.  An entry never moves to
+            // a later position, and every turn has read its entries before it writes any, so the
+            // tail that spills into the first unit's global list lands on entries already read.
+            const SrcParts src{A.ord, P.pbase, P.pofs, nunits};
+            uint32_t run = 0;
+            for (uint32_t q0 = 0; q0 < c; q0 += GU * SEL_THREADS) {
+                uint2 e[GU];
+                uint32_t keep = 0;
+#pragma unroll
+                for (uint32_t u = 0; u < GU; ++u) {
+                    const uint32_t q = q0 + tid * GU + u;
+                    e[u] = (q < c) ? src.get(q) : make_uint2(0, 0);
+                }
+#pragma unroll
+                for (uint32_t u = 0; u < GU; ++u) {
+                    const uint32_t q = q0 + tid * GU + u;
+                    if (q < c && (e[u].y & 0x7FFFFFFFu) >= tau_new) keep |= 1u << u;
+                }
+                uint32_t tot;
+                uint32_t pos = run + block_excl_scan<SEL_WAVES>((uint32_t)__popcll((unsigned long long)keep), P.S.wsum, tot);
+#pragma unroll
+                for (uint32_t u = 0; u < GU; ++u) {
+                    if ((keep >> u) & 1u) {
+                        if (pos < c2) put_entry(llist, glist, pos, e[u]);
+                        ++pos;
+                    }
+                }
+                run += tot;
+            }
+            wait_mem();
+            __syncthreads();
+            if (tid == 0) {
+                if (run != c2) atomicAdd(&A.stats->internal_errors, 1ull);      // the two passes disagree
+                atomicAdd(&A.stats->candidates, (unsigned long long)c2);
+                if (round == 0) atomicAdd(&A.stats->repaired_tensors, 1ull);
+            }
+            // (smallest key unknown: the threshold is a lower bound of it, and the window is
+            // counted from the list)
+            list_select<OP>(A, td, pe, j, c2, tau_new, tau_new, hint2_cur, 0xFFFFFFFFu, false, true, P, llist, glist);
+            status = SEG_DONE;
+        }
     }
     if (status == 0) status = (round == 0 && A.repair) ? (uint32_t)SEG_PENDING : (uint32_t)SEG_FALLBACK;
     if (status == SEG_FALLBACK) {

@@ -398,6 +398,17 @@ int main(int argc, char **argv)
     worker_server("ragged, predicted", ragged, 0.004, 0.004, 0.5f, 0.9f, false, steady, 0, def, 1);
     worker_server("scale jumps, residual mode (re-collection)", two, 0.002, 0.004, 1.0f, 0.0f, true, jumps, 0, def, 2);
     worker_server("scale jumps, chain for every large tensor", two, 0.002, 0.002, 1.0f, 0.0f, true, jumps, 0, always, 3);
+    {
+        // a scale that grows three- and fourfold: every candidate is collected, but the lists of
+        // the large tensors outgrow one workgroup and are trimmed against their own histogram
+        // inside the launch -- with the re-collecting roles switched off, where such a tensor
+        // would otherwise fall back to the single-workgroup selection
+        const std::vector<float> grows = {1, 1, 1, 3, 1, 1, 4, 4};
+        const dgs_stats st = worker_server("scale grows, lists trimmed (no re-collecting roles)", {300000, 64, 150000}, 0.002,
+                                           0.002, 1.0f, 0.9f, false, grows, 0, norepair, 33);
+        CHECK(st.repaired_tensors >= 1 && st.fallback_tensors == 0);
+        if (!quick) worker_server("scale grows, lists trimmed", {300000, 64, 150000}, 0.002, 0.002, 1.0f, 0.0f, true, grows, 0, def, 32);
+    }
     if (!quick) {
         worker_server("ragged, exact path", ragged, 0.01, 0.002, 0.5f, 0.9f, false, {1, 1}, 0, exact, 4);
         Opts sampled;

@@ -100,7 +100,7 @@ def assert_state_match(got: np.ndarray, want: np.ndarray, what=""):
 
 
 def run_worker_parity(oracle, off, grads, lr, m, rho, *, force_exact=False, residual=False,
-                      misalign=0, margin=None, init_state=None, seg_mode=None):
+                      misalign=0, margin=None, init_state=None, seg_mode=None, repair_round=None):
     """Several steps of dgs_worker_step vs the oracle; returns the GPU context stats."""
     from paper_1910_10929_amd import dgs
     ctx = dgs.Context(off, W=0)
@@ -110,6 +110,8 @@ def run_worker_parity(oracle, off, grads, lr, m, rho, *, force_exact=False, resi
         ctx.set_option(dgs.OPT_MARGIN_PCT, margin)
     if seg_mode is not None:
         ctx.set_option(dgs.OPT_SEGMENTED, seg_mode)
+    if repair_round is not None:
+        ctx.set_option(dgs.OPT_REPAIR_ROUND, repair_round)
     w = Worker(ctx, density_max=rho, misalign=misalign)
     n = int(off[-1])
     s_ref = np.zeros(n, np.float32) if init_state is None else init_state.copy()

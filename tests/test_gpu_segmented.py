@@ -204,6 +204,24 @@ def test_collapsed_scale_is_recollected_by_many_workgroups(oracle):
     assert st.repaired_tensors >= 1 and st.fallback_tensors == 0 and st.segmented_tensors == 0
 
 
+@pytest.mark.parametrize("repair_round", [1, 0], ids=["roles", "no-roles"])
+def test_overlong_complete_lists_are_trimmed_inside_the_launch(oracle, repair_round):
+    """A 6M-element tensor (two join groups) whose scale triples: the hinted threshold lets some
+    8 % of the elements through -- every candidate is collected, no tile overflows, but the lists
+    are far beyond what one workgroup selects from.  The workgroup that gathers them takes the
+    fresh threshold from the lists' own histogram and filters them on the way, without another
+    pass over the tensor.  With the re-collecting roles switched off nothing else could repair
+    the tensor except the slow single-workgroup selection, which must stay unused."""
+    off = synth.offsets_from_sizes([6_000_011, 300_000, 64])
+    n = int(off[-1])
+    rng = np.random.default_rng(61)
+    grads = [synth.gaussian(n, rng) * np.float32(f) for f in (1, 1, 1, 3, 3)]
+    st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.001, residual=True, repair_round=repair_round)
+    assert st.repaired_tensors >= 2 and st.segmented_tensors == 0
+    if repair_round == 0:
+        assert st.fallback_tensors == 0
+
+
 def test_a_wait_that_gives_up_is_counted_and_every_kernel_ends(oracle):
     """The workgroups that stand by to collect a tensor again poll for the verdict of its join
     a bounded number of times.  With the bound set to one poll they give up before the verdict
