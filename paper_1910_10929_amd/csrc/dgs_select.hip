@@ -656,6 +656,79 @@ struct SrcParts {
     __device__ __forceinline__ uint32_t index(uint32_t p) const { return get(p).x; }
 };
 
+// TRIM: a candidate list that is complete but too long for one workgroup is cut down to what a
+// fresh collection would have found.  The list's own key histogram (bits [30:20]) gives the
+// threshold -- the lower edge of the bucket that holds rank pe.k2 -- and the entries at or above
+// it are moved up in list order into llist / glist.  No second pass over the tensor.  Returns the
+// new count, or 0 (nothing moved) if that is still beyond list_max; tau is raised to the new
+// threshold.  A success is published to `verdict` before the entries are moved.
+//   In place: an entry never moves to a later position, and every turn has read its entries
+//   before it writes any, so both an LDS list and the tail that spills into the first unit's
+//   global list are only ever written where they have been read.
+template <class Src>
+__device__ __forceinline__ uint32_t trim_list(const SelectArgs &A, const Src &src, uint32_t c, uint32_t list_max,
+                                              const PlanEntry &pe, uint32_t *verdict, PartShared &P, uint2 *llist,
+                                              uint2 *glist, uint32_t &tau)
+{
+    const uint32_t tid = threadIdx.x;
+    constexpr uint32_t GU = 8;      // entries per thread in flight
+    for (uint32_t b = tid; b < 2048; b += SEL_THREADS) P.S.h[b] = 0;
+    __syncthreads();
+    for (uint32_t q0 = 0; q0 < c; q0 += GU * SEL_THREADS) {
+        uint32_t key[GU];
+#pragma unroll
+        for (uint32_t u = 0; u < GU; ++u) {
+            const uint32_t q = q0 + u * SEL_THREADS + tid;
+            key[u] = (q < c) ? (src.bits(q) & 0x7FFFFFFFu) : 0u;
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < GU; ++u)
+            if (key[u] != 0) atomicAdd(&P.S.h[key[u] >> 20], 1u);
+    }
+    find_ranks<2048, SEL_WAVES>(P.S.h, pe.k2, pe.k, 0u, P.S.rowsum, P.S.res);
+    const int b2 = P.S.res[0];
+    // (rank k2 beyond the nonzero keys of the list: nothing to cut, the count below says so)
+    const uint32_t t = max((b2 > 0) ? ((uint32_t)b2 << 20) : 1u, tau);    // nothing below tau is in the list
+    uint32_t reach = 0;      // entries at or above t: whole buckets, by construction
+    for (uint32_t b = tid; b < 2048; b += SEL_THREADS)
+        if (b >= (t >> 20)) reach += P.S.h[b];
+    __syncthreads();
+    const uint32_t c2 = block_sum(reach, P.S.wsum, SEL_WAVES);
+    __syncthreads();
+    if (c2 < pe.k || c2 > list_max) return 0u;
+    if (verdict && tid == 0) st_dev(verdict, 0x100u | (uint32_t)SEG_DONE);
+    uint32_t run = 0;
+    for (uint32_t q0 = 0; q0 < c; q0 += GU * SEL_THREADS) {      // GU consecutive entries per thread
+        uint2 e[GU];
+        uint32_t keep = 0;
+#pragma unroll
+        for (uint32_t u = 0; u < GU; ++u) {
+            const uint32_t q = q0 + tid * GU + u;
+            e[u] = (q < c) ? src.get(q) : make_uint2(0, 0);
+        }
+#pragma unroll
+        for (uint32_t u = 0; u < GU; ++u) {
+            const uint32_t q = q0 + tid * GU + u;
+            if (q < c && (e[u].y & 0x7FFFFFFFu) >= t) keep |= 1u << u;
+        }
+        uint32_t tot;
+        uint32_t pos = run + block_excl_scan<SEL_WAVES>((uint32_t)__popcll((unsigned long long)keep), P.S.wsum, tot);
+#pragma unroll
+        for (uint32_t u = 0; u < GU; ++u) {
+            if ((keep >> u) & 1u) {
+                if (pos < c2) put_entry(llist, glist, pos, e[u]);
+                ++pos;
+            }
+        }
+        run += tot;
+    }
+    wait_mem();
+    __syncthreads();
+    if (tid == 0 && run != c2) atomicAdd(&A.stats->internal_errors, 1ull);      // the two passes disagree
+    tau = t;
+    return c2;
+}
+
 // What the workgroup that completes a tensor's candidate lists does with them (`round` 0: the
 // streaming pass's candidates, 1: re-collected with a fresh threshold).  Returns the tensor's
 // status: SEG_DONE, SEG_ACTIVE / SEG_ALL (the chain kernels go on), or SEG_PENDING (round 0
@@ -780,77 +853,16 @@ __device__ __forceinline__ uint32_t tensor_select(const SelectArgs &A, const Ten
         if (tid == 0) atomicAdd(&A.stats->candidates, (unsigned long long)c);
         status = SEG_DONE;
     }
-    if (status == 0 && multi && !pe.seg && !ovf && have_pbase && c >= pe.k && c > list_max) {
-        // TRIM.  Every candidate is in the lists, there are only too many of them for one
-        // workgroup (the threshold has fallen behind a scale that grew).  The lists' own key
-        // histogram gives the threshold that a fresh collection would use, and the lists are
-        // filtered against it while they are gathered: no second pass over the tensor.
-        uint32_t *lh = (uint32_t *)llist;        // (free until the gathered list is written)
-        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS) lh[b] = 0;
-        __syncthreads();
-        constexpr uint32_t GU = 8;      // entries per thread in flight
-        for (uint32_t s = 0; s < nunits; ++s) {
-            const uint2 *ul = A.ord + P.pofs[s];
-            const uint32_t cnt = P.pbase[s + 1] - P.pbase[s];
-            for (uint32_t e0 = 0; e0 < cnt; e0 += GU * SEL_THREADS) {
-                uint32_t key[GU];
-#pragma unroll
-                for (uint32_t u = 0; u < GU; ++u) {
-                    const uint32_t e = e0 + u * SEL_THREADS + tid;
-                    key[u] = (e < cnt) ? (ld_dev(&ul[e]).y & 0x7FFFFFFFu) : 0u;
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < GU; ++u)
-                    if (key[u] != 0) atomicAdd(&lh[key[u] >> HSHIFT], 1u);
-            }
-        }
-        __syncthreads();
-        uint32_t tau_new = 0, tprev_new = 0;
-        pick_from_hist<SEL_WAVES>(lh, pe, P.S.rowsum, P.S.res, tau_new, tprev_new);
-        if (tid == 0) P.bc = max(tau_new, tau_cur);       // (nothing below tau_cur is in the lists)
-        __syncthreads();
-        tau_new = P.bc;
-        uint32_t reach = 0;      // entries at or above the new threshold: whole buckets, by construction
-        for (uint32_t b = tid; b < HBINS; b += SEL_THREADS)
-            if (b >= (tau_new >> HSHIFT)) reach += lh[b];
-        const uint32_t c2 = block_sum(reach, P.S.wsum, SEL_WAVES);
-        __syncthreads();
-        if (c2 >= pe.k && c2 <= list_max) {
+    if (status == 0 && !pe.seg && !ovf && (!multi || have_pbase) && c >= pe.k && c > list_max) {
+        // Every candidate is in the lists, there are only too many of them for one workgroup
+        // (the threshold has fallen behind a scale that grew): trimmed on the spot.
+        uint32_t tau_new = tau_cur;
+        const uint32_t c2 = multi ? trim_list(A, SrcParts{A.ord, P.pbase, P.pofs, nunits}, c, list_max, pe, verdict, P,
+                                              llist, glist, tau_new)
+                                  : trim_list(A, SrcSplit{llist, glist}, c, list_max, pe, verdict, P, llist, glist, tau_new);
+        if (c2 != 0) {
             early = true;
-            if (verdict && tid == 0) st_dev(verdict, 0x100u | (uint32_t)SEG_DONE);
-            // Gathered in list order, GU consecutive entries per thread.  An entry never moves to
-            // a later position, and every turn has read its entries before it writes any, so the
-            // tail that spills into the first unit's global list lands on entries already read.
-            const SrcParts src{A.ord, P.pbase, P.pofs, nunits};
-            uint32_t run = 0;
-            for (uint32_t q0 = 0; q0 < c; q0 += GU * SEL_THREADS) {
-                uint2 e[GU];
-                uint32_t keep = 0;
-#pragma unroll
-                for (uint32_t u = 0; u < GU; ++u) {
-                    const uint32_t q = q0 + tid * GU + u;
-                    e[u] = (q < c) ? src.get(q) : make_uint2(0, 0);
-                }
-#pragma unroll
-                for (uint32_t u = 0; u < GU; ++u) {
-                    const uint32_t q = q0 + tid * GU + u;
-                    if (q < c && (e[u].y & 0x7FFFFFFFu) >= tau_new) keep |= 1u << u;
-                }
-                uint32_t tot;
-                uint32_t pos = run + block_excl_scan<SEL_WAVES>((uint32_t)__popcll((unsigned long long)keep), P.S.wsum, tot);
-#pragma unroll
-                for (uint32_t u = 0; u < GU; ++u) {
-                    if ((keep >> u) & 1u) {
-                        if (pos < c2) put_entry(llist, glist, pos, e[u]);
-                        ++pos;
-                    }
-                }
-                run += tot;
-            }
-            wait_mem();
-            __syncthreads();
             if (tid == 0) {
-                if (run != c2) atomicAdd(&A.stats->internal_errors, 1ull);      // the two passes disagree
                 atomicAdd(&A.stats->candidates, (unsigned long long)c2);
                 if (round == 0) atomicAdd(&A.stats->repaired_tensors, 1ull);
             }

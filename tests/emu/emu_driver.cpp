@@ -383,6 +383,13 @@ int main(int argc, char **argv)
         Opts o;
         worker_server("groups of several rounds", {1500017, 64, 2300000}, 0.001, 0.002, 1.0f, 0.9f, false, {1, 1, 1, 30, 30},
                       0, o, 29);
+        // one workgroup's join that ends with more candidates than it can select from, all of
+        // them collected (LDS list plus global tail): trimmed in place
+        Opts nr;
+        nr.repair = 0;
+        const dgs_stats st = worker_server("scale triples, one group's list trimmed", {1200000, 64}, 0.001, 0.001, 1.0f, 0.0f,
+                                           true, {1, 1, 1, 3, 3}, 0, nr, 34);
+        CHECK(st.repaired_tensors >= 1 && st.fallback_tensors == 0);
         return 0;
     }
     const std::vector<uint64_t> ragged = {1, 7, 64, 1000, 8192, 8193, 9408, 3, 100003, 20000, 70001, 17, 65537, 12345};

@@ -186,6 +186,10 @@ def test_recollection_after_a_join_that_outgrew_the_lds_list(oracle):
     scales = synth.tensor_scales(len(sizes), 55)
     rng = np.random.default_rng(56)
     grads = [synth.gaussian_grads(off, scales, rng) for _ in range(3)]
+    # a stretch where every element is a candidate: tiles beyond their 256 slots, so the overlong
+    # lists cannot be trimmed in place (they are not complete) and the tensors are collected again
+    grads[1][1_000_000:1_003_000] *= np.float32(50.0)
+    grads[1][5_000_000:5_003_000] *= np.float32(50.0)
     st = run_worker_parity(oracle, off, grads, np.float32(1.0), np.float32(0.9), 1e-3)
     assert st.repaired_tensors >= 2 and st.fallback_tensors == 0 and st.internal_errors == 0
 
@@ -206,18 +210,20 @@ def test_collapsed_scale_is_recollected_by_many_workgroups(oracle):
 
 @pytest.mark.parametrize("repair_round", [1, 0], ids=["roles", "no-roles"])
 def test_overlong_complete_lists_are_trimmed_inside_the_launch(oracle, repair_round):
-    """A 6M-element tensor (two join groups) whose scale triples: the hinted threshold lets some
-    8 % of the elements through -- every candidate is collected, no tile overflows, but the lists
-    are far beyond what one workgroup selects from.  The workgroup that gathers them takes the
-    fresh threshold from the lists' own histogram and filters them on the way, without another
-    pass over the tensor.  With the re-collecting roles switched off nothing else could repair
-    the tensor except the slow single-workgroup selection, which must stay unused."""
-    off = synth.offsets_from_sizes([6_000_011, 300_000, 64])
+    """A 6M-element tensor (two join groups) and a 3M-element one (joined by one workgroup, its
+    list spilling from LDS into global scratch) whose scale triples: the hinted threshold lets
+    some 8 % of the elements through -- every candidate is collected, no tile overflows, but the
+    lists are far beyond what one workgroup selects from.  The workgroup that holds them takes
+    the fresh threshold from the lists' own histogram and moves the entries that reach it up in
+    place, without another pass over the tensor.  With the re-collecting roles switched off
+    nothing else could repair the tensors except the slow single-workgroup selection, which
+    must stay unused."""
+    off = synth.offsets_from_sizes([6_000_011, 3_000_000, 300_000, 64])
     n = int(off[-1])
     rng = np.random.default_rng(61)
     grads = [synth.gaussian(n, rng) * np.float32(f) for f in (1, 1, 1, 3, 3)]
     st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.001, residual=True, repair_round=repair_round)
-    assert st.repaired_tensors >= 2 and st.segmented_tensors == 0
+    assert st.repaired_tensors >= 4 and st.segmented_tensors == 0
     if repair_round == 0:
         assert st.fallback_tensors == 0
 

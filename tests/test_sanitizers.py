@@ -75,7 +75,9 @@ def test_kernels_on_the_cpu_under_asan_ubsan(tmp_path):
     selection launch with joins by several workgroups and re-collection after failed
     predictions, the chain kernels, the entry point that allocates nothing, wire form, apply,
     pull_all.  (`emu_run` without arguments runs the long list of scenarios, `emu_run soak
-    <seed> <count>` randomised ones; this test runs the short list.)"""
+    <seed> <count>` randomised ones, `emu_run rounds` -- built with seg_tiles=256 and
+    group_tiles=4096, the library's own sizes -- joins of several rounds per workgroup and the
+    trimming of one workgroup's overlong list; this test runs the short list.)"""
     exe = build_emulated_kernels(str(tmp_path))
     env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0")
     r = subprocess.run([exe, "quick"], capture_output=True, text=True, env=env, timeout=1500)
