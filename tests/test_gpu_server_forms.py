@@ -155,3 +155,50 @@ def test_printed_form_argument_errors():
     torch.cuda.synchronize()
     assert not model.any().item()
     ctx.close()
+
+
+@pytest.mark.parametrize("repair_round", [1, 0], ids=["roles", "no-roles"])
+@pytest.mark.parametrize("form", ["sent", "diff"])
+def test_pulls_trim_complete_but_overlong_lists(oracle, form, repair_round):
+    """Dense pushes whose scale grows between pulls, in both server forms: the threshold hinted by
+    the previous pull lets several per cent of a 6M-element tensor (two join groups) and of a
+    3M-element one (joined by one workgroup) through.  Every candidate is collected, so the
+    selecting workgroups cut the lists down against their own histogram -- also with the
+    re-collecting roles switched off, where the only other way out would be the slow
+    single-workgroup selection."""
+    from harness import Server
+    off = synth.offsets_from_sizes([6_000_011, 3_000_000, 64])
+    n = int(off[-1])
+    rho = 1e-3
+    rng = np.random.default_rng(71)
+    ctx = dgs.Context(off, W=1)
+    ctx.set_option(dgs.OPT_REPAIR_ROUND, repair_round)
+    everything = np.arange(n, dtype=np.uint32)
+    model_ref = np.zeros(n, np.float32)
+    if form == "sent":
+        srv = SentServer(ctx, model_ref, density_max=rho)
+        sent_ref = np.zeros((1, n), np.float32)
+    else:
+        srv = Server(ctx, model_ref, density_max=rho)
+        diff_ref = np.zeros((1, n), np.float32)
+    for e, f in enumerate((1, 1, 3)):
+        val = synth.gaussian(n, rng) * np.float32(f)
+        if form == "sent":
+            oracle.server_push_model(model_ref, everything, val)
+            srv.push(everything, val)
+            wi, wv = oracle.server_pull_sent(model_ref, sent_ref, 0, off, rho)
+        else:
+            oracle.server_push(model_ref, diff_ref, everything, val)
+            srv.push(0, everything, val)
+            wi, wv = oracle.server_pull(diff_ref, 0, off, rho)
+        gi, gv = srv.pull(0, rho)
+        assert_pairs_match(gi, gv, wi, wv, f"{form} pull {e}")
+    if form == "sent":
+        assert_state_match(srv.sent.cpu().numpy().ravel(), sent_ref.ravel(), "sent")
+    else:
+        assert_state_match(srv.diff.cpu().numpy().ravel(), diff_ref.ravel(), "difference row")
+    st = ctx.stats()
+    assert st.internal_errors == 0 and st.repaired_tensors >= 2
+    if repair_round == 0:
+        assert st.fallback_tensors == 0
+    ctx.close()
