@@ -209,21 +209,28 @@ def test_collapsed_scale_is_recollected_by_many_workgroups(oracle):
 
 
 @pytest.mark.parametrize("repair_round", [1, 0], ids=["roles", "no-roles"])
-def test_overlong_complete_lists_are_trimmed_inside_the_launch(oracle, repair_round):
-    """A 6M-element tensor (two join groups) and a 3M-element one (joined by one workgroup, its
-    list spilling from LDS into global scratch) whose scale triples: the hinted threshold lets
-    some 8 % of the elements through -- every candidate is collected, no tile overflows, but the
-    lists are far beyond what one workgroup selects from.  The workgroup that holds them takes
-    the fresh threshold from the lists' own histogram and moves the entries that reach it up in
-    place, without another pass over the tensor.  With the re-collecting roles switched off
-    nothing else could repair the tensors except the slow single-workgroup selection, which
-    must stay unused."""
-    off = synth.offsets_from_sizes([6_000_011, 3_000_000, 300_000, 64])
+@pytest.mark.parametrize("sizes,rho,trimmed", [
+    ([6_000_011, 3_000_000, 300_000, 64], 1e-3, 4),
+    ([6_000_011, 64], 1.5e-3, 2),        # what remains of the gathered lists is longer than the LDS list
+    ([4_000_000, 64], 2.5e-3, 2),        # the same for one workgroup's own list
+], ids=["both-kinds", "gathered-spills", "own-list-spills"])
+def test_overlong_complete_lists_are_trimmed_inside_the_launch(oracle, sizes, rho, trimmed, repair_round):
+    """A 6M-element tensor (two join groups) and a 3M- or 4M-element one (joined by one
+    workgroup, its list spilling from LDS into global scratch) whose scale triples: the hinted
+    threshold lets some 8 % of the elements through -- every candidate is collected, no tile
+    overflows, but the lists are far beyond what one workgroup selects from.  The workgroup that
+    holds them takes the fresh threshold from the lists' own histogram and moves the entries
+    that reach it up in place, without another pass over the tensor; at the higher densities
+    the trimmed list itself (about 2 k_j entries) is longer than the LDS list and ends in the
+    global scratch it is being read from.  With the re-collecting roles switched off nothing
+    else could repair the tensors except the slow single-workgroup selection, which must stay
+    unused."""
+    off = synth.offsets_from_sizes(sizes)
     n = int(off[-1])
     rng = np.random.default_rng(61)
     grads = [synth.gaussian(n, rng) * np.float32(f) for f in (1, 1, 1, 3, 3)]
-    st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), 0.001, residual=True, repair_round=repair_round)
-    assert st.repaired_tensors >= 4 and st.segmented_tensors == 0
+    st = run_worker_parity(oracle, off, grads, 1.0, np.float32(0.0), rho, residual=True, repair_round=repair_round)
+    assert st.repaired_tensors >= trimmed and st.segmented_tensors == 0
     if repair_round == 0:
         assert st.fallback_tensors == 0
 
