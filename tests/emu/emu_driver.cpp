@@ -390,6 +390,11 @@ int main(int argc, char **argv)
         const dgs_stats st = worker_server("scale triples, one group's list trimmed", {1200000, 64}, 0.001, 0.001, 1.0f, 0.0f,
                                            true, {1, 1, 1, 3, 3}, 0, nr, 34);
         CHECK(st.repaired_tensors >= 1 && st.fallback_tensors == 0);
+        // the same where what remains (about 2 k entries) is itself longer than the LDS list and
+        // ends in the global scratch it is read from
+        const dgs_stats st2 = worker_server("one group's list trimmed into LDS and scratch", {4000000, 64}, 0.0025, 0.0025,
+                                            1.0f, 0.0f, true, {1, 1, 2}, 0, nr, 35);
+        CHECK(st2.repaired_tensors >= 1 && st2.fallback_tensors == 0);
         return 0;
     }
     const std::vector<uint64_t> ragged = {1, 7, 64, 1000, 8192, 8193, 9408, 3, 100003, 20000, 70001, 17, 65537, 12345};
