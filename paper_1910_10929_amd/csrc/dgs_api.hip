@@ -13,6 +13,10 @@
 #include "../../include/dgs.h"
 #include "dgs_device.h"
 
+#ifndef DGS_SAMPLE_WGS_PER_CU
+#define DGS_SAMPLE_WGS_PER_CU 4u      // workgroups of the sampling pass per compute unit
+#endif
+
 using namespace dgs;
 
 namespace {
@@ -414,9 +418,11 @@ int run_selection(dgs_ctx *c, int op_stream, int op_select, const float *grad, f
         sb.tile_list = c->qlist;
         sb.nlist = c->nqlist;
         sb.nquads = (c->nqlist + WAVES_PER_BLOCK - 1) / WAVES_PER_BLOCK;
-        // about two workgroups per compute unit: every workgroup ends with a flush of its LDS
-        // histogram into the tensors' counters, and those atomics meet on a few hundred addresses
-        sb.quads_per_block = std::max<uint32_t>(1u, (sb.nquads + (uint32_t)c->cus * 2u - 1u) / ((uint32_t)c->cus * 2u));
+        // a few workgroups per compute unit: enough loads in flight, but every workgroup ends with a
+        // flush of its LDS histogram into the tensors' counters, and those atomics meet on a few
+        // hundred addresses (at 1e9 parameters: 119 us with two per unit, 90 with four, 101 with eight)
+        const uint32_t wgs = (uint32_t)c->cus * DGS_SAMPLE_WGS_PER_CU;
+        sb.quads_per_block = std::max<uint32_t>(1u, (sb.nquads + wgs - 1u) / wgs);
         launch_stream(op_stream, MODE_SAMPLE, vec, sb, (sb.nquads + sb.quads_per_block - 1u) / sb.quads_per_block,
                       c->stream, ps.ev0, ps.ev1);
         ps.launched();
