@@ -50,7 +50,7 @@ LR, MOMENTUM = 1.0, 0.9
 PROFILED_TRAFFIC = {
     "c5": {"bytes": 12068.64e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
     "c2": {"bytes": 308.62e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
-    "c3": {"bytes": 207.71e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
+    "c3": {"bytes": 207.70e6, "profile": "profiles/k_stream_k_select_fabric_traffic_c5_c2_c3.txt"},
 }
 
 
