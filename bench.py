@@ -177,11 +177,13 @@ class WorkerServer:
         self.ctx.close()
 
 
-def timed(torch, step, t, warmup, steps):
+def timed(torch, step, t, warmup, steps, after_warmup=None):
     for _ in range(warmup):
         step(t)
         t += 1
     torch.cuda.synchronize()
+    if after_warmup is not None:
+        after_warmup()
     t0 = time.perf_counter()
     for _ in range(steps):
         step(t)
@@ -252,7 +254,9 @@ def run_worker_server(torch, dgs, name, wl, steps, warmup, dev, *, cpu=True, exa
     g_dev = [torch.from_numpy(g).to(dev) for g in wl["grads"]]
     ws = WorkerServer(torch, dgs, wl, g_dev, dev)
     K, W = ws.K, 1
-    dt, t = timed(torch, ws.step, 0, warmup, steps)
+    snap = {}
+    dt, t = timed(torch, ws.step, 0, warmup, steps, after_warmup=lambda: snap.update(w=ws.ctx.stats()))
+    snap["t"] = ws.ctx.stats()
     # per-kernel durations: HIP events attached to each kernel dispatch on the context's stream
     ws.ctx.set_option(dgs.OPT_PROFILE, 1)
     for _ in range(min(max(steps, 20), 200)):
@@ -321,6 +325,11 @@ def run_worker_server(torch, dgs, name, wl, steps, warmup, dev, *, cpu=True, exa
     out["stats"] = {"exact_calls": st.exact_calls, "fallback_tensors": st.fallback_tensors,
                     "segmented_tensors": st.segmented_tensors, "repaired_tensors": st.repaired_tensors,
                     "internal_errors": st.internal_errors}
+    # the timed steps alone (the counters above include the warm-up, whose first calls have no
+    # usable prediction yet)
+    out["stats_timed_steps"] = {k: getattr(snap["t"], k) - getattr(snap["w"], k)
+                                for k in ("exact_calls", "fallback_tensors", "segmented_tensors",
+                                          "repaired_tensors", "internal_errors")}
     assert st.internal_errors == 0, "libdgs reported internal errors"
     ws.close()
     del ws
