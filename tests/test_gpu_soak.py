@@ -1,6 +1,6 @@
 """Randomised GPU parity: seeded layouts (tensors from 1 to 4.6M elements), densities that change
 on the way, momentum / residual mode, tuning options picked at random (selection mode, candidate
-margin, launch shape, repair round), and gradients whose scale jumps, collapses, vanishes or
+margin, launch shape, repair round), and gradients whose scale jumps, grows a little, collapses, vanishes or
 carries a large tie class -- so predictions fail and every fallback runs.  Worker steps, pushes
 and a random number of pulls per step, each compared with the oracle (indices bit-exact, values
 1e-6 relative / 1e-7 absolute, state bits equal).  DGS_SOAK_SEEDS=a:b widens the seed range."""
@@ -60,6 +60,7 @@ def run(oracle, seed):
         elif ev == 2: g[: n // 2] = 0.0
         elif ev == 3: g[:] = np.float32(0.0)
         elif ev == 4: g[rng.integers(0, n, size=max(n // 50, 1))] = np.float32(7.0)      # a tie class
+        elif ev == 5: g *= np.float32(rng.choice([2.0, 3.0, 5.0]))      # growth: complete but overlong lists
         wi, wv = oracle.worker_step(g, s_ref, off, lr, m, rho)
         gi, gv = w.step(g, lr, m, rho, residual_mode=(m == 0.0 and seed % 3 == 0))
         assert_pairs_match(gi, gv, wi, wv, f"seed {seed} step {t}")
